@@ -1,0 +1,391 @@
+"""Pins of the fp64 CPU oracle against things other than itself: a worked
+example computed by hand, brute force in pure Python, delta-kernel and
+linearity invariants, closed forms, reductions to library routines, and an
+independent float64 PyTorch evaluation.  All CPU only."""
+
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from paper_2109_01611_amd import workloads
+
+RNG = np.random.default_rng(20210901)
+
+
+def _read_golden(path):
+    blocks, name = {}, None
+    with open(path) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line[0].isalpha():
+                name = line
+                blocks[name] = []
+            else:
+                blocks[name].append([float(v) for v in line.split()])
+    return {k: np.array(v) for k, v in blocks.items()}
+
+
+# ---------------------------------------------------------------- worked example
+
+def test_worked_3x3_example(golden_dir):
+    g = _read_golden(os.path.join(golden_dir, "conv3x3_worked_example.txt"))
+    x = g["x"].reshape(1, 1, 3, 3)
+    w = g["w"].reshape(1, 1, 3, 3)
+    b = g["b"].reshape(1)
+    y = oracle.conv2d(x, w, b, stride=1, pad=1)
+    assert np.array_equal(y[0, 0], g["y_stride1_pad1"])
+    assert not np.array_equal(y[0, 0], g["y_flipped_wrong"])
+    assert np.array_equal(oracle.conv2d(x, w, b, 1, 1, relu=True)[0, 0], g["y_stride1_pad1_relu"])
+    assert np.array_equal(oracle.conv2d(x, w, b, 2, 1)[0, 0], g["y_stride2_pad1"])
+
+
+# ---------------------------------------------------------------- brute force
+
+def _brute_conv(x, w, b, stride, pad, relu, residual):
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    y = [[[[0.0] * Q for _ in range(P)] for _ in range(K)] for _ in range(N)]
+    for n in range(N):
+        for k in range(K):
+            for p in range(P):
+                for q in range(Q):
+                    acc = float(b[k])
+                    for c in range(C):
+                        for r in range(R):
+                            for s in range(S):
+                                h = p * stride + r - pad
+                                v = q * stride + s - pad
+                                if 0 <= h < H and 0 <= v < W:
+                                    acc += float(x[n, c, h, v]) * float(w[k, c, r, s])
+                    if residual is not None:
+                        acc += float(residual[n, k, p, q])
+                    if relu:
+                        acc = max(acc, 0.0)
+                    y[n][k][p][q] = acc
+    return np.array(y)
+
+
+@pytest.mark.parametrize("R,stride,pad", [(1, 1, 0), (1, 2, 0), (3, 1, 0), (3, 1, 1), (3, 2, 1),
+                                          (5, 1, 2), (5, 2, 0), (3, 2, 2), (5, 1, 1)])
+def test_conv_brute_force(R, stride, pad):
+    N, C, K, H, W = 2, 3, 2, 6, 5
+    x = RNG.standard_normal((N, C, H, W))
+    w = RNG.standard_normal((K, C, R, R))
+    b = RNG.standard_normal(K)
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    res = RNG.standard_normal((N, K, P, Q))
+    for relu, use_res in itertools.product((False, True), (False, True)):
+        got = oracle.conv2d(x, w, b, stride, pad, relu, res if use_res else None)
+        want = _brute_conv(x, w, b, stride, pad, relu, res if use_res else None)
+        assert got.shape == want.shape
+        assert np.max(np.abs(got - want)) < 1e-12
+
+
+def test_conv_brute_force_nonsquare_kernel():
+    x = RNG.standard_normal((1, 2, 5, 7))
+    w = RNG.standard_normal((3, 2, 3, 3))
+    w[:, :, :, 2] = 0.0  # effectively a 3x2 kernel, exercises r/s not being swapped
+    b = np.zeros(3)
+    assert np.max(np.abs(oracle.conv2d(x, w, b, 1, 1) - _brute_conv(x, w, b, 1, 1, False, None))) < 1e-12
+
+
+def test_pool_and_fc_brute_force():
+    x = RNG.standard_normal((2, 3, 7, 6))
+    for k, stride, pad in [(2, 2, 0), (3, 2, 1), (3, 1, 1), (3, 3, 0), (2, 1, 1)]:
+        P = (7 + 2 * pad - k) // stride + 1
+        Q = (6 + 2 * pad - k) // stride + 1
+        mx = np.empty((2, 3, P, Q))
+        av = np.empty((2, 3, P, Q))
+        for n, c, p, q in itertools.product(range(2), range(3), range(P), range(Q)):
+            vals = [x[n, c, p * stride + r - pad, q * stride + s - pad]
+                    for r in range(k) for s in range(k)
+                    if 0 <= p * stride + r - pad < 7 and 0 <= q * stride + s - pad < 6]
+            mx[n, c, p, q] = max(vals)
+            av[n, c, p, q] = sum(vals) / (k * k)
+        assert np.array_equal(oracle.maxpool(x, k, stride, pad), mx)
+        assert np.max(np.abs(oracle.avgpool(x, k, stride, pad) - av)) < 1e-14
+    xf = RNG.standard_normal((3, 5))
+    wf = RNG.standard_normal((4, 5))
+    bf = RNG.standard_normal(4)
+    want = np.array([[bf[o] + sum(xf[n, i] * wf[o, i] for i in range(5)) for o in range(4)]
+                     for n in range(3)])
+    assert np.max(np.abs(oracle.fc(xf, wf, bf) - want)) < 1e-13
+    assert np.max(np.abs(oracle.fc(xf, wf, bf, relu=True) - np.maximum(want, 0))) < 1e-13
+
+
+# ---------------------------------------------------------------- delta kernels
+
+def test_identity_kernel_returns_input_plus_bias():
+    C, R = 3, 5
+    x = RNG.standard_normal((2, C, 6, 7))
+    w = np.zeros((C, C, R, R))
+    for c in range(C):
+        w[c, c, R // 2, R // 2] = 1.0
+    b = np.array([0.5, -1.0, 2.0])
+    y = oracle.conv2d(x, w, b, 1, R // 2)
+    assert np.array_equal(y, x + b[None, :, None, None])
+
+
+@pytest.mark.parametrize("r0,s0", [(0, 0), (0, 2), (2, 1), (1, 0)])
+def test_shifted_delta_shifts_the_image(r0, s0):
+    x = RNG.standard_normal((1, 1, 5, 6))
+    w = np.zeros((1, 1, 3, 3))
+    w[0, 0, r0, s0] = 1.0
+    y = oracle.conv2d(x, w, None, 1, 1)
+    want = np.zeros_like(x)
+    dh, dw = r0 - 1, s0 - 1          # y[p,q] = x[p+dh, q+dw], zero outside
+    for p in range(5):
+        for q in range(6):
+            if 0 <= p + dh < 5 and 0 <= q + dw < 6:
+                want[0, 0, p, q] = x[0, 0, p + dh, q + dw]
+    assert np.array_equal(y, want)
+
+
+def test_1x1_delta_stride2_subsamples():
+    x = RNG.standard_normal((2, 2, 7, 8))
+    w = np.eye(2).reshape(2, 2, 1, 1)
+    assert np.array_equal(oracle.conv2d(x, w, None, 2, 0), x[:, :, ::2, ::2])
+
+
+def test_channel_routing_is_not_transposed():
+    # w[k=1, c=0] = 1 sends input channel 0 to output channel 1 only.
+    x = RNG.standard_normal((1, 2, 4, 4))
+    w = np.zeros((3, 2, 1, 1))
+    w[1, 0, 0, 0] = 1.0
+    y = oracle.conv2d(x, w, None)
+    assert np.array_equal(y[:, 1], x[:, 0])
+    assert not y[:, 0].any() and not y[:, 2].any()
+
+
+# ---------------------------------------------------------------- linearity
+
+def test_linearity_in_input_and_weights():
+    x1, x2 = RNG.standard_normal((2, 2, 3, 6, 6))
+    w1, w2 = RNG.standard_normal((2, 4, 3, 3, 3))
+    b = RNG.standard_normal(4)
+    a, c = 0.75, -2.5
+    f = lambda x, w, bias=None: oracle.conv2d(x, w, bias, 2, 1)
+    assert np.max(np.abs(f(a * x1 + c * x2, w1) - (a * f(x1, w1) + c * f(x2, w1)))) < 1e-12
+    assert np.max(np.abs(f(x1, a * w1 + c * w2) - (a * f(x1, w1) + c * f(x1, w2)))) < 1e-12
+    zero = np.zeros_like(x1)
+    lin = lambda x: f(x, w1, b) - f(zero, w1, b)
+    assert np.max(np.abs(lin(a * x1 + c * x2) - (a * lin(x1) + c * lin(x2)))) < 1e-12
+    # the bias alone is what an all-zero input gives
+    assert np.array_equal(f(zero, w1, b), np.broadcast_to(b[None, :, None, None], f(zero, w1, b).shape))
+
+
+# ---------------------------------------------------------------- closed forms
+
+def test_all_ones_counts_in_bounds_taps():
+    C, R, H, W = 3, 3, 5, 4
+    x = np.ones((1, C, H, W))
+    w = np.ones((2, C, R, R))
+    b = np.array([0.25, -0.5])
+    y0 = oracle.conv2d(x, w, b, 1, 0)
+    assert np.array_equal(y0, np.broadcast_to((C * R * R + b)[None, :, None, None], y0.shape))
+    y1 = oracle.conv2d(x, w, b, 1, 1)
+    for p in range(H):
+        for q in range(W):
+            taps = (min(p + 1, H - 1) - max(p - 1, 0) + 1) * (min(q + 1, W - 1) - max(q - 1, 0) + 1)
+            assert y1[0, 0, p, q] == taps * C + b[0]
+            assert y1[0, 1, p, q] == taps * C + b[1]
+
+
+@pytest.mark.parametrize("n,k,stride,pad,want", [(224, 7, 2, 3, 112), (112, 3, 2, 1, 56), (28, 5, 1, 2, 28),
+                                                 (14, 5, 1, 0, 10), (224, 2, 2, 0, 112), (7, 3, 2, 1, 4),
+                                                 (56, 1, 2, 0, 28), (2, 3, 1, 0, 0)])
+def test_output_size_rule(n, k, stride, pad, want):
+    assert oracle.out_dim(n, k, stride, pad) == want
+
+
+# ---------------------------------------------------------------- reductions to library routines
+
+def test_1x1_conv_is_a_matmul():
+    x = RNG.standard_normal((2, 5, 4, 3))
+    w = RNG.standard_normal((7, 5, 1, 1))
+    b = RNG.standard_normal(7)
+    y = oracle.conv2d(x, w, b)
+    want = (x.transpose(0, 2, 3, 1).reshape(-1, 5) @ w.reshape(7, 5).T + b).reshape(2, 4, 3, 7)
+    assert np.max(np.abs(y - want.transpose(0, 3, 1, 2))) < 1e-12
+
+
+def test_full_window_conv_is_fc_and_fc_is_matmul():
+    x = RNG.standard_normal((3, 4, 5, 6))
+    w = RNG.standard_normal((8, 4, 5, 6))
+    b = RNG.standard_normal(8)
+    yc = oracle.conv2d(x, w, b)
+    yf = oracle.fc(x.reshape(3, -1), w.reshape(8, -1), b)
+    assert yc.shape == (3, 8, 1, 1)
+    assert np.max(np.abs(yc.reshape(3, 8) - yf)) < 1e-12
+    assert np.max(np.abs(yf - (x.reshape(3, -1) @ w.reshape(8, -1).T + b))) < 1e-12
+
+
+def test_pools_reduce_to_numpy():
+    x = RNG.standard_normal((2, 3, 6, 8))
+    assert np.max(np.abs(oracle.global_avgpool(x) - x.mean(axis=(2, 3)))) < 1e-15
+    want = x.reshape(2, 3, 3, 2, 4, 2).max(axis=(3, 5))
+    assert np.array_equal(oracle.maxpool(x, 2, 2), want)
+    assert np.max(np.abs(oracle.avgpool(x, 2, 2) - x.reshape(2, 3, 3, 2, 4, 2).mean(axis=(3, 5)))) < 1e-15
+
+
+def test_stride2_is_subsampled_stride1_and_shift_equivariance():
+    x = RNG.standard_normal((1, 2, 9, 9))
+    w = RNG.standard_normal((3, 2, 3, 3))
+    b = RNG.standard_normal(3)
+    assert np.array_equal(oracle.conv2d(x, w, b, 2, 1), oracle.conv2d(x, w, b, 1, 1)[:, :, ::2, ::2])
+    xs = np.zeros((1, 2, 12, 12))
+    xs[:, :, 4:7, 4:7] = RNG.standard_normal((1, 2, 3, 3))
+    y = oracle.conv2d(xs, w, None, 1, 1)
+    ys = oracle.conv2d(np.roll(xs, (1, 2), axis=(2, 3)), w, None, 1, 1)
+    assert np.array_equal(np.roll(y, (1, 2), axis=(2, 3)), ys)
+
+
+@pytest.mark.parametrize("C,K,R,stride,pad", [(3, 4, 7, 2, 3), (6, 16, 5, 1, 0), (8, 8, 3, 1, 1),
+                                              (5, 3, 3, 2, 1), (4, 6, 1, 2, 0), (2, 2, 5, 1, 2)])
+def test_conv_matches_torch_float64(C, K, R, stride, pad):
+    x = RNG.standard_normal((2, C, 11, 9))
+    w = RNG.standard_normal((K, C, R, R))
+    b = RNG.standard_normal(K)
+    want = F.conv2d(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(b), stride, pad).numpy()
+    got = oracle.conv2d(x, w, b, stride, pad)
+    assert got.shape == want.shape
+    assert np.max(np.abs(got - want)) < 1e-11
+
+
+def test_pool_fc_match_torch_float64():
+    x = RNG.standard_normal((2, 5, 13, 10))
+    xt = torch.from_numpy(x)
+    for k, s, p in [(3, 2, 1), (2, 2, 0), (3, 1, 1)]:
+        assert np.array_equal(oracle.maxpool(x, k, s, p), F.max_pool2d(xt, k, s, p).numpy())
+        assert np.max(np.abs(oracle.avgpool(x, k, s, p) - F.avg_pool2d(xt, k, s, p).numpy())) < 1e-14
+    xf, wf, bf = RNG.standard_normal((4, 9)), RNG.standard_normal((6, 9)), RNG.standard_normal(6)
+    want = F.linear(torch.from_numpy(xf), torch.from_numpy(wf), torch.from_numpy(bf)).numpy()
+    assert np.max(np.abs(oracle.fc(xf, wf, bf) - want)) < 1e-13
+
+
+# ---------------------------------------------------------------- model tables
+
+def test_model_totals_match_published_counts():
+    # LeNet-5: 61,706 parameters with 16*5*5 = 400 flattened features.
+    assert oracle.model_params(workloads.lenet5()) == 61706
+    # VGG-16: 138,357,544 parameters, 15.47 G multiply-adds per 224x224 image.
+    vgg = workloads.vgg16()
+    assert oracle.model_params(vgg) == 138357544
+    conv, fcf = oracle.model_flops(vgg)
+    assert abs((conv + fcf) / 2 / 1e9 - 15.47) < 0.01
+    # ResNet-50 (stride on the 3x3): 25,557,032 parameters counting two batch-norm
+    # vectors per convolution and no convolution bias; folded, each convolution
+    # keeps one bias vector.  4.09 G multiply-adds per image.
+    res = workloads.resnet50()
+    n_conv_bias = sum(nd.attr["K"] for nd in res.nodes if nd.op == "conv")
+    assert n_conv_bias == 26560
+    assert oracle.model_params(res) + n_conv_bias == 25557032
+    conv, fcf = oracle.model_flops(res)
+    assert sum(1 for nd in res.nodes if nd.op == "conv") == 53
+    assert abs((conv + fcf) / 2 / 1e9 - 4.09) < 0.01
+    # GoogLeNet without auxiliary heads: 57 convolutions, 1024 features into the FC.
+    goo = workloads.googlenet()
+    assert sum(1 for nd in goo.nodes if nd.op == "conv") == 57
+    conv, fcf = oracle.model_flops(goo)
+    assert fcf == 2 * 1024 * 1000
+    assert abs((conv + fcf) / 1e9 - 3.165) < 0.005
+    # single 3x3 layer at batch 32: 2*32*14*14*256*256*9
+    conv, _ = oracle.model_flops(workloads.single_conv())
+    assert conv * 32 == 7398752256
+
+
+def _torch_bottleneck_net(x, P):
+    """ResNet-shaped wiring written by hand (not from the table)."""
+    def cv(t, name, stride=1, pad=0):
+        w, b = P[name]
+        return F.conv2d(t, torch.from_numpy(w).double(), torch.from_numpy(b).double(), stride, pad)
+    t = F.relu(cv(x, "stem", 2, 3))
+    t = F.max_pool2d(t, 3, 2, 1)
+    for s, reps in enumerate((1, 2), 1):
+        for b in range(reps):
+            p = "l%d_%d" % (s, b)
+            stride = 2 if (s > 1 and b == 0) else 1
+            u = F.relu(cv(t, p + "_a"))
+            u = F.relu(cv(u, p + "_b", stride, 1))
+            u = cv(u, p + "_c")
+            sc = cv(t, p + "_proj", stride) if b == 0 else t
+            t = F.relu(u + sc)
+    t = t.mean(dim=(2, 3))
+    w, b = P["fc"]
+    return F.linear(t, torch.from_numpy(w).double(), torch.from_numpy(b).double())
+
+
+def test_resnet_wiring_against_handwritten_torch():
+    m = workloads.resnet50(width_div=8, in_hw=32, n_class=10, blocks=(1, 2))
+    P = workloads.parameters(m, seed=3)
+    x = workloads.batch_input(m, 2, seed=3)
+    got = oracle.run_model(m, P, x)
+    want = _torch_bottleneck_net(torch.from_numpy(x).double(), P).numpy()
+    assert got.shape == (2, 10)
+    assert np.max(np.abs(got - want)) < 1e-10 * max(1.0, np.abs(want).max())
+
+
+def test_inception_wiring_against_handwritten_torch():
+    m = workloads.googlenet(width_div=4, in_hw=32, n_class=10, n_blocks=1)
+    P = workloads.parameters(m, seed=4)
+    x = workloads.batch_input(m, 2, seed=4)
+
+    def cv(t, name, stride=1, pad=0):
+        w, b = P[name]
+        return F.relu(F.conv2d(t, torch.from_numpy(w).double(), torch.from_numpy(b).double(), stride, pad))
+    t = torch.from_numpy(x).double()
+    t = F.max_pool2d(cv(t, "stem1", 2, 3), 3, 2, 1)
+    t = F.max_pool2d(cv(cv(t, "stem2"), "stem3", 1, 1), 3, 2, 1)
+    b1 = cv(t, "i3a_1x1")
+    b2 = cv(cv(t, "i3a_3x3r"), "i3a_3x3", 1, 1)
+    b3 = cv(cv(t, "i3a_5x5r"), "i3a_5x5", 1, 2)
+    b4 = cv(F.max_pool2d(t, 3, 1, 1), "i3a_poolproj")
+    t = torch.cat([b1, b2, b3, b4], dim=1).mean(dim=(2, 3))
+    w, b = P["fc"]
+    want = F.linear(t, torch.from_numpy(w).double(), torch.from_numpy(b).double()).numpy()
+    got = oracle.run_model(m, P, x)
+    assert np.max(np.abs(got - want)) < 1e-10 * max(1.0, np.abs(want).max())
+
+
+def test_lenet_and_vgg_wiring_against_handwritten_torch():
+    m = workloads.lenet5()
+    P = workloads.parameters(m, seed=0)
+    x = workloads.batch_input(m, 3, seed=0)
+    tp = {k: (torch.from_numpy(w).double(), torch.from_numpy(b).double()) for k, (w, b) in P.items()}
+    t = torch.from_numpy(x).double()
+    t = F.max_pool2d(F.relu(F.conv2d(t, *tp["conv1"], 1, 2)), 2, 2)
+    t = F.max_pool2d(F.relu(F.conv2d(t, *tp["conv2"], 1, 0)), 2, 2)
+    t = t.flatten(1)
+    assert t.shape[1] == 400
+    t = F.relu(F.linear(t, *tp["fc1"]))
+    t = F.relu(F.linear(t, *tp["fc2"]))
+    want = F.linear(t, *tp["fc3"]).numpy()
+    got = oracle.run_model(m, P, x)
+    assert got.shape == (3, 10)
+    assert np.max(np.abs(got - want)) < 1e-11 * max(1.0, np.abs(want).max())
+
+    m = workloads.vgg16(width_div=16, in_hw=32, n_class=10)
+    P = workloads.parameters(m, seed=1)
+    x = workloads.batch_input(m, 2, seed=1)
+    tp = {k: (torch.from_numpy(w).double(), torch.from_numpy(b).double()) for k, (w, b) in P.items()}
+    t = torch.from_numpy(x).double()
+    for g, reps in enumerate((2, 2, 3, 3, 3), 1):
+        for i in range(1, reps + 1):
+            t = F.relu(F.conv2d(t, *tp["conv%d_%d" % (g, i)], 1, 1))
+        t = F.max_pool2d(t, 2, 2)
+    t = t.flatten(1)
+    t = F.relu(F.linear(t, *tp["fc6"]))
+    t = F.relu(F.linear(t, *tp["fc7"]))
+    want = F.linear(t, *tp["fc8"]).numpy()
+    got = oracle.run_model(m, P, x)
+    assert np.max(np.abs(got - want)) < 1e-11 * max(1.0, np.abs(want).max())
