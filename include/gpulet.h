@@ -1,0 +1,325 @@
+/*
+ * gpulet.h - C ABI of the MI355X-native hot path behind gpu-lets.
+ *
+ * Paper: "Multi-model Machine Learning Inference Serving with GPU Spatial
+ * Partitioning" (arXiv 2109.01611).  A gpu-let is a virtual GPU holding p% of
+ * one physical GPU's compute (Sec. 2.3); a batch of b requests of model m is
+ * served on it with latency L(b, p) (Sec. 3.1, Fig. 3; Table 2), and at most
+ * two gpu-lets share a GPU, their sizes summing to at most 100 (Sec. 1;
+ * Sec. 4.3 "Split": p and 100-p).  Here a gpu-let is a CU-masked HIP stream,
+ * and the forward pass (the paper's executors ran PyTorch's, Sec. 5) is a set
+ * of hand-written gfx950 kernels.
+ *
+ * Conventions for every call
+ *   - Returns a gpulet_status: 0 on success, negative on error.  Nothing
+ *     throws or aborts.  After GPULET_EHIP, gpulet_last_hip_error() gives the
+ *     hipError_t (per calling thread).
+ *   - Tensor pointers are DEVICE pointers owned by the caller; the library
+ *     never frees or keeps them past the call's enqueued work.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Kernel calls only enqueue work on it; they do not synchronise.
+ *   - Layouts: activations NHWC bf16 (n, h, w, c with c fastest); convolution
+ *     weights KRSC bf16 ([K][R][S][C]); FC weights [Out][In] bf16 with In in
+ *     the NHWC flatten order of the tensor feeding it; bias fp32.
+ *   - Arithmetic: bf16 x bf16 products accumulated in fp32 (MFMA), bias,
+ *     residual and ReLU in fp32, one round-to-nearest-even to bf16 on store.
+ */
+#ifndef GPULET_H
+#define GPULET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t gpulet_status;
+
+enum {
+    GPULET_OK = 0,
+    GPULET_EINVAL = -1,   /* NULL pointer, non-positive or overflowing shape, pct outside 1..100 */
+    GPULET_EOVERSUB = -2, /* more than two live gpu-lets on a device, or sizes summing past 100 */
+    GPULET_EHIP = -3,     /* a HIP runtime call failed; see gpulet_last_hip_error() */
+    GPULET_ENOMEM = -4    /* caller-provided workspace or output array too small */
+};
+
+/* Static, human-readable name of a status code. */
+const char *gpulet_status_string(gpulet_status s);
+
+/* hipError_t of the last GPULET_EHIP on the calling thread (0 if none). */
+int gpulet_last_hip_error(void);
+
+/* ------------------------------------------------------------------------
+ * gpu-let = spatial partition (Sec. 2.3; Sec. 4.3 "Split").
+ * ------------------------------------------------------------------------ */
+
+/*
+ * CU mask of a gpu-let of `pct` percent on a device of n_cu_total compute
+ * units in n_xcd equal dies.  Pure integer host code, no GPU needed.
+ *
+ * The paper gives sizes in percent; a CU mask needs a whole number of CUs.
+ * The share is rounded per die so that every die contributes the same count:
+ *   share(pct) = (pct * cus_per_xcd + 50) / 100   (integer division),
+ * clamped to 1 .. cus_per_xcd - 1 for pct < 100 (share(100) = cus_per_xcd), so
+ * a Split always leaves the partner at least one CU per die.  which = 0 takes
+ * the first share(pct) CUs of every die; which = 1 is the partner produced by
+ * Split: it takes what a which = 0 gpu-let of (100 - pct) leaves, i.e.
+ * cus_per_xcd - share(100 - pct) CUs per die, so the two are disjoint and
+ * together cover the device.
+ *
+ * Mask bit i names CU (i / n_xcd) of die (i % n_xcd): the driver deals mask
+ * bits round-robin over the dies.
+ *
+ * words[]: at least (n_cu_total + 31) / 32 entries (n_words_cap says how
+ * many); *n_words receives the count written, *n_cu the popcount.
+ * Errors: GPULET_EINVAL (NULL, pct outside 1..100, which outside 0..1,
+ * n_cu_total not a positive multiple of n_xcd, a share of zero CUs),
+ * GPULET_ENOMEM (n_words_cap too small).
+ */
+gpulet_status gpulet_mask_for_pct(int n_cu_total, int n_xcd, int pct, int which,
+                                  uint32_t *words, int n_words_cap, int *n_words, int *n_cu);
+
+typedef struct gpulet_partition gpulet_partition; /* opaque, library-owned */
+
+/*
+ * Create a gpu-let of `pct` percent on HIP device `device`: computes the mask
+ * as above from the device's CU count and creates a CU-masked stream.
+ * At most two gpu-lets may be live per device and their pct must sum to at
+ * most 100 (Sec. 1: up to two per GPU); otherwise GPULET_EOVERSUB.  Two live
+ * gpu-lets must use different `which`.  *out is set only on success and must
+ * be released with gpulet_partition_destroy.  Thread-safe.
+ */
+gpulet_status gpulet_partition_create(int device, int pct, int which, gpulet_partition **out);
+
+/* Synchronises the stream, destroys it and frees the record.  Destroying a
+ * handle twice, or NULL, returns GPULET_EINVAL. */
+gpulet_status gpulet_partition_destroy(gpulet_partition *p);
+
+/*
+ * Facts of a live gpu-let.  Any output pointer may be NULL.  mask_words must
+ * have room for 8 words (256 CUs); *n_words says how many are meaningful.
+ * *hip_stream is the hipStream_t to pass as `stream` below.
+ */
+gpulet_status gpulet_partition_info(const gpulet_partition *p, int *device, int *pct, int *which,
+                                    int *n_cu, int *n_cu_total, uint32_t mask_words[8],
+                                    int *n_words, void **hip_stream);
+
+/* Mask the HIP runtime reports for the gpu-let's stream (hipExtStreamGetCUMask);
+ * same array rules as above. */
+gpulet_status gpulet_partition_query_mask(const gpulet_partition *p, uint32_t mask_words[8],
+                                          int *n_words);
+
+/* Request bookkeeping (Sec. 5: the frontend forms batches and dispatches each
+ * to the executor of one gpu-let): batches and images run on this gpu-let
+ * through gpulet_run_model and the profiling calls, exact integers. */
+gpulet_status gpulet_partition_counters(const gpulet_partition *p, uint64_t *batches_run,
+                                        uint64_t *images_run);
+
+/* Blocks until all work enqueued on the gpu-let's stream has finished. */
+gpulet_status gpulet_partition_sync(gpulet_partition *p);
+
+/*
+ * Runs n_blocks workgroups of a tiny kernel on the gpu-let and records, per
+ * workgroup, where the hardware placed it: out[2*i] = die (XCC) id,
+ * out[2*i+1] = the hardware id register (shader engine, shader array and CU
+ * fields).  `out` is a DEVICE array of 2*n_blocks uint32.  Synchronises.
+ * Used to check that a mask is honoured and which physical CUs it names.
+ */
+gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_blocks);
+
+/* ------------------------------------------------------------------------
+ * Layers of the forward pass (Sec. 5; models of Table 4).
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Convolution layer, implicit GEMM on MFMA with fused bias and ReLU:
+ *   y[n,p,q,k] = act(b[k] + sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c])
+ * with x taken as zero outside the image (cross-correlation, no kernel flip)
+ * and P = (H + 2*pad - R) / stride + 1, Q likewise from W and S.
+ * x: N*H*W*C bf16, w: K*R*S*C bf16, b: K fp32 (NULL = no bias), y: N*P*Q*K bf16.
+ * Errors: GPULET_EINVAL for NULL x/w/y, non-positive sizes, pad < 0, empty
+ * output, or any tensor of 2^31 or more elements.
+ */
+gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const float *b, void *y, int N,
+                                int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                int relu, void *stream);
+
+/*
+ * Same, plus what residual and inception blocks need:
+ *   residual      NULL, or a bf16 tensor N*P*Q*K (dense) added before the ReLU;
+ *   y_ch_stride   channels per pixel of the tensor y points into (0 means K);
+ *   y_ch_offset   first channel written, so a branch lands directly inside a
+ *                 concatenated tensor: y[((n*P+p)*Q+q)*y_ch_stride + y_ch_offset + k].
+ * Extra error: y_ch_offset < 0 or y_ch_offset + K > y_ch_stride.
+ */
+gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b, void *y, int N,
+                                   int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                   int relu, const void *residual, int y_ch_stride,
+                                   int y_ch_offset, void *stream);
+
+/*
+ * Tuning and testing knob: force every later convolution launch of the
+ * process onto one workgroup tile (pixels x channels):
+ *   0: 128x128  1: 128x64  2: 64x128  3: 64x64  4: 128x32  5: 32x128,
+ * or -1 to return to automatic selection, which picks the tile whose busiest
+ * CU has the least work for the launch's shape and the stream's CU count.
+ * Results do not depend on the tile.  GPULET_EINVAL outside -1..5.
+ */
+enum { GPULET_CONV_TILES = 6 };
+gpulet_status gpulet_set_conv_tile(int tile);
+
+enum { GPULET_POOL_MAX = 0, GPULET_POOL_AVG = 1, GPULET_POOL_GLOBAL_AVG = 2 };
+
+/*
+ * Pooling over NHWC bf16.  mode MAX: maximum over the in-image taps of a
+ * k x k window (padding never wins).  mode AVG: sum of the in-image taps
+ * divided by k*k (padding counts as zero).  mode GLOBAL_AVG: mean over the
+ * H x W plane (k, stride, pad ignored), output N*1*1*C.  Sums are fp32.
+ * Output extent as for convolution.  Requires pad < k.
+ */
+gpulet_status gpulet_pool(const void *x, void *y, int N, int C, int H, int W, int mode, int k,
+                          int stride, int pad, void *stream);
+
+/*
+ * Fully connected layer on MFMA:
+ *   y[n,o] = act(b[o] + sum_i x[n,i] * w[o,i])
+ * x: N*In bf16, w: Out*In bf16, b: Out fp32 or NULL, y: N*Out, bf16 or (if
+ * out_fp32) fp32.
+ */
+gpulet_status gpulet_fc(const void *x, const void *w, const float *b, void *y, int N, int In,
+                        int Out, int relu, int out_fp32, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Whole model on a gpu-let (Sec. 5 "Backend inference executor").
+ * ------------------------------------------------------------------------ */
+
+enum { GPULET_OP_CONV = 0, GPULET_OP_POOL = 1, GPULET_OP_FC = 2 };
+
+/*
+ * One layer.  Activations live in numbered buffers; a layer reads in_buf and
+ * writes out_buf.  Spatial sizes are inferred by the library from the model
+ * input.  Fields not used by an op are ignored.
+ */
+typedef struct gpulet_layer {
+    int32_t op;            /* GPULET_OP_* */
+    int32_t in_buf;        /* buffer read */
+    int32_t out_buf;       /* buffer written */
+    int32_t res_buf;       /* CONV: buffer added before the ReLU, or -1 */
+    int32_t C;             /* CONV/POOL: input channels; FC: In (= C*H*W of in_buf) */
+    int32_t K;             /* CONV: output channels; FC: Out */
+    int32_t R;             /* CONV: kernel height; POOL: window k */
+    int32_t S;             /* CONV: kernel width */
+    int32_t stride;
+    int32_t pad;
+    int32_t relu;          /* CONV/FC */
+    int32_t mode;          /* POOL: GPULET_POOL_* */
+    int32_t out_ch_total;  /* CONV: channels of out_buf when this layer writes a slice of
+                              a concatenated tensor; 0 means K */
+    int32_t out_ch_offset; /* CONV: first channel written */
+    int32_t out_fp32;      /* FC: store fp32 instead of bf16 */
+    int32_t reserved;
+    const void *w;         /* device: CONV KRSC bf16, FC [Out][In] bf16 */
+    const float *b;        /* device: fp32 bias or NULL */
+} gpulet_layer;
+
+/*
+ * A model: layers in execution order over n_bufs buffers.  Buffer in_buf is
+ * the caller's input tensor (N, in_H, in_W, in_C), buffer out_buf the caller's
+ * output; all others are carved from the workspace.  A buffer may be written
+ * by several layers (disjoint channel slices, or reuse after its readers have
+ * run); its size is the largest it ever needs.  Every buffer must be written
+ * before it is read.
+ */
+typedef struct gpulet_model_desc {
+    int32_t n_layers;
+    int32_t n_bufs;
+    int32_t in_C, in_H, in_W;
+    int32_t in_buf;
+    int32_t out_buf;
+    int32_t reserved;
+    const gpulet_layer *layers;
+} gpulet_model_desc;
+
+/* Bytes of workspace gpulet_run_model needs for `batch` images (a multiple of
+ * 256).  GPULET_EINVAL if the description is inconsistent (channel or feature
+ * counts that do not match the inferred shapes, bad buffer indices, a buffer
+ * read before written, empty outputs). */
+gpulet_status gpulet_model_workspace_bytes(const gpulet_model_desc *m, int batch, size_t *bytes);
+
+/* Inferred shape of one buffer for one image (its last writer's view), its
+ * element size in bytes, and its byte offset inside the workspace for `batch`
+ * images (offset is (size_t)-1 for the model's input and output buffers). */
+gpulet_status gpulet_model_buffer_info(const gpulet_model_desc *m, int batch, int buf, int *C,
+                                       int *H, int *W, int *elem_bytes, size_t *ws_offset);
+
+/*
+ * Forward pass of one batch on a gpu-let: every layer is enqueued on the
+ * partition's stream with no host synchronisation in between.  `in` is the
+ * input batch (batch*in_H*in_W*in_C bf16), `out` receives the output buffer.
+ * `workspace` must be 256-byte aligned device memory of at least
+ * gpulet_model_workspace_bytes() bytes (GPULET_ENOMEM otherwise).
+ * If latency_ms is not NULL the call brackets the batch with events, waits
+ * for it and stores the elapsed milliseconds; if NULL it returns right after
+ * enqueueing.  Counts one batch and `batch` images on the partition.
+ */
+gpulet_status gpulet_run_model(const gpulet_model_desc *m, int batch, gpulet_partition *p,
+                               const void *in, void *out, void *workspace,
+                               size_t workspace_bytes, float *latency_ms);
+
+/* ------------------------------------------------------------------------
+ * Profiling: the L(b, p) table and co-run interference (Sec. 3.1, 3.2, 4.1).
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Runs `warmup` untimed batches, then `iters` batches each bracketed by its
+ * own event pair on the gpu-let's stream; latency_ms[i] receives batch i's
+ * elapsed milliseconds.  With sync_each != 0 the host waits for a batch to
+ * finish before dispatching the next (the serving pattern: one batch in
+ * flight per gpu-let); with sync_each == 0 batches are enqueued back to back.
+ * If total_ms is not NULL it receives the time from the first timed batch's
+ * start to the last one's end.  Synchronises before returning.
+ */
+gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int batch, gpulet_partition *p,
+                                   const void *in, void *out, void *workspace,
+                                   size_t workspace_bytes, int warmup, int iters, int sync_each,
+                                   float *latency_ms, float *total_ms);
+
+/*
+ * Two gpu-lets at once (Sec. 3.2): model A on partition pa and model B on pb
+ * are driven by two host threads, each dispatching one batch at a time (timed
+ * by its own event pair, waited for before the next) until `window_ms` of wall
+ * time has passed after `warmup` untimed batches each; the timed windows of
+ * the two threads start together.  lat_a/lat_b (capacity cap_a/cap_b)
+ * receive the per-batch latencies, *n_a and *n_b how many were recorded (batches
+ * beyond the capacity still run but are not recorded).  pa and pb must be
+ * different live gpu-lets of one device.
+ */
+gpulet_status gpulet_profile_corun(const gpulet_model_desc *ma, int batch_a, gpulet_partition *pa,
+                                   const void *in_a, void *out_a, void *ws_a, size_t ws_a_bytes,
+                                   const gpulet_model_desc *mb, int batch_b, gpulet_partition *pb,
+                                   const void *in_b, void *out_b, void *ws_b, size_t ws_b_bytes,
+                                   int warmup, double window_ms, float *lat_a, int cap_a,
+                                   int *n_a, float *lat_b, int cap_b, int *n_b);
+
+/* Mean, median and nearest-rank 99th percentile of n latencies (host, fp64).
+ * The p-th percentile is the value at rank ceil(p/100 * n) of the sorted list. */
+gpulet_status gpulet_latency_stats(const float *latency_ms, int n, double *mean, double *p50,
+                                   double *p99);
+
+/*
+ * Times `iters` back-to-back launches of one convolution layer between a
+ * single event pair on `stream` (after `warmup` untimed launches) and stores
+ * the average milliseconds per launch.  Arguments as gpulet_conv2d_fwd_ex.
+ * Synchronises.
+ */
+gpulet_status gpulet_time_conv2d(const void *x, const void *w, const float *b, void *y, int N,
+                                 int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                 int relu, const void *residual, int y_ch_stride,
+                                 int y_ch_offset, void *stream, int warmup, int iters,
+                                 float *avg_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPULET_H */

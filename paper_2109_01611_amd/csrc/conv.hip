@@ -1,0 +1,331 @@
+// Convolution layer of the forward pass served on a gpu-let (paper Sec. 5; the
+// models of Table 4), as an implicit GEMM on gfx950 matrix cores:
+//
+//   rows    m = (n, p, q)   output pixels          M  = N*P*Q
+//   columns k               output channels        Ng = K
+//   depth   g = (r, s, c)   filter taps x channels Kg = R*S*C
+//
+// x is NHWC and w is KRSC, so both operands are contiguous along the depth
+// and neither the im2col matrix nor a transposed weight is ever built.
+//
+// One workgroup of four wavefronts owns a BM x BN output tile and walks the
+// depth in slices of 64.  Each slice is gathered from global memory as 16-byte
+// chunks (8 channels of one tap; zero for padding taps and ragged edges) into
+// a double-buffered, XOR-swizzled LDS tile; the next slice's loads are issued
+// before the MFMAs of the current one.  Wavefronts read 8-element fragments
+// back with ds_read_b128 and feed v_mfma_f32_32x32x16_bf16; accumulators stay
+// in registers for the whole depth.  The epilogue adds bias and the optional
+// residual in fp32, applies ReLU, rounds once to bf16 and stores, optionally
+// at a channel offset inside a wider (concatenated) tensor.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+
+#include "gpulet_internal.h"
+
+namespace gpulet {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BK = 64;        // depth slice per main-loop step (elements)
+constexpr int CHUNK = 8;      // elements per 16-byte chunk
+constexpr int NTHREADS = 256; // four wavefronts
+
+struct ConvParams {
+    const __bf16 *x, *w;
+    const float *b;
+    __bf16 *y;
+    const __bf16 *res;
+    int N, C, H, W, K, R, S, stride, pad, relu, P, Q;
+    int M, Kg;          // GEMM rows and depth
+    int ldy, y_off;     // channels per output pixel of the destination, first channel
+    int tiles_n, n_tiles, tiles_per_xcd;
+};
+
+// LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
+// Rows are 128 bytes; XOR-ing the chunk index with bits 1..3 of the row spreads
+// 16 consecutive rows at one logical chunk over all 64 banks.
+__device__ __forceinline__ int lds_pos(int row, int chunk) {
+    return row * BK + ((chunk ^ ((row >> 1) & 7)) * CHUNK);
+}
+
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
+
+template <int BM, int BN, int WGM, int WGN, bool VEC>
+__global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p) {
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int WM = BM / WGM, WN = BN / WGN;  // wavefront tile
+    constexpr int MT = WM / 32, NT = WN / 32;    // MFMA tiles per wavefront
+    static_assert(MT >= 1 && NT >= 1 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    constexpr int AROWS = BM / 32, BROWS = BN / 32;  // chunks each thread stages per slice
+
+    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM * BK];
+    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN * BK];
+
+    // Workgroups are dealt round-robin to the eight dies, each with its own L2.
+    // Give every die a contiguous run of tiles so that tiles sharing a pixel
+    // block (all their channel tiles) hit the same L2.
+    const int tile = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+    if (tile >= p.n_tiles) return;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wy = wave / WGN, wx = wave - wy * WGN;
+
+    // ---- staging roles: this thread always carries depth chunk `cc` of rows lrow + 32*i
+    const int cc = tid & 7;
+    const int lrow = tid >> 3;
+
+    int a_base[AROWS], a_h0[AROWS], a_w0[AROWS];
+#pragma unroll
+    for (int i = 0; i < AROWS; ++i) {
+        const int m = m0 + lrow + 32 * i;
+        if (m < p.M) {
+            const int n = m / (p.P * p.Q);
+            const int pq = m - n * (p.P * p.Q);
+            const int pp = pq / p.Q, qq = pq - pp * p.Q;
+            a_h0[i] = pp * p.stride - p.pad;
+            a_w0[i] = qq * p.stride - p.pad;
+            a_base[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C;
+        } else {
+            a_h0[i] = -(1 << 28);  // fails every bounds test below
+            a_w0[i] = -(1 << 28);
+            a_base[i] = 0;
+        }
+    }
+    int b_base[BROWS];
+    bool b_ok[BROWS];
+#pragma unroll
+    for (int i = 0; i < BROWS; ++i) {
+        const int k = n0 + lrow + 32 * i;
+        b_ok[i] = k < p.K;
+        b_base[i] = (b_ok[i] ? k : 0) * p.Kg;
+    }
+
+    uint4 ra[AROWS], rb[BROWS];
+
+    // Gathers depth slice `kt` into registers.
+    auto load_slice = [&](int kt) {
+        const int g0 = kt * BK + cc * CHUNK;
+        if (VEC) {
+            // C % 8 == 0: the 8 elements of a chunk are 8 channels of one tap.
+            const int rs = g0 / p.C;
+            const int c = g0 - rs * p.C;
+            const int r = rs / p.S, s = rs - r * p.S;
+            const bool g_ok = g0 < p.Kg;
+            const int tap = (r * p.W + s) * p.C + c;
+#pragma unroll
+            for (int i = 0; i < AROWS; ++i) {
+                const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
+                                (unsigned)(a_w0[i] + s) < (unsigned)p.W;
+                ra[i] = ok ? *reinterpret_cast<const uint4 *>(p.x + (a_base[i] + tap)) : zero4();
+            }
+#pragma unroll
+            for (int i = 0; i < BROWS; ++i)
+                rb[i] = (g_ok && b_ok[i]) ? *reinterpret_cast<const uint4 *>(p.w + (b_base[i] + g0))
+                                          : zero4();
+        } else {
+            // Any C: every element is decoded on its own.
+            int rs = g0 / p.C;
+            int c = g0 - rs * p.C;
+            int r = rs / p.S, s = rs - r * p.S;
+            unsigned short ea[AROWS][CHUNK], eb[BROWS][CHUNK];
+#pragma unroll
+            for (int e = 0; e < CHUNK; ++e) {
+                const bool g_ok = g0 + e < p.Kg;
+                const int tap = (r * p.W + s) * p.C + c;
+#pragma unroll
+                for (int i = 0; i < AROWS; ++i) {
+                    const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
+                                    (unsigned)(a_w0[i] + s) < (unsigned)p.W;
+                    ea[i][e] = ok ? reinterpret_cast<const unsigned short *>(p.x)[a_base[i] + tap]
+                                  : (unsigned short)0;
+                }
+#pragma unroll
+                for (int i = 0; i < BROWS; ++i)
+                    eb[i][e] = (g_ok && b_ok[i])
+                                   ? reinterpret_cast<const unsigned short *>(p.w)[b_base[i] + g0 + e]
+                                   : (unsigned short)0;
+                if (++c == p.C) {
+                    c = 0;
+                    if (++s == p.S) {
+                        s = 0;
+                        ++r;
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < AROWS; ++i)
+                ra[i] = make_uint4(ea[i][0] | ((unsigned)ea[i][1] << 16), ea[i][2] | ((unsigned)ea[i][3] << 16),
+                                   ea[i][4] | ((unsigned)ea[i][5] << 16), ea[i][6] | ((unsigned)ea[i][7] << 16));
+#pragma unroll
+            for (int i = 0; i < BROWS; ++i)
+                rb[i] = make_uint4(eb[i][0] | ((unsigned)eb[i][1] << 16), eb[i][2] | ((unsigned)eb[i][3] << 16),
+                                   eb[i][4] | ((unsigned)eb[i][5] << 16), eb[i][6] | ((unsigned)eb[i][7] << 16));
+        }
+    };
+
+    auto store_slice = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < AROWS; ++i)
+            *reinterpret_cast<uint4 *>(&sA[buf][lds_pos(lrow + 32 * i, cc)]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < BROWS; ++i)
+            *reinterpret_cast<uint4 *>(&sB[buf][lds_pos(lrow + 32 * i, cc)]) = rb[i];
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = (p.Kg + BK - 1) / BK;
+    const int frow = lane & 31;  // row of an MFMA operand this lane supplies
+    const int fhalf = lane >> 5; // which 8 of the 16 depth elements of a step
+
+    load_slice(0);
+    store_slice(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_slice(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[MT], fb[NT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8 *>(
+                    &sA[buf][lds_pos(wy * WM + i * 32 + frow, ks * 2 + fhalf)]);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8 *>(
+                    &sB[buf][lds_pos(wx * WN + j * 32 + frow, ks * 2 + fhalf)]);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_slice(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue.  Accumulator register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4
+    // and column lane%32 of the 32x32 tile.
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int k = n0 + wx * WN + j * 32 + frow;
+        if (k >= p.K) continue;
+        const float bias = p.b ? p.b[k] : 0.f;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wy * WM + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
+                if (m >= p.M) continue;
+                float val = acc[i][j][v] + bias;
+                if (p.res) val += static_cast<float>(p.res[m * p.K + k]);
+                if (p.relu) val = val > 0.f ? val : 0.f;
+                p.y[m * p.ldy + p.y_off + k] = static_cast<__bf16>(val);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_tile(ConvParams p, bool vec, hipStream_t stream) {
+    const int tiles_m = (p.M + BM - 1) / BM;
+    p.tiles_n = (p.K + BN - 1) / BN;
+    p.n_tiles = tiles_m * p.tiles_n;
+    p.tiles_per_xcd = (p.n_tiles + 7) / 8;
+    const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8));
+    if (vec)
+        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, WGM, WGN, true>), grid, dim3(NTHREADS), 0, stream, p);
+    else
+        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, WGM, WGN, false>), grid, dim3(NTHREADS), 0, stream, p);
+    return hipGetLastError();
+}
+
+std::atomic<int> g_tile_override{-1};
+
+struct TileChoice {
+    int bm, bn;
+    float eff;  // relative MFMA efficiency of the tile shape (bigger tiles reuse LDS reads more)
+};
+
+}  // namespace
+
+gpulet_status check_conv(const ConvArgs &a) {
+    if (!a.x || !a.w || !a.y) return GPULET_EINVAL;
+    if (a.N < 1 || a.C < 1 || a.H < 1 || a.W < 1 || a.K < 1 || a.R < 1 || a.S < 1 || a.stride < 1 ||
+        a.pad < 0)
+        return GPULET_EINVAL;
+    if (a.P < 1 || a.Q < 1) return GPULET_EINVAL;
+    if (a.y_ch_offset < 0 || a.y_ch_offset + a.K > a.y_ch_stride) return GPULET_EINVAL;
+    const long long lim = 1LL << 31;
+    const long long xe = 1LL * a.N * a.H * a.W * a.C;
+    const long long we = 1LL * a.K * a.R * a.S * a.C;
+    const long long ye = 1LL * a.N * a.P * a.Q * a.y_ch_stride;
+    // The gather indexes from (h, w) = (-pad, -pad); keep that offset inside int32 too.
+    const long long slack = (1LL * a.pad * a.W + a.pad + a.R * 1LL * a.W + a.S) * a.C;
+    if (xe + slack >= lim || we >= lim || ye >= lim) return GPULET_EINVAL;
+    return GPULET_OK;
+}
+
+hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
+    ConvParams p;
+    p.x = static_cast<const __bf16 *>(a.x);
+    p.w = static_cast<const __bf16 *>(a.w);
+    p.b = a.b;
+    p.y = static_cast<__bf16 *>(a.y);
+    p.res = static_cast<const __bf16 *>(a.residual);
+    p.N = a.N; p.C = a.C; p.H = a.H; p.W = a.W; p.K = a.K; p.R = a.R; p.S = a.S;
+    p.stride = a.stride; p.pad = a.pad; p.relu = a.relu; p.P = a.P; p.Q = a.Q;
+    p.M = a.N * a.P * a.Q;
+    p.Kg = a.R * a.S * a.C;
+    p.ldy = a.y_ch_stride;
+    p.y_off = a.y_ch_offset;
+    p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
+
+    const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
+
+    // Pick the tile that minimises (workgroups the busiest CU runs) x (tile area) / efficiency.
+    static const TileChoice kTiles[] = {{128, 128, 1.00f}, {128, 64, 0.85f}, {64, 128, 0.85f},
+                                        {64, 64, 0.70f},   {128, 32, 0.60f}, {32, 128, 0.60f}};
+    int best = 0;
+    double best_cost = 0.0;
+    if (n_cu < 1) n_cu = 1;
+    for (int i = 0; i < 6; ++i) {
+        const TileChoice &t = kTiles[i];
+        const long long blocks = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
+        const long long per_cu = (blocks + n_cu - 1) / n_cu;
+        const double cost = static_cast<double>(per_cu) * t.bm * t.bn / t.eff;
+        if (i == 0 || cost < best_cost) {
+            best = i;
+            best_cost = cost;
+        }
+    }
+    const int forced = g_tile_override.load();
+    if (forced >= 0 && forced < 6) best = forced;
+    switch (best) {
+        case 0: return launch_tile<128, 128, 2, 2>(p, vec, stream);
+        case 1: return launch_tile<128, 64, 2, 2>(p, vec, stream);
+        case 2: return launch_tile<64, 128, 2, 2>(p, vec, stream);
+        case 3: return launch_tile<64, 64, 2, 2>(p, vec, stream);
+        case 4: return launch_tile<128, 32, 4, 1>(p, vec, stream);
+        default: return launch_tile<32, 128, 1, 4>(p, vec, stream);
+    }
+}
+
+void set_conv_tile(int tile) { g_tile_override.store(tile); }
+
+}  // namespace gpulet

@@ -1,0 +1,164 @@
+// Fully connected layer of the forward pass served on a gpu-let (paper Sec. 5;
+// classifier heads of the models in Table 4) on gfx950 matrix cores.
+//
+// At serving batch sizes (1-32, Fig. 3) this GEMM has as many rows as the
+// batch, so it is bound by streaming the [Out][In] weights from HBM once.
+// A workgroup owns 16 outputs and up to 32 batch rows; its four wavefronts each
+// stream a contiguous quarter of the In range straight from global memory into
+// v_mfma_f32_16x16x32_bf16 operands (no LDS staging: every weight is used
+// once), then the four partial accumulators are summed through LDS and the
+// first wavefront adds bias, applies ReLU and stores bf16 or fp32.
+#include <hip/hip_runtime.h>
+
+#include "gpulet_internal.h"
+
+namespace gpulet {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+struct FcParams {
+    const __bf16 *x, *w;
+    const float *b;
+    void *y;
+    int N, In, Out, relu, out_fp32;
+};
+
+constexpr int UNROLL = 4;  // depth steps of 32 in flight per wavefront
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &v) {
+    return *reinterpret_cast<const bf16x8 *>(&v);
+}
+
+// Loads 8 consecutive elements starting at row_ptr[k]; zero where out of range.
+template <bool VEC>
+__device__ __forceinline__ uint4 load_chunk(const __bf16 *row_ptr, int k, int In, bool row_ok) {
+    if (VEC) {
+        if (row_ok && k < In) return *reinterpret_cast<const uint4 *>(row_ptr + k);
+        return make_uint4(0u, 0u, 0u, 0u);
+    }
+    unsigned short e[8];
+    const unsigned short *s = reinterpret_cast<const unsigned short *>(row_ptr);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) e[i] = (row_ok && k + i < In) ? s[k + i] : (unsigned short)0;
+    return make_uint4(e[0] | ((unsigned)e[1] << 16), e[2] | ((unsigned)e[3] << 16),
+                      e[4] | ((unsigned)e[5] << 16), e[6] | ((unsigned)e[7] << 16));
+}
+
+// NB = batch tiles of 16 rows handled per workgroup (1 or 2).
+template <int NB, bool VEC>
+__global__ __launch_bounds__(256) void fc_kernel(const FcParams p) {
+    __shared__ float red[3][NB][64][4];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int o0 = blockIdx.x * 16;
+    const int n0 = blockIdx.y * (16 * NB);
+    const int sub = lane & 15;   // operand row (batch row for x, output for w)
+    const int kq = lane >> 4;    // which 8 of the 32 depth elements of a step
+
+    const int o = o0 + sub;
+    const bool o_ok = o < p.Out;
+    const __bf16 *wrow = p.w + static_cast<size_t>(o_ok ? o : 0) * p.In;
+    const __bf16 *xrow[NB];
+    bool n_ok[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const int n = n0 + t * 16 + sub;
+        n_ok[t] = n < p.N;
+        xrow[t] = p.x + static_cast<size_t>(n_ok[t] ? n : 0) * p.In;
+    }
+
+    const int steps = (p.In + 31) / 32;
+    const int per_wave = (steps + 3) / 4;
+    const int s_begin = wave * per_wave;
+    const int s_end = min(steps, s_begin + per_wave);
+
+    f32x4 acc[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int s = s_begin; s < s_end; s += UNROLL) {
+        uint4 rw[UNROLL], rx[NB][UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int k = (s + u) * 32 + kq * 8;
+            const bool live = s + u < s_end;
+            rw[u] = load_chunk<VEC>(wrow, k, p.In, o_ok && live);
+#pragma unroll
+            for (int t = 0; t < NB; ++t) rx[t][u] = load_chunk<VEC>(xrow[t], k, p.In, n_ok[t] && live);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+            for (int t = 0; t < NB; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(rx[t][u]), as_bf16x8(rw[u]),
+                                                                 acc[t], 0, 0, 0);
+    }
+
+    if (wave > 0) {
+#pragma unroll
+        for (int t = 0; t < NB; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[wave - 1][t][lane][v] = acc[t][v];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+
+    // Accumulator register v of a lane holds batch row 4*(lane/16) + v, output lane%16.
+    const float bias = (p.b && o_ok) ? p.b[o] : 0.f;
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float val = acc[t][v] + red[0][t][lane][v] + red[1][t][lane][v] + red[2][t][lane][v];
+            const int n = n0 + t * 16 + 4 * kq + v;
+            if (!o_ok || n >= p.N) continue;
+            val += bias;
+            if (p.relu) val = val > 0.f ? val : 0.f;
+            const size_t idx = static_cast<size_t>(n) * p.Out + o;
+            if (p.out_fp32)
+                static_cast<float *>(p.y)[idx] = val;
+            else
+                static_cast<__bf16 *>(p.y)[idx] = static_cast<__bf16>(val);
+        }
+    }
+}
+
+}  // namespace
+
+gpulet_status check_fc(int N, int In, int Out) {
+    if (N < 1 || In < 1 || Out < 1) return GPULET_EINVAL;
+    const long long lim = 1LL << 31;
+    if (1LL * N * In >= lim || 1LL * Out * In >= lim || 1LL * N * Out >= lim) return GPULET_EINVAL;
+    return GPULET_OK;
+}
+
+hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
+                     int relu, int out_fp32, hipStream_t stream) {
+    FcParams p;
+    p.x = static_cast<const __bf16 *>(x);
+    p.w = static_cast<const __bf16 *>(w);
+    p.b = b;
+    p.y = y;
+    p.N = N; p.In = In; p.Out = Out; p.relu = relu; p.out_fp32 = out_fp32;
+    const bool vec = (In % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(w) % 16 == 0);
+    const unsigned gx = static_cast<unsigned>((Out + 15) / 16);
+    if (N <= 16) {
+        const dim3 grid(gx, 1);
+        if (vec)
+            hipLaunchKernelGGL((fc_kernel<1, true>), grid, dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((fc_kernel<1, false>), grid, dim3(256), 0, stream, p);
+    } else {
+        const dim3 grid(gx, static_cast<unsigned>((N + 31) / 32));
+        if (vec)
+            hipLaunchKernelGGL((fc_kernel<2, true>), grid, dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((fc_kernel<2, false>), grid, dim3(256), 0, stream, p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace gpulet

@@ -1,0 +1,79 @@
+// Internal declarations shared by the translation units of libgpulet.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstddef>
+#include <cstdint>
+
+#include "gpulet.h"
+
+namespace gpulet {
+
+// Records the failing hipError_t for gpulet_last_hip_error() and returns GPULET_EHIP.
+gpulet_status hip_fail(hipError_t e);
+
+#define GPULET_HIP(expr)                                   \
+    do {                                                   \
+        hipError_t e__ = (expr);                           \
+        if (e__ != hipSuccess) return ::gpulet::hip_fail(e__); \
+    } while (0)
+
+constexpr int kMaxMaskWords = 8;
+
+}  // namespace gpulet
+
+// A live gpu-let (paper Sec. 2.3): a CU-masked stream plus its bookkeeping.
+struct gpulet_partition {
+    int device;
+    int pct;
+    int which;
+    int n_cu;
+    int n_cu_total;
+    int n_words;
+    uint32_t mask[gpulet::kMaxMaskWords];
+    hipStream_t stream;
+    std::atomic<uint64_t> batches_run;
+    std::atomic<uint64_t> images_run;
+};
+
+namespace gpulet {
+
+// True if p is a handle gpulet_partition_create returned and nobody destroyed yet
+// (looked up in the registry, so a stale pointer is never dereferenced).
+bool live(const gpulet_partition *p);
+
+// Output extent of a window op; <= 0 means empty.
+inline int out_extent(int in, int k, int stride, int pad) {
+    const int span = in + 2 * pad - k;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+// Number of CUs a launch on `stream` may use: the owning gpu-let's CU count if the
+// stream belongs to one, else the device's.  Tile selection keys on it.
+int stream_cu_count(hipStream_t stream);
+
+// Kernel launchers (conv.hip, pool.hip, fc.hip).  Arguments are validated by the callers.
+struct ConvArgs {
+    const void *x, *w;
+    const float *b;
+    void *y;
+    const void *residual;
+    int N, C, H, W, K, R, S, stride, pad, relu, P, Q, y_ch_stride, y_ch_offset;
+};
+hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream);
+void set_conv_tile(int tile);
+hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P, int Q, int mode,
+                       int k, int stride, int pad, hipStream_t stream);
+hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
+                     int relu, int out_fp32, hipStream_t stream);
+hipError_t launch_probe(uint32_t *out, int n_blocks, hipStream_t stream);
+
+// Argument checks shared by the single-layer entry points and the model runner.
+gpulet_status check_conv(const ConvArgs &a);
+gpulet_status check_pool(int N, int C, int H, int W, int mode, int k, int stride, int pad, int *P,
+                         int *Q);
+gpulet_status check_fc(int N, int In, int Out);
+
+}  // namespace gpulet

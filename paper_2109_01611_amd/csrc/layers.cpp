@@ -1,0 +1,103 @@
+// Single-layer entry points of the C ABI: argument checks, then a launch on
+// the caller's stream (paper Sec. 5: the executor runs the model's layers on
+// its gpu-let).
+#include "gpulet_internal.h"
+
+using namespace gpulet;
+
+namespace {
+
+gpulet_status make_conv_args(ConvArgs &a, const void *x, const void *w, const float *b, void *y,
+                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                             int relu, const void *residual, int y_ch_stride, int y_ch_offset) {
+    a.x = x; a.w = w; a.b = b; a.y = y; a.residual = residual;
+    a.N = N; a.C = C; a.H = H; a.W = W; a.K = K; a.R = R; a.S = S;
+    a.stride = stride; a.pad = pad; a.relu = relu ? 1 : 0;
+    a.y_ch_stride = y_ch_stride == 0 ? K : y_ch_stride;
+    a.y_ch_offset = y_ch_offset;
+    if (stride < 1 || R < 1 || S < 1 || pad < 0 || H < 1 || W < 1) return GPULET_EINVAL;
+    a.P = out_extent(H, R, stride, pad);
+    a.Q = out_extent(W, S, stride, pad);
+    return check_conv(a);
+}
+
+}  // namespace
+
+extern "C" gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b, void *y,
+                                              int N, int C, int H, int W, int K, int R, int S,
+                                              int stride, int pad, int relu, const void *residual,
+                                              int y_ch_stride, int y_ch_offset, void *stream) {
+    ConvArgs a;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual,
+                                      y_ch_stride, y_ch_offset);
+    if (st != GPULET_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv(a, stream_cu_count(s), s));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const float *b, void *y,
+                                           int N, int C, int H, int W, int K, int R, int S,
+                                           int stride, int pad, int relu, void *stream) {
+    return gpulet_conv2d_fwd_ex(x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, nullptr, 0, 0,
+                                stream);
+}
+
+extern "C" gpulet_status gpulet_set_conv_tile(int tile) {
+    if (tile < -1 || tile >= GPULET_CONV_TILES) return GPULET_EINVAL;
+    set_conv_tile(tile);
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_pool(const void *x, void *y, int N, int C, int H, int W, int mode,
+                                     int k, int stride, int pad, void *stream) {
+    if (!x || !y) return GPULET_EINVAL;
+    int P = 0, Q = 0;
+    gpulet_status st = check_pool(N, C, H, W, mode, k, stride, pad, &P, &Q);
+    if (st != GPULET_OK) return st;
+    GPULET_HIP(launch_pool(x, y, N, C, H, W, P, Q, mode, k, stride, pad, static_cast<hipStream_t>(stream)));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_fc(const void *x, const void *w, const float *b, void *y, int N,
+                                   int In, int Out, int relu, int out_fp32, void *stream) {
+    if (!x || !w || !y) return GPULET_EINVAL;
+    gpulet_status st = check_fc(N, In, Out);
+    if (st != GPULET_OK) return st;
+    GPULET_HIP(launch_fc(x, w, b, y, N, In, Out, relu ? 1 : 0, out_fp32 ? 1 : 0,
+                         static_cast<hipStream_t>(stream)));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_time_conv2d(const void *x, const void *w, const float *b, void *y,
+                                            int N, int C, int H, int W, int K, int R, int S,
+                                            int stride, int pad, int relu, const void *residual,
+                                            int y_ch_stride, int y_ch_offset, void *stream,
+                                            int warmup, int iters, float *avg_ms) {
+    if (!avg_ms || iters < 1 || warmup < 0) return GPULET_EINVAL;
+    ConvArgs a;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual,
+                                      y_ch_stride, y_ch_offset);
+    if (st != GPULET_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int n_cu = stream_cu_count(s);
+    for (int i = 0; i < warmup; ++i) GPULET_HIP(launch_conv(a, n_cu, s));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    GPULET_HIP(hipEventCreate(&e0));
+    hipError_t e = hipEventCreate(&e1);
+    if (e != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return hip_fail(e);
+    }
+    e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_conv(a, n_cu, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(e);
+    *avg_ms = ms / static_cast<float>(iters);
+    return GPULET_OK;
+}

@@ -1,0 +1,400 @@
+// Whole-model forward pass on a gpu-let, the L(b, p) latency profiler and the
+// two-gpu-let co-run measurement (paper Sec. 5 "Backend inference executor";
+// Sec. 3.1 / Fig. 3 and Sec. 4.1 for L(b, p); Sec. 3.2 / Fig. 6 for co-run
+// interference).
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cmath>
+#include <thread>
+#include <vector>
+
+#include "gpulet_internal.h"
+
+using namespace gpulet;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+struct BufState {
+    int C = 0, H = 0, W = 0, elem = 2;
+    bool written = false;
+    size_t bytes_per_image = 0;  // largest footprint over the buffer's lifetime
+};
+
+struct Step {
+    int op;
+    int in_buf, out_buf, res_buf;
+    ConvArgs conv;  // CONV
+    int N, C, H, W, P, Q, mode, k, stride, pad;  // POOL
+    int In, Out, relu, out_fp32;                 // FC
+    const void *w;
+    const float *b;
+};
+
+struct Plan {
+    std::vector<Step> steps;
+    std::vector<BufState> bufs;
+    std::vector<size_t> offset;  // workspace offset per buffer, (size_t)-1 for caller-owned
+    size_t ws_bytes = 0;
+    int in_buf = 0, out_buf = 0;
+};
+
+size_t round_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Shape inference and validation of a model description for `batch` images.
+gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
+    if (!m || !m->layers || m->n_layers < 1 || m->n_bufs < 2 || batch < 1) return GPULET_EINVAL;
+    if (m->in_C < 1 || m->in_H < 1 || m->in_W < 1) return GPULET_EINVAL;
+    if (m->in_buf < 0 || m->in_buf >= m->n_bufs || m->out_buf < 0 || m->out_buf >= m->n_bufs ||
+        m->in_buf == m->out_buf)
+        return GPULET_EINVAL;
+    if (1LL * batch * m->in_C * m->in_H * m->in_W >= (1LL << 31)) return GPULET_EINVAL;
+
+    plan.bufs.assign(static_cast<size_t>(m->n_bufs), BufState());
+    plan.steps.clear();
+    plan.in_buf = m->in_buf;
+    plan.out_buf = m->out_buf;
+    BufState &in = plan.bufs[static_cast<size_t>(m->in_buf)];
+    in.C = m->in_C; in.H = m->in_H; in.W = m->in_W; in.elem = 2; in.written = true;
+    in.bytes_per_image = 2ull * m->in_C * m->in_H * m->in_W;
+
+    for (int li = 0; li < m->n_layers; ++li) {
+        const gpulet_layer &L = m->layers[li];
+        if (L.in_buf < 0 || L.in_buf >= m->n_bufs || L.out_buf < 0 || L.out_buf >= m->n_bufs)
+            return GPULET_EINVAL;
+        if (L.out_buf == m->in_buf || L.in_buf == L.out_buf) return GPULET_EINVAL;
+        const BufState src = plan.bufs[static_cast<size_t>(L.in_buf)];
+        if (!src.written || src.elem != 2) return GPULET_EINVAL;
+        BufState &dst = plan.bufs[static_cast<size_t>(L.out_buf)];
+        Step s{};
+        s.op = L.op;
+        s.in_buf = L.in_buf;
+        s.out_buf = L.out_buf;
+        s.res_buf = -1;
+        s.w = L.w;
+        s.b = L.b;
+        int oc = 0, oh = 0, ow = 0, oelem = 2;
+        if (L.op == GPULET_OP_CONV) {
+            if (L.C != src.C || !L.w) return GPULET_EINVAL;
+            if (L.stride < 1 || L.R < 1 || L.S < 1 || L.pad < 0) return GPULET_EINVAL;
+            ConvArgs &a = s.conv;
+            a.x = nullptr; a.w = L.w; a.b = L.b; a.y = nullptr; a.residual = nullptr;
+            a.N = batch; a.C = L.C; a.H = src.H; a.W = src.W; a.K = L.K; a.R = L.R; a.S = L.S;
+            a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0;
+            a.P = out_extent(src.H, L.R, L.stride, L.pad);
+            a.Q = out_extent(src.W, L.S, L.stride, L.pad);
+            a.y_ch_stride = L.out_ch_total > 0 ? L.out_ch_total : L.K;
+            a.y_ch_offset = L.out_ch_total > 0 ? L.out_ch_offset : 0;
+            // Pointers are filled in at run time; validate the rest with stand-ins.
+            ConvArgs chk = a;
+            chk.x = chk.w = chk.y = &chk;
+            gpulet_status st = check_conv(chk);
+            if (st != GPULET_OK) return st;
+            if (L.res_buf >= 0) {
+                if (L.res_buf >= m->n_bufs) return GPULET_EINVAL;
+                const BufState &r = plan.bufs[static_cast<size_t>(L.res_buf)];
+                if (!r.written || r.elem != 2 || r.C != L.K || r.H != a.P || r.W != a.Q) return GPULET_EINVAL;
+                if (L.res_buf == L.out_buf && a.y_ch_stride != L.K) return GPULET_EINVAL;
+                s.res_buf = L.res_buf;
+            }
+            oc = a.y_ch_stride; oh = a.P; ow = a.Q;
+        } else if (L.op == GPULET_OP_POOL) {
+            if (L.C != src.C) return GPULET_EINVAL;
+            int P = 0, Q = 0;
+            gpulet_status st = check_pool(batch, src.C, src.H, src.W, L.mode, L.R, L.stride, L.pad, &P, &Q);
+            if (st != GPULET_OK) return st;
+            s.N = batch; s.C = src.C; s.H = src.H; s.W = src.W; s.P = P; s.Q = Q;
+            s.mode = L.mode; s.k = L.R; s.stride = L.stride; s.pad = L.pad;
+            oc = src.C; oh = P; ow = Q;
+        } else if (L.op == GPULET_OP_FC) {
+            if (!L.w || 1LL * src.C * src.H * src.W != L.C) return GPULET_EINVAL;
+            gpulet_status st = check_fc(batch, L.C, L.K);
+            if (st != GPULET_OK) return st;
+            s.N = batch; s.In = L.C; s.Out = L.K; s.relu = L.relu ? 1 : 0; s.out_fp32 = L.out_fp32 ? 1 : 0;
+            oc = L.K; oh = 1; ow = 1; oelem = L.out_fp32 ? 4 : 2;
+        } else {
+            return GPULET_EINVAL;
+        }
+        dst.C = oc; dst.H = oh; dst.W = ow; dst.elem = oelem; dst.written = true;
+        dst.bytes_per_image = std::max(dst.bytes_per_image, static_cast<size_t>(oelem) * oc * oh * ow);
+        plan.steps.push_back(s);
+    }
+    if (!plan.bufs[static_cast<size_t>(m->out_buf)].written) return GPULET_EINVAL;
+
+    plan.offset.assign(static_cast<size_t>(m->n_bufs), static_cast<size_t>(-1));
+    size_t off = 0;
+    for (int i = 0; i < m->n_bufs; ++i) {
+        if (i == m->in_buf || i == m->out_buf) continue;
+        plan.offset[static_cast<size_t>(i)] = off;
+        off += round_up(plan.bufs[static_cast<size_t>(i)].bytes_per_image * static_cast<size_t>(batch));
+    }
+    plan.ws_bytes = off;
+    return GPULET_OK;
+}
+
+struct Bound {
+    const Plan *plan;
+    const void *in;
+    void *out;
+    char *ws;
+    void *ptr(int buf) const {
+        if (buf == plan->in_buf) return const_cast<void *>(in);
+        if (buf == plan->out_buf) return out;
+        return ws + plan->offset[static_cast<size_t>(buf)];
+    }
+};
+
+// Enqueues every layer of one batch on `stream`; no host synchronisation.
+hipError_t enqueue(const Bound &bd, int n_cu, hipStream_t stream) {
+    for (const Step &s : bd.plan->steps) {
+        hipError_t e;
+        if (s.op == GPULET_OP_CONV) {
+            ConvArgs a = s.conv;
+            a.x = bd.ptr(s.in_buf);
+            a.y = bd.ptr(s.out_buf);
+            a.residual = s.res_buf >= 0 ? bd.ptr(s.res_buf) : nullptr;
+            e = launch_conv(a, n_cu, stream);
+        } else if (s.op == GPULET_OP_POOL) {
+            e = launch_pool(bd.ptr(s.in_buf), bd.ptr(s.out_buf), s.N, s.C, s.H, s.W, s.P, s.Q, s.mode, s.k,
+                            s.stride, s.pad, stream);
+        } else {
+            e = launch_fc(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.In, s.Out, s.relu, s.out_fp32,
+                          stream);
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+gpulet_status check_run_args(const Plan &plan, const void *in, void *out, void *ws, size_t ws_bytes) {
+    if (!in || !out) return GPULET_EINVAL;
+    if (plan.ws_bytes > 0) {
+        if (!ws) return GPULET_EINVAL;
+        if (ws_bytes < plan.ws_bytes) return GPULET_ENOMEM;
+        if (reinterpret_cast<uintptr_t>(ws) % kAlign != 0) return GPULET_EINVAL;
+    }
+    return GPULET_OK;
+}
+
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t create() {
+        hipError_t e = hipEventCreate(&a);
+        if (e != hipSuccess) return e;
+        e = hipEventCreate(&b);
+        if (e != hipSuccess) {
+            (void)hipEventDestroy(a);
+            a = nullptr;
+        }
+        return e;
+    }
+    ~EventPair() {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
+
+// One timed batch, waited for: returns its elapsed milliseconds.
+hipError_t timed_batch(const Bound &bd, gpulet_partition *p, int batch, EventPair &ev, float *ms) {
+    hipError_t e = hipEventRecord(ev.a, p->stream);
+    if (e == hipSuccess) e = enqueue(bd, p->n_cu, p->stream);
+    if (e == hipSuccess) e = hipEventRecord(ev.b, p->stream);
+    if (e == hipSuccess) e = hipEventSynchronize(ev.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(ms, ev.a, ev.b);
+    if (e == hipSuccess) {
+        p->batches_run.fetch_add(1);
+        p->images_run.fetch_add(static_cast<uint64_t>(batch));
+    }
+    return e;
+}
+
+}  // namespace
+
+extern "C" gpulet_status gpulet_model_workspace_bytes(const gpulet_model_desc *m, int batch,
+                                                      size_t *bytes) {
+    if (!bytes) return GPULET_EINVAL;
+    Plan plan;
+    gpulet_status st = build_plan(m, batch, plan);
+    if (st != GPULET_OK) return st;
+    *bytes = plan.ws_bytes;
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_model_buffer_info(const gpulet_model_desc *m, int batch, int buf,
+                                                  int *C, int *H, int *W, int *elem_bytes,
+                                                  size_t *ws_offset) {
+    Plan plan;
+    gpulet_status st = build_plan(m, batch, plan);
+    if (st != GPULET_OK) return st;
+    if (buf < 0 || buf >= m->n_bufs) return GPULET_EINVAL;
+    const BufState &b = plan.bufs[static_cast<size_t>(buf)];
+    if (!b.written) return GPULET_EINVAL;
+    if (C) *C = b.C;
+    if (H) *H = b.H;
+    if (W) *W = b.W;
+    if (elem_bytes) *elem_bytes = b.elem;
+    if (ws_offset) *ws_offset = plan.offset[static_cast<size_t>(buf)];
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_run_model(const gpulet_model_desc *m, int batch, gpulet_partition *p,
+                                          const void *in, void *out, void *workspace,
+                                          size_t workspace_bytes, float *latency_ms) {
+    if (!live(p)) return GPULET_EINVAL;
+    Plan plan;
+    gpulet_status st = build_plan(m, batch, plan);
+    if (st != GPULET_OK) return st;
+    st = check_run_args(plan, in, out, workspace, workspace_bytes);
+    if (st != GPULET_OK) return st;
+    const Bound bd{&plan, in, out, static_cast<char *>(workspace)};
+    if (latency_ms) {
+        EventPair ev;
+        GPULET_HIP(ev.create());
+        GPULET_HIP(timed_batch(bd, p, batch, ev, latency_ms));
+        return GPULET_OK;
+    }
+    GPULET_HIP(enqueue(bd, p->n_cu, p->stream));
+    p->batches_run.fetch_add(1);
+    p->images_run.fetch_add(static_cast<uint64_t>(batch));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int batch,
+                                              gpulet_partition *p, const void *in, void *out,
+                                              void *workspace, size_t workspace_bytes, int warmup,
+                                              int iters, int sync_each, float *latency_ms,
+                                              float *total_ms) {
+    if (!live(p) || !latency_ms || iters < 1 || warmup < 0) return GPULET_EINVAL;
+    Plan plan;
+    gpulet_status st = build_plan(m, batch, plan);
+    if (st != GPULET_OK) return st;
+    st = check_run_args(plan, in, out, workspace, workspace_bytes);
+    if (st != GPULET_OK) return st;
+    const Bound bd{&plan, in, out, static_cast<char *>(workspace)};
+
+    for (int i = 0; i < warmup; ++i) {
+        GPULET_HIP(enqueue(bd, p->n_cu, p->stream));
+        p->batches_run.fetch_add(1);
+        p->images_run.fetch_add(static_cast<uint64_t>(batch));
+    }
+    GPULET_HIP(hipStreamSynchronize(p->stream));
+
+    std::vector<EventPair> ev(static_cast<size_t>(iters));
+    for (EventPair &e : ev) GPULET_HIP(e.create());
+    for (int i = 0; i < iters; ++i) {
+        EventPair &e = ev[static_cast<size_t>(i)];
+        GPULET_HIP(hipEventRecord(e.a, p->stream));
+        GPULET_HIP(enqueue(bd, p->n_cu, p->stream));
+        GPULET_HIP(hipEventRecord(e.b, p->stream));
+        p->batches_run.fetch_add(1);
+        p->images_run.fetch_add(static_cast<uint64_t>(batch));
+        if (sync_each) GPULET_HIP(hipEventSynchronize(e.b));
+    }
+    GPULET_HIP(hipStreamSynchronize(p->stream));
+    for (int i = 0; i < iters; ++i)
+        GPULET_HIP(hipEventElapsedTime(&latency_ms[i], ev[static_cast<size_t>(i)].a, ev[static_cast<size_t>(i)].b));
+    if (total_ms) GPULET_HIP(hipEventElapsedTime(total_ms, ev.front().a, ev.back().b));
+    return GPULET_OK;
+}
+
+namespace {
+
+struct CorunSide {
+    const Plan *plan;
+    Bound bd;
+    gpulet_partition *p;
+    int batch, warmup, cap;
+    float *lat;
+    int n = 0;
+    gpulet_status status = GPULET_OK;
+    int hip_error = 0;
+};
+
+void corun_thread(CorunSide *s, std::atomic<int> *ready, double window_ms) {
+    auto fail = [&](hipError_t e) {
+        s->status = GPULET_EHIP;
+        s->hip_error = static_cast<int>(e);
+    };
+    hipError_t e = hipSetDevice(s->p->device);
+    EventPair ev;
+    if (e == hipSuccess) e = ev.create();
+    for (int i = 0; i < s->warmup && e == hipSuccess; ++i) {
+        float ms;
+        e = timed_batch(s->bd, s->p, s->batch, ev, &ms);
+    }
+    // Both sides start their timed window together; a side that failed still
+    // checks in so the other never waits forever.
+    ready->fetch_add(1);
+    while (ready->load() < 2) std::this_thread::yield();
+    if (e != hipSuccess) {
+        fail(e);
+        return;
+    }
+    const auto t0 = std::chrono::steady_clock::now();
+    for (;;) {
+        float ms = 0.f;
+        e = timed_batch(s->bd, s->p, s->batch, ev, &ms);
+        if (e != hipSuccess) {
+            fail(e);
+            return;
+        }
+        if (s->n < s->cap) s->lat[s->n] = ms;
+        ++s->n;
+        const double el = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        if (el >= window_ms) break;
+    }
+}
+
+}  // namespace
+
+extern "C" gpulet_status gpulet_profile_corun(
+    const gpulet_model_desc *ma, int batch_a, gpulet_partition *pa, const void *in_a, void *out_a,
+    void *ws_a, size_t ws_a_bytes, const gpulet_model_desc *mb, int batch_b, gpulet_partition *pb,
+    const void *in_b, void *out_b, void *ws_b, size_t ws_b_bytes, int warmup, double window_ms,
+    float *lat_a, int cap_a, int *n_a, float *lat_b, int cap_b, int *n_b) {
+    if (!live(pa) || !live(pb) || pa == pb || pa->device != pb->device) return GPULET_EINVAL;
+    if (!lat_a || !lat_b || !n_a || !n_b || cap_a < 1 || cap_b < 1 || warmup < 0 || !(window_ms > 0.0))
+        return GPULET_EINVAL;
+    Plan plan_a, plan_b;
+    gpulet_status st = build_plan(ma, batch_a, plan_a);
+    if (st != GPULET_OK) return st;
+    st = build_plan(mb, batch_b, plan_b);
+    if (st != GPULET_OK) return st;
+    st = check_run_args(plan_a, in_a, out_a, ws_a, ws_a_bytes);
+    if (st != GPULET_OK) return st;
+    st = check_run_args(plan_b, in_b, out_b, ws_b, ws_b_bytes);
+    if (st != GPULET_OK) return st;
+
+    CorunSide sa{&plan_a, Bound{&plan_a, in_a, out_a, static_cast<char *>(ws_a)}, pa, batch_a, warmup, cap_a, lat_a};
+    CorunSide sb{&plan_b, Bound{&plan_b, in_b, out_b, static_cast<char *>(ws_b)}, pb, batch_b, warmup, cap_b, lat_b};
+    std::atomic<int> ready{0};
+    std::thread ta(corun_thread, &sa, &ready, window_ms);
+    std::thread tb(corun_thread, &sb, &ready, window_ms);
+    ta.join();
+    tb.join();
+    *n_a = std::min(sa.n, cap_a);
+    *n_b = std::min(sb.n, cap_b);
+    if (sa.status != GPULET_OK) return hip_fail(static_cast<hipError_t>(sa.hip_error));
+    if (sb.status != GPULET_OK) return hip_fail(static_cast<hipError_t>(sb.hip_error));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_latency_stats(const float *latency_ms, int n, double *mean,
+                                              double *p50, double *p99) {
+    if (!latency_ms || n < 1) return GPULET_EINVAL;
+    std::vector<double> v(latency_ms, latency_ms + n);
+    std::sort(v.begin(), v.end());
+    double sum = 0.0;
+    for (double d : v) sum += d;
+    auto rank = [&](double pct) {
+        int r = static_cast<int>(std::ceil(pct / 100.0 * n));
+        r = std::max(1, std::min(n, r));
+        return v[static_cast<size_t>(r - 1)];
+    };
+    if (mean) *mean = sum / n;
+    if (p50) *p50 = rank(50.0);
+    if (p99) *p99 = rank(99.0);
+    return GPULET_OK;
+}

@@ -1,0 +1,194 @@
+"""Turns a ``workloads.Model`` table plus host weights into what
+``gpulet_run_model`` takes: device weights in the library's layouts and the
+flat ``gpulet_layer`` array over numbered activation buffers.
+
+Only marshalling happens here (layout permutations, buffer numbering, device
+copies); no layer is computed.  torch provides device memory.
+
+Layout conversions
+  * activations (N, C, H, W) -> NHWC bf16,
+  * convolution weights (K, C, R, S) -> KRSC bf16,
+  * FC weights whose input is a (C, H, W) feature map: columns go from the
+    channel-major flatten order to the NHWC one.
+
+Buffers are reused once their last reader has run, which keeps the working
+set small enough to stay in the last-level cache between layers.  A concat
+node costs nothing: its source convolutions store straight into channel
+slices of the concatenated buffer.
+"""
+
+import numpy as np
+import torch
+
+from . import gpulet
+
+
+def to_device_bf16(a, device):
+    """bfloat16-exact float32 numpy array -> torch bf16 tensor on ``device``."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=torch.bfloat16)
+
+
+def nchw_to_nhwc(x, device):
+    return to_device_bf16(np.transpose(x, (0, 2, 3, 1)), device)
+
+
+def nhwc_to_nchw(t):
+    """Device NHWC tensor -> float64 numpy (N, C, H, W)."""
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64).transpose(0, 3, 1, 2)
+
+
+def kcrs_to_krsc(w, device):
+    return to_device_bf16(np.transpose(w, (0, 2, 3, 1)), device)
+
+
+class DeviceModel:
+    """A model resident on the GPU, ready for ``run`` / ``profile`` on a gpu-let.
+    ``reuse=False`` gives every tensor its own buffer so intermediates can be
+    read back after a run."""
+
+    def __init__(self, model, params, device="cuda:0", reuse=True):
+        self.model = model
+        self.device = torch.device(device)
+        self.in_shape = tuple(model.in_shape)
+        self._keep = []  # device tensors the layer records point into
+        nodes = [nd for nd in model.nodes]
+
+        # channels of every named tensor, straight from the table
+        chans = {"x": model.in_shape[0]}
+        alias = {}  # concat source -> (concat tensor, channel offset, total channels)
+        for nd in nodes:
+            if nd.op == "conv":
+                chans[nd.dst] = nd.attr["K"]
+            elif nd.op in ("maxpool", "gavgpool"):
+                chans[nd.dst] = chans[nd.src]
+            elif nd.op == "fc":
+                chans[nd.dst] = nd.attr["Out"]
+            elif nd.op == "concat":
+                total = sum(chans[s] for s in nd.src)
+                off = 0
+                for s in nd.src:
+                    alias[s] = (nd.dst, off, total)
+                    off += chans[s]
+                chans[nd.dst] = total
+        producers = {nd.dst: nd for nd in nodes}
+        for s in alias:
+            if producers[s].op != "conv":
+                raise ValueError("concat source %r must be produced by a convolution" % s)
+
+        def storage(t):  # the tensor whose buffer holds t
+            return alias[t][0] if t in alias else t
+
+        # last node index at which each storage tensor is read
+        last_use = {}
+        for i, nd in enumerate(nodes):
+            reads = list(nd.src) if nd.op == "concat" else [nd.src]
+            if nd.op == "conv" and nd.attr["residual"]:
+                reads.append(nd.attr["residual"])
+            for t in reads:
+                last_use[storage(t)] = i
+        last_use[storage(model.out)] = len(nodes)
+
+        buf_of = {"x": 0, storage(model.out): 1}
+        free, n_bufs = [], 2
+        layers = []
+        self.tensor_buf = {}
+        for i, nd in enumerate(nodes):
+            if nd.op == "concat":
+                self.tensor_buf[nd.dst] = buf_of[nd.dst]
+                continue
+            st = storage(nd.dst)
+            if st not in buf_of:
+                if free:
+                    buf_of[st] = free.pop()
+                else:
+                    buf_of[st] = n_bufs
+                    n_bufs += 1
+            L = gpulet.Layer()
+            L.in_buf, L.out_buf, L.res_buf = buf_of[storage(nd.src)], buf_of[st], -1
+            if storage(nd.src) != nd.src:
+                raise ValueError("reading a concat slice on its own is not supported")
+            a = nd.attr
+            if nd.op == "conv":
+                w, b = params[nd.name]
+                wd = kcrs_to_krsc(w, self.device)
+                bd = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(self.device)
+                self._keep += [wd, bd]
+                L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, a["C"], a["K"], a["k"], a["k"]
+                L.stride, L.pad, L.relu = a["stride"], a["pad"], int(a["relu"])
+                if a["residual"]:
+                    L.res_buf = buf_of[storage(a["residual"])]
+                if nd.dst in alias:
+                    _, off, total = alias[nd.dst]
+                    L.out_ch_total, L.out_ch_offset = total, off
+                L.w, L.b = wd.data_ptr(), bd.data_ptr()
+            elif nd.op == "maxpool":
+                L.op, L.C, L.R, L.stride, L.pad = gpulet.OP_POOL, chans[nd.src], a["k"], a["stride"], a["pad"]
+                L.mode = gpulet.POOL_MAX
+            elif nd.op == "gavgpool":
+                L.op, L.C, L.R, L.stride, L.mode = gpulet.OP_POOL, chans[nd.src], 1, 1, gpulet.POOL_GLOBAL_AVG
+            elif nd.op == "fc":
+                w, b = params[nd.name]
+                C = chans[nd.src]
+                hw = a["In"] // C
+                if producers.get(nd.src) is not None and producers[nd.src].op != "fc" and hw > 1:
+                    w = np.asarray(w).reshape(a["Out"], C, hw).transpose(0, 2, 1).reshape(a["Out"], a["In"])
+                wd = to_device_bf16(w, self.device)
+                bd = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(self.device)
+                self._keep += [wd, bd]
+                L.op, L.C, L.K, L.relu = gpulet.OP_FC, a["In"], a["Out"], int(a["relu"])
+                L.out_fp32 = int(nd.dst == model.out)
+                L.w, L.b = wd.data_ptr(), bd.data_ptr()
+            else:
+                raise ValueError("unknown node kind %r" % (nd.op,))
+            layers.append(L)
+            self.tensor_buf[nd.dst] = buf_of[st]
+            # release buffers whose last reader was this node (never the input or output)
+            for t, last in list(last_use.items()):
+                if reuse and last == i and t in buf_of and buf_of[t] > 1:
+                    free.append(buf_of.pop(t))
+                    del last_use[t]
+
+        self.layers = (gpulet.Layer * len(layers))(*layers)
+        d = gpulet.ModelDesc()
+        d.n_layers, d.n_bufs = len(layers), n_bufs
+        d.in_C, d.in_H, d.in_W = self.in_shape
+        d.in_buf, d.out_buf = 0, 1
+        d.layers = self.layers
+        self.desc = d
+        self.out_fp32 = producers[model.out].op == "fc"
+        self._ws = {}
+
+    def output_shape(self, batch):
+        C, H, W, _, _ = gpulet.model_buffer_info(self.desc, batch, 1)
+        return (batch, H, W, C)
+
+    def workspace(self, batch):
+        """Device workspace for ``batch`` images -> (tensor, bytes)."""
+        if batch not in self._ws:
+            n = gpulet.model_workspace_bytes(self.desc, batch)
+            self._ws[batch] = (torch.empty(max(n, 256), dtype=torch.uint8, device=self.device), n)
+        return self._ws[batch]
+
+    def alloc_output(self, batch):
+        dt = torch.float32 if self.out_fp32 else torch.bfloat16
+        return torch.empty(self.output_shape(batch), dtype=dt, device=self.device)
+
+    def run(self, partition, x_nhwc, timed=False):
+        """Forward pass of one batch (device NHWC bf16) -> (output tensor, ms or None)."""
+        batch = x_nhwc.shape[0]
+        ws, n = self.workspace(batch)
+        y = self.alloc_output(batch)
+        torch.cuda.synchronize(self.device)
+        ms = gpulet.run_model(self.desc, batch, partition, x_nhwc, y, ws, n, timed=timed)
+        partition.sync()
+        return y, ms
+
+    def read_tensor(self, name, batch):
+        """Copy of a named intermediate tensor (NHWC) from the workspace after a run.
+        Only meaningful for tensors whose buffer was not reused later."""
+        buf = self.tensor_buf[name]
+        ws, _ = self.workspace(batch)
+        C, H, W, e, off = gpulet.model_buffer_info(self.desc, batch, buf)
+        n = batch * C * H * W * e
+        raw = ws[off:off + n]
+        return raw.view(torch.bfloat16 if e == 2 else torch.float32).reshape(batch, H, W, C).clone()

@@ -1,0 +1,208 @@
+"""Host-side checks that need no GPU: the shared library loads and exports
+every symbol the header declares, mask arithmetic and bookkeeping are exact,
+argument errors are reported before any GPU call, and the model description
+is validated with the shapes the tables imply."""
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2109_01611_amd import gpulet
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "gpulet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gpulet_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 20
+    raw = ctypes.CDLL(gpulet.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert set(names) == set(gpulet.EXPORTS)
+
+
+def test_status_strings():
+    for s, word in [(0, "OK"), (-1, "EINVAL"), (-2, "EOVERSUB"), (-3, "EHIP"), (-4, "ENOMEM"), (-99, "?")]:
+        assert word in gpulet.status_string(s)
+
+
+def _popcount(words):
+    return sum(bin(w).count("1") for w in words)
+
+
+@pytest.mark.parametrize("pct,n_cu", [(20, 48), (25, 64), (40, 104), (50, 128), (60, 152), (80, 208),
+                                      (100, 256), (1, 8), (99, 248)])
+def test_mask_sizes_on_256_cus(pct, n_cu):
+    words, n = gpulet.mask_for_pct(256, 8, pct, 0)
+    assert len(words) == 8 and n == n_cu and _popcount(words) == n_cu
+    # the first n/8 CUs of every die are the lowest n bits
+    as_int = sum(w << (32 * i) for i, w in enumerate(words))
+    assert as_int == (1 << n_cu) - 1
+
+
+@pytest.mark.parametrize("pct", [1, 20, 25, 33, 40, 50, 60, 75, 80, 99])
+def test_split_gives_disjoint_cover(pct):
+    a, na = gpulet.mask_for_pct(256, 8, pct, 0)
+    b, nb = gpulet.mask_for_pct(256, 8, 100 - pct, 1)
+    assert na + nb == 256
+    for x, y in zip(a, b):
+        assert x & y == 0 and (x | y) == 0xFFFFFFFF
+    # per-die symmetry: bit i is CU i // 8 of die i % 8
+    bits = [i for i in range(256) if (a[i // 32] >> (i % 32)) & 1]
+    per_die = [sum(1 for i in bits if i % 8 == d) for d in range(8)]
+    assert len(set(per_die)) == 1
+
+
+def test_two_partitions_never_overlap_when_sizes_fit():
+    for p in range(1, 100):
+        for q in range(1, 101 - p):
+            a, _ = gpulet.mask_for_pct(256, 8, p, 0)
+            b, _ = gpulet.mask_for_pct(256, 8, q, 1)
+            assert all(x & y == 0 for x, y in zip(a, b)), (p, q)
+
+
+def test_mask_other_geometries_and_errors():
+    words, n = gpulet.mask_for_pct(64, 1, 25, 0)
+    assert n == 16 and words == [0xFFFF, 0]
+    words, n = gpulet.mask_for_pct(64, 1, 75, 1)
+    assert n == 48 and words == [0xFFFF0000, 0xFFFFFFFF]
+    for args in [(256, 8, 0, 0), (256, 8, 101, 0), (256, 8, 50, 2), (255, 8, 50, 0), (0, 8, 50, 0), (256, 0, 50, 0)]:
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.mask_for_pct(*args)
+        assert e.value.status == gpulet.EINVAL
+    w = (ctypes.c_uint32 * 8)()
+    nw, nc = ctypes.c_int(), ctypes.c_int()
+    assert gpulet.lib.gpulet_mask_for_pct(256, 8, 50, 0, w, 4, ctypes.byref(nw), ctypes.byref(nc)) == gpulet.ENOMEM
+    assert gpulet.lib.gpulet_mask_for_pct(256, 8, 50, 0, None, 8, ctypes.byref(nw), ctypes.byref(nc)) == gpulet.EINVAL
+
+
+def test_latency_stats_nearest_rank():
+    lat = [float(v) for v in range(1, 201)]          # 1..200
+    rng = np.random.default_rng(0)
+    rng.shuffle(lat)
+    mean, p50, p99 = gpulet.latency_stats(lat)
+    assert mean == 100.5 and p50 == 100.0 and p99 == 198.0   # ceil(0.99*200) = 198
+    assert gpulet.latency_stats([3.0]) == (3.0, 3.0, 3.0)
+    assert gpulet.latency_stats([1.0, 2.0])[1:] == (1.0, 2.0)
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.latency_stats([])
+
+
+def test_layer_calls_reject_bad_arguments_before_touching_the_gpu():
+    x = w = y = 4096  # stand-in non-NULL addresses; never dereferenced on these paths
+    ok = dict(N=1, C=8, H=8, W=8, K=8, R=3, S=3, stride=1, pad=1, relu=1)
+    bad = [dict(ok, N=0), dict(ok, C=-1), dict(ok, stride=0), dict(ok, pad=-1), dict(ok, R=0),
+           dict(ok, H=2, pad=0, R=5, S=5),                 # empty output
+           dict(ok, N=1 << 20, H=64, W=64, C=64)]          # 2^38 elements
+    for kw in bad:
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.conv2d_fwd(x, w, None, y, **kw)
+        assert e.value.status == gpulet.EINVAL, kw
+    for args in [(None, w, None, y), (x, None, None, y), (x, w, None, None)]:
+        with pytest.raises(gpulet.GpuletError):
+            gpulet.conv2d_fwd(*args, **ok)
+    with pytest.raises(gpulet.GpuletError):   # slice does not fit the destination
+        gpulet.conv2d_fwd_ex(x, w, None, y, residual=None, y_ch_stride=12, y_ch_offset=8, **ok)
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.pool(x, y, 1, 8, 8, 8, gpulet.POOL_MAX, k=2, stride=2, pad=2)    # pad >= k
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.pool(x, y, 1, 8, 8, 8, 7, k=2, stride=2, pad=0)                  # unknown mode
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.pool(None, y, 1, 8, 8, 8, gpulet.POOL_MAX, k=2, stride=2, pad=0)
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.fc(x, w, None, y, 0, 8, 8, relu=0)
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.fc(x, w, None, y, 1 << 16, 1 << 16, 8, relu=0)
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.Partition(0, 0)
+    assert e.value.status == gpulet.EINVAL
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.Partition(0, 50, which=3)
+    assert e.value.status == gpulet.EINVAL
+    assert gpulet.lib.gpulet_partition_destroy(None) == gpulet.EINVAL
+    assert gpulet.lib.gpulet_partition_destroy(ctypes.c_void_p(12345)) == gpulet.EINVAL
+
+
+def _layer(**kw):
+    L = gpulet.Layer()
+    L.res_buf = -1
+    for k, v in kw.items():
+        setattr(L, k, v)
+    return L
+
+
+def _desc(layers, n_bufs, in_shape, in_buf=0, out_buf=1):
+    arr = (gpulet.Layer * len(layers))(*layers)
+    d = gpulet.ModelDesc()
+    d.n_layers, d.n_bufs = len(layers), n_bufs
+    d.in_C, d.in_H, d.in_W = in_shape
+    d.in_buf, d.out_buf = in_buf, out_buf
+    d.layers = arr
+    d._arr = arr
+    return d
+
+
+def test_model_shape_inference_and_workspace_layout():
+    W = 4096  # stand-in weight address
+    layers = [
+        _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=16, R=7, S=7, stride=2, pad=3, relu=1, w=W),
+        _layer(op=gpulet.OP_POOL, in_buf=2, out_buf=3, C=16, R=3, stride=2, pad=1, mode=gpulet.POOL_MAX),
+        # two branches concatenated into buffer 4 (8 + 24 channels)
+        _layer(op=gpulet.OP_CONV, in_buf=3, out_buf=4, C=16, K=8, R=1, S=1, stride=1, pad=0, relu=1, w=W,
+               out_ch_total=32, out_ch_offset=0),
+        _layer(op=gpulet.OP_CONV, in_buf=3, out_buf=4, C=16, K=24, R=3, S=3, stride=1, pad=1, relu=1, w=W,
+               out_ch_total=32, out_ch_offset=8),
+        _layer(op=gpulet.OP_CONV, in_buf=4, out_buf=2, C=32, K=32, R=1, S=1, stride=1, pad=0, relu=1, w=W,
+               res_buf=4),
+        _layer(op=gpulet.OP_POOL, in_buf=2, out_buf=3, C=32, R=1, stride=1, mode=gpulet.POOL_GLOBAL_AVG),
+        _layer(op=gpulet.OP_FC, in_buf=3, out_buf=1, C=32, K=10, out_fp32=1, w=W),
+    ]
+    d = _desc(layers, 5, (3, 64, 64))
+    batch = 4
+    # buffer 2: conv out 16x32x32 (32 KiB/img in bf16), later 32x16x16 (16 KiB) -> 32 KiB
+    # buffer 3: pool out 16x16x16 (8 KiB), later 32x1x1 -> 8 KiB;  buffer 4: 32x16x16 -> 16 KiB
+    assert gpulet.model_workspace_bytes(d, batch) == batch * (32768 + 8192 + 16384)
+    assert gpulet.model_buffer_info(d, batch, 4) == (32, 16, 16, 2, batch * (32768 + 8192))
+    assert gpulet.model_buffer_info(d, batch, 2) == (32, 16, 16, 2, 0)
+    assert gpulet.model_buffer_info(d, batch, 1) == (10, 1, 1, 4, None)
+    assert gpulet.model_buffer_info(d, batch, 0) == (3, 64, 64, 2, None)
+    # odd sizes round every buffer up to 256 bytes
+    d1 = _desc([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=1, K=3, R=3, S=3, stride=1, pad=0, w=W),
+                _layer(op=gpulet.OP_POOL, in_buf=2, out_buf=1, C=3, R=1, stride=1, mode=gpulet.POOL_GLOBAL_AVG)],
+               3, (1, 5, 5))
+    assert gpulet.model_workspace_bytes(d1, 1) == 256       # 3*3*3*2 = 54 bytes -> 256
+
+
+def test_model_description_errors():
+    W = 4096
+    good = _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)
+    assert gpulet.model_workspace_bytes(_desc([good], 2, (3, 8, 8)), 2) == 0
+
+    def bad(layers, n_bufs=3, in_shape=(3, 8, 8), batch=1, **kw):
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.model_workspace_bytes(_desc(layers, n_bufs, in_shape, **kw), batch)
+        assert e.value.status == gpulet.EINVAL
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=4, K=8, R=3, S=3, stride=1, pad=1, w=W)])  # C mismatch
+    bad([_layer(op=gpulet.OP_CONV, in_buf=2, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)])  # read before write
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=0, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)])  # writes the input
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=5, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)])  # bad index
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=None)])  # no weights
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)])  # output never written
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=9, S=9, stride=1, pad=0, w=W)], in_shape=(3, 8, 8))
+    bad([_layer(op=gpulet.OP_FC, in_buf=0, out_buf=1, C=100, K=8, w=W)])                             # In != C*H*W
+    bad([_layer(op=9, in_buf=0, out_buf=1)])
+    bad([good], batch=0)
+    bad([good], in_buf=1, out_buf=1)
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])
+    # residual of the wrong shape
+    bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=2, pad=1, w=W),
+         _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])

@@ -1,0 +1,175 @@
+"""Parity of the single-layer HIP entry points against the fp64 oracle, element
+by element on the same seeded tensors: tiny and ragged shapes, every tile,
+strides, paddings, residual and channel-slice stores, plus the benchmark's
+layer at full size on several gpu-let sizes."""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2109_01611_amd import gpulet, inputs, lowering
+
+from gpu_util import DEV, LAYER_TOL, conv_tensors, gpu_conv
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def part():
+    p = gpulet.Partition(0, 100, 0)
+    yield p
+    p.destroy()
+
+
+# N, C, H, W, K, R, stride, pad
+CONV_CASES = [
+    (1, 3, 7, 7, 5, 3, 1, 1),          # everything smaller than a tile, C not a multiple of 8
+    (2, 1, 28, 28, 6, 5, 1, 2),        # LeNet conv1
+    (2, 6, 14, 14, 16, 5, 1, 0),       # LeNet conv2
+    (2, 3, 33, 31, 64, 7, 2, 3),       # stem-like, odd image
+    (3, 8, 9, 9, 8, 1, 1, 0),
+    (2, 16, 10, 10, 24, 1, 2, 0),      # strided 1x1 (projection shortcut)
+    (2, 24, 13, 13, 40, 3, 2, 1),
+    (1, 48, 7, 7, 128, 5, 1, 2),       # inception 5x5
+    (1, 136, 5, 5, 72, 3, 1, 1),       # depth 1224: ragged last slice, K not a multiple of 32
+    (1, 8, 4, 4, 8, 3, 1, 3),          # padding wider than the kernel reach
+    (2, 64, 56, 56, 64, 3, 1, 1),      # several tiles, M = 6272
+    (1, 512, 7, 7, 520, 1, 1, 0),      # M = 49, ragged K
+    (5, 32, 12, 11, 96, 3, 1, 1),      # M = 660: ragged last pixel tile
+    (2, 20, 9, 9, 12, 3, 1, 1),        # C multiple of 4 only
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_parity_every_tile(part, case):
+    N, C, H, W, K, R, stride, pad = case
+    x, w, b = conv_tensors(11, N, C, H, W, K, R)
+    ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
+    first = None
+    for tile in range(-1, 6):
+        got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
+        whole, per_img = oracle.rel_err(got, ref)
+        assert max(whole, per_img) <= LAYER_TOL, (tile, whole, per_img)
+        if first is None:
+            first = raw.clone()
+        else:  # the accumulation order does not depend on the tile
+            assert torch.equal(raw, first), tile
+
+
+def test_conv_is_deterministic(part):
+    x, w, b = conv_tensors(12, 4, 64, 28, 28, 96, 3)
+    _, r0 = gpu_conv(part, x, w, b, 1, 1, True)
+    for _ in range(3):
+        _, r = gpu_conv(part, x, w, b, 1, 1, True)
+        assert torch.equal(r, r0)
+
+
+def test_conv_no_bias_no_relu_and_zero_input(part):
+    x, w, b = conv_tensors(13, 2, 16, 8, 8, 32, 3)
+    got, _ = gpu_conv(part, x, w, None, 1, 1, False)
+    ref = oracle.conv2d(x, w, None, 1, 1, False)
+    assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+    assert (got < 0).any()
+    got, _ = gpu_conv(part, np.zeros_like(x), w, b, 1, 1, False)
+    want = inputs.bf16_round(b)[None, :, None, None] * np.ones_like(got)
+    assert np.array_equal(got, want)
+
+
+def test_conv_delta_kernel_copies_input_exactly(part):
+    C = 16
+    x = inputs.tensor(14, "delta", (2, C, 9, 9), "normal")
+    w = np.zeros((C, C, 3, 3), dtype=np.float32)
+    for c in range(C):
+        w[c, c, 1, 1] = 1.0
+    got, _ = gpu_conv(part, x, w, None, 1, 1, False)
+    assert np.array_equal(got, x.astype(np.float64))
+
+
+@pytest.mark.parametrize("tile", [-1, 0, 3, 4])
+def test_conv_residual_and_channel_slice(part, tile):
+    N, C, H, W, K, R = 2, 32, 10, 10, 40, 3
+    x, w, b = conv_tensors(15, N, C, H, W, K, R)
+    res = inputs.tensor(15, "res", (N, K, H, W), "normal")
+    ref = oracle.conv2d(x, w, b, 1, 1, True, residual=res)
+    got, _ = gpu_conv(part, x, w, b, 1, 1, True, residual=res, tile=tile)
+    assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+    # store into channels 24..63 of an 72-channel tensor; the rest stays untouched
+    got, raw = gpu_conv(part, x, w, b, 1, 1, True, residual=res, ch_total=72, ch_offset=24, tile=tile)
+    assert oracle.rel_err(got[:, 24:64], ref)[1] <= LAYER_TOL
+    assert np.all(got[:, :24] == -512.0) and np.all(got[:, 64:] == -512.0)
+
+
+# N, C, H, W, mode, k, stride, pad
+POOL_CASES = [
+    (2, 6, 28, 28, gpulet.POOL_MAX, 2, 2, 0), (2, 16, 10, 10, gpulet.POOL_MAX, 2, 2, 0),
+    (2, 64, 17, 15, gpulet.POOL_MAX, 3, 2, 1), (1, 24, 9, 9, gpulet.POOL_MAX, 3, 1, 1),
+    (3, 5, 7, 7, gpulet.POOL_MAX, 3, 2, 1), (2, 40, 8, 8, gpulet.POOL_AVG, 2, 2, 0),
+    (2, 7, 9, 9, gpulet.POOL_AVG, 3, 2, 1), (4, 2048, 7, 7, gpulet.POOL_GLOBAL_AVG, 1, 1, 0),
+    (3, 1000, 5, 3, gpulet.POOL_GLOBAL_AVG, 1, 1, 0), (2, 13, 6, 6, gpulet.POOL_GLOBAL_AVG, 1, 1, 0),
+    (1, 8, 1, 1, gpulet.POOL_GLOBAL_AVG, 1, 1, 0), (1, 1024, 7, 7, gpulet.POOL_GLOBAL_AVG, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_pool_parity(part, case):
+    N, C, H, W, mode, k, stride, pad = case
+    x = inputs.tensor(21, "pool%d_%d_%d" % (C, H, mode), (N, C, H, W), "normal")
+    if mode == gpulet.POOL_GLOBAL_AVG:
+        ref = oracle.global_avgpool(x).reshape(N, C, 1, 1)
+    elif mode == gpulet.POOL_MAX:
+        ref = oracle.maxpool(x, k, stride, pad)
+    else:
+        ref = oracle.avgpool(x, k, stride, pad)
+    P, Q = ref.shape[2:]
+    xd = lowering.nchw_to_nhwc(x, DEV)
+    yd = torch.full((N, P, Q, C), -512.0, dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    gpulet.pool(xd, yd, N, C, H, W, mode, k, stride, pad, part.stream)
+    part.sync()
+    got = lowering.nhwc_to_nchw(yd)
+    if mode == gpulet.POOL_MAX:
+        assert np.array_equal(got, ref)            # a max of bf16 values is exact
+    else:
+        assert np.max(np.abs(got - ref)) <= 2.0 ** -8 * np.max(np.abs(ref)) + 1e-30
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+
+
+# N, In, Out
+FC_CASES = [(32, 400, 120), (32, 120, 84), (32, 84, 10), (1, 2048, 1000), (8, 1024, 1000),
+            (33, 72, 17), (5, 8, 3), (40, 4096, 1000), (16, 25088, 64), (2, 100, 7)]
+
+
+@pytest.mark.parametrize("case", FC_CASES, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("out_fp32", [False, True])
+def test_fc_parity(part, case, out_fp32):
+    N, In, Out = case
+    x = inputs.tensor(31, "fcx%d_%d" % (N, In), (N, In), "normal")
+    w = inputs.he_normal(31, "fcw%d_%d" % (In, Out), (Out, In))
+    b = inputs.bias(31, "fcb%d" % Out, Out)
+    relu = not out_fp32
+    ref = oracle.fc(x, w, b, relu)
+    xd, wd = lowering.to_device_bf16(x, DEV), lowering.to_device_bf16(w, DEV)
+    bd = torch.from_numpy(b).to(DEV)
+    yd = torch.full((N, Out), -512.0, dtype=torch.float32 if out_fp32 else torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    gpulet.fc(xd, wd, bd, yd, N, In, Out, relu, out_fp32, part.stream)
+    part.sync()
+    got = yd.to(torch.float32).cpu().numpy().astype(np.float64)
+    tol = 1e-5 if out_fp32 else LAYER_TOL       # fp32 output: accumulation error only
+    assert oracle.rel_err(got, ref)[1] <= tol
+
+
+def test_full_size_vgg_fc6(part):
+    # FC 25088 -> 4096 at batch 16: the weight-streaming case
+    N, In, Out = 16, 25088, 4096
+    x = inputs.tensor(32, "fc6x", (N, In), "uniform")
+    w = inputs.he_normal(32, "fc6w", (Out, In))
+    b = inputs.bias(32, "fc6b", Out)
+    ref = oracle.fc(x, w, b, True)
+    xd, wd, bd = lowering.to_device_bf16(x, DEV), lowering.to_device_bf16(w, DEV), torch.from_numpy(b).to(DEV)
+    yd = torch.empty((N, Out), dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    gpulet.fc(xd, wd, bd, yd, N, In, Out, True, False, part.stream)
+    part.sync()
+    assert oracle.rel_err(yd.to(torch.float32).cpu().numpy(), ref)[1] <= LAYER_TOL

@@ -1,0 +1,140 @@
+"""Whole-model parity: gpulet_run_model on a gpu-let against the fp64 oracle's
+forward pass of the same table, same seeded weights and inputs.  Small
+variants exercise every wiring element quickly; the full shapes run at a
+batch the oracle finishes in seconds, and at the serving batch sizes on
+sampled images (images of a batch are independent)."""
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2109_01611_amd import gpulet, lowering, workloads
+
+from gpu_util import DEV, LAYER_TOL, MODEL_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(model, batch, pct=100, which=0, seed=0, reuse=True, images=None):
+    params = workloads.parameters(model, seed)
+    x = workloads.batch_input(model, batch, seed)
+    dm = lowering.DeviceModel(model, params, DEV, reuse=reuse)
+    with gpulet.Partition(0, pct, which) as p:
+        y, ms = dm.run(p, lowering.nchw_to_nhwc(x, DEV), timed=True)
+        assert ms > 0
+        assert p.counters() == (1, batch)
+    got = y.to(torch.float32).cpu().numpy().astype(np.float64).reshape(batch, -1)
+    sel = list(range(batch)) if images is None else images
+    ref = oracle.run_model(model, params, x[sel]).reshape(len(sel), -1)
+    return got, ref, sel, dm, params, x
+
+
+def _assert_close(got, ref, tol=MODEL_TOL):
+    whole, per_img = oracle.rel_err(got, ref)
+    assert np.all(np.isfinite(got))
+    assert max(whole, per_img) <= tol, (whole, per_img)
+
+
+def test_lenet5_batch32_full_gpu():
+    got, ref, _, _, _, _ = _run(workloads.lenet5(), 32)
+    assert got.shape == (32, 10)
+    _assert_close(got, ref)
+
+
+@pytest.mark.parametrize("pct,which", [(20, 0), (50, 1)])
+def test_lenet5_on_small_gpulets(pct, which):
+    got, ref, _, _, _, _ = _run(workloads.lenet5(), 5, pct, which)
+    _assert_close(got, ref)
+
+
+@pytest.mark.parametrize("model", [
+    workloads.resnet50(width_div=4, in_hw=64, n_class=20, blocks=(2, 2, 2, 2)),
+    workloads.googlenet(width_div=2, in_hw=64, n_class=20),
+    workloads.vgg16(width_div=8, in_hw=64, n_class=20),
+], ids=lambda m: m.name)
+def test_small_variants(model):
+    got, ref, _, _, _, _ = _run(model, 3, seed=5)
+    _assert_close(got, ref)
+
+
+def test_per_layer_parity_on_actual_inputs():
+    # Feed the oracle each layer's actual (bf16) device input and compare that layer alone:
+    # separates kernel error from the compounding of roundings through the model.
+    model = workloads.resnet50(width_div=4, in_hw=64, n_class=20, blocks=(1, 2, 1, 1))
+    batch = 2
+    _, _, _, dm, params, x = _run(model, batch, seed=6, reuse=False)
+    t = {"x": x.astype(np.float64)}
+    for nd in model.nodes:
+        a = nd.attr
+        if nd.op == "fc":
+            continue  # the output buffer is the caller's, checked by the whole-model tests
+        dev = dm.read_tensor(nd.dst, batch)
+        got = dev.to(torch.float32).cpu().numpy().astype(np.float64).transpose(0, 3, 1, 2)
+        src = t[nd.src]
+        if nd.op == "conv":
+            w, b = params[nd.name]
+            ref = oracle.conv2d(src, w, b, a["stride"], a["pad"], a["relu"],
+                                t[a["residual"]] if a["residual"] else None)
+        elif nd.op == "maxpool":
+            ref = oracle.maxpool(src, a["k"], a["stride"], a["pad"])
+        elif nd.op == "gavgpool":
+            ref = oracle.global_avgpool(src).reshape(batch, -1, 1, 1)
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL, nd.name
+        t[nd.dst] = got  # the next layer's oracle input is what the device really produced
+
+
+def test_resnet50_full_shape_batch2():
+    got, ref, _, _, _, _ = _run(workloads.resnet50(), 2)
+    assert got.shape == (2, 1000)
+    _assert_close(got, ref)
+
+
+def test_googlenet_full_shape_batch2_half_gpu():
+    got, ref, _, _, _, _ = _run(workloads.googlenet(), 2, 50, 1)
+    _assert_close(got, ref)
+
+
+def test_vgg16_full_shape_batch1():
+    got, ref, _, _, _, _ = _run(workloads.vgg16(), 1)
+    _assert_close(got, ref)
+
+
+@pytest.mark.parametrize("name,batch,pct,which", [("resnet50", 32, 100, 0), ("resnet50", 8, 25, 0),
+                                                  ("googlenet", 32, 50, 1), ("vgg16", 16, 50, 0)])
+def test_serving_batch_sizes_on_sampled_images(name, batch, pct, which):
+    model = getattr(workloads, name)()
+    images = [0, batch - 1]
+    got, ref, sel, _, _, _ = _run(model, batch, pct, which, images=images)
+    _assert_close(got[sel], ref)
+    # every image of the batch produced finite, distinct logits
+    assert np.all(np.isfinite(got))
+    assert len({got[i].tobytes() for i in range(batch)}) == batch
+
+
+def test_batch_size_does_not_change_an_images_result():
+    model = workloads.resnet50(width_div=2, in_hw=96, n_class=50)
+    a, _, _, _, _, _ = _run(model, 2, seed=7, images=[0])
+    b, _, _, _, _, _ = _run(model, 9, 40, 0, seed=7, images=[0])
+    assert np.array_equal(a[:2], b[:2])
+
+
+def test_corun_two_gpulets_gives_same_results_and_counts():
+    ma, mb = workloads.resnet50(width_div=4, in_hw=64, n_class=20), workloads.googlenet(width_div=4, in_hw=64, n_class=20)
+    pa_, pb_ = workloads.parameters(ma, 8), workloads.parameters(mb, 8)
+    xa, xb = workloads.batch_input(ma, 4, 8), workloads.batch_input(mb, 6, 8)
+    da, db = lowering.DeviceModel(ma, pa_, DEV), lowering.DeviceModel(mb, pb_, DEV)
+    xad, xbd = lowering.nchw_to_nhwc(xa, DEV), lowering.nchw_to_nhwc(xb, DEV)
+    ya, yb = da.alloc_output(4), db.alloc_output(6)
+    (wsa, na), (wsb, nb) = da.workspace(4), db.workspace(6)
+    torch.cuda.synchronize()
+    with gpulet.Partition(0, 50, 0) as p0, gpulet.Partition(0, 50, 1) as p1:
+        la, lb = gpulet.profile_corun((da.desc, 4, p0, xad, ya, wsa, na), (db.desc, 6, p1, xbd, yb, wsb, nb),
+                                      warmup=2, window_ms=200.0)
+        assert len(la) >= 1 and len(lb) >= 1 and min(la) > 0 and min(lb) > 0
+        assert p0.counters() == (2 + len(la), 4 * (2 + len(la)))
+        assert p1.counters() == (2 + len(lb), 6 * (2 + len(lb)))
+        with pytest.raises(gpulet.GpuletError):
+            gpulet.profile_corun((da.desc, 4, p0, xad, ya, wsa, na), (db.desc, 6, p0, xbd, yb, wsb, nb), 1, 10.0)
+    _assert_close(ya.cpu().numpy().astype(np.float64).reshape(4, -1), oracle.run_model(ma, pa_, xa))
+    _assert_close(yb.cpu().numpy().astype(np.float64).reshape(6, -1), oracle.run_model(mb, pb_, xb))

@@ -1,0 +1,104 @@
+"""gpu-let bookkeeping on the real device: masks honoured by the hardware,
+Split partners disjoint, over-subscription refused, request counters exact."""
+
+import collections
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2109_01611_amd import gpulet
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _placement(part, n_blocks=8192):
+    out = torch.zeros(2 * n_blocks, dtype=torch.int32, device=DEV)
+    torch.cuda.synchronize()
+    part.probe(out, n_blocks)
+    o = out.cpu().numpy().astype(np.uint32).reshape(n_blocks, 2)
+    xcc = o[:, 0] & 0xF
+    # hardware id register: CU in bits 8..11, shader array bit 12, shader engine bits 13..15
+    phys = (o[:, 1] >> 8) & 0xFF
+    return set(zip(xcc.tolist(), phys.tolist()))
+
+
+def _popcount(words):
+    return sum(bin(w).count("1") for w in words)
+
+
+@pytest.mark.parametrize("pct", [20, 40, 50, 60, 80])
+def test_split_partners_run_on_disjoint_cus(pct):
+    with gpulet.Partition(0, pct, 0) as a, gpulet.Partition(0, 100 - pct, 1) as b:
+        assert a.n_cu_total == b.n_cu_total == 256
+        assert a.n_cu + b.n_cu == 256
+        assert _popcount(a.mask) == a.n_cu and _popcount(b.mask) == b.n_cu
+        assert all(x & y == 0 for x, y in zip(a.mask, b.mask))
+        assert a.query_mask() == a.mask and b.query_mask() == b.mask
+        pa, pb = _placement(a), _placement(b)
+        assert len(pa) == a.n_cu and len(pb) == b.n_cu
+        assert not (pa & pb)
+        # the same number of CUs in every die
+        for pl, part in ((pa, a), (pb, b)):
+            per_die = collections.Counter(x for x, _ in pl)
+            assert sorted(per_die) == list(range(8))
+            assert set(per_die.values()) == {part.n_cu // 8}
+
+
+def test_sizes_and_full_gpu():
+    want = {20: 48, 25: 64, 40: 104, 50: 128, 60: 152, 80: 208, 100: 256}
+    for pct, n_cu in want.items():
+        with gpulet.Partition(0, pct, 0) as p:
+            assert (p.pct, p.which, p.n_cu, p.device) == (pct, 0, n_cu, 0)
+            assert p.stream
+    with gpulet.Partition(0, 100, 0) as p:
+        assert len(_placement(p)) == 256
+
+
+def test_oversubscription_and_handle_errors():
+    a = gpulet.Partition(0, 60, 0)
+    try:
+        for pct, which in [(50, 1), (40, 0), (60, 1)]:     # >100%, same side, >100%
+            with pytest.raises(gpulet.GpuletError) as e:
+                gpulet.Partition(0, pct, which)
+            assert e.value.status == gpulet.EOVERSUB
+        b = gpulet.Partition(0, 40, 1)
+        with pytest.raises(gpulet.GpuletError) as e:       # a third gpu-let
+            gpulet.Partition(0, 1, 0)
+        assert e.value.status == gpulet.EOVERSUB
+        h = b.handle
+        b.destroy()
+        assert gpulet.lib.gpulet_partition_destroy(h) == gpulet.EINVAL   # second destroy
+        assert gpulet.lib.gpulet_partition_sync(h) == gpulet.EINVAL
+        c = gpulet.Partition(0, 40, 1)                      # the share is free again
+        c.destroy()
+    finally:
+        a.destroy()
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.Partition(7, 50, 0)                          # no such device
+
+
+def test_request_counters_are_exact():
+    from paper_2109_01611_amd import lowering, workloads
+    m = workloads.lenet5()
+    dm = lowering.DeviceModel(m, workloads.parameters(m, 0), DEV)
+    with gpulet.Partition(0, 50, 0) as p:
+        assert p.counters() == (0, 0)
+        total = 0
+        for i, batch in enumerate([1, 7, 32, 5], 1):
+            x = lowering.nchw_to_nhwc(workloads.batch_input(m, batch, 0), DEV)
+            dm.run(p, x)
+            total += batch
+            assert p.counters() == (i, total)
+        x = lowering.nchw_to_nhwc(workloads.batch_input(m, 4, 0), DEV)
+        ws, n = dm.workspace(4)
+        y = dm.alloc_output(4)
+        torch.cuda.synchronize()
+        lat, tot = gpulet.profile_model(dm.desc, 4, p, x, y, ws, n, warmup=3, iters=10)
+        assert len(lat) == 10 and all(v > 0 for v in lat) and tot >= max(lat)
+        assert p.counters() == (4 + 13, total + 13 * 4)
+        with pytest.raises(gpulet.GpuletError) as e:        # workspace too small
+            gpulet.run_model(dm.desc, 4, p, x, y, ws, n - 1)
+        assert e.value.status == gpulet.ENOMEM
+        assert p.counters() == (17, total + 52)
