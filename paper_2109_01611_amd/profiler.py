@@ -1,0 +1,200 @@
+"""Offline profiler: the L(b, p) latency table and co-run interference.
+
+The paper's scheduler consumes, per model, the profiled latency of batch b on
+a gpu-let of size p (Sec. 4.1; Table 2; Fig. 3 sweeps batch 1-32 over 20-100%)
+and the slowdown two co-located gpu-lets inflict on each other (Sec. 3.2,
+Fig. 6).  This module drives the library's profiling calls and writes the
+rows; all timing happens inside ``libgpulet.so`` with HIP events on the
+gpu-let's stream.
+
+Run ``python -m paper_2109_01611_amd.profiler --help`` for the command line.
+"""
+
+import argparse
+import json
+import os
+import sys
+import tempfile
+
+from . import gpulet, lowering, workloads
+
+# Dense bf16 MFMA peak of one MI355X compute unit: 2.5 PFLOP/s over 256 CUs.
+PEAK_TFLOPS_PER_CU = 2500.0 / 256.0
+
+
+def _extent(n, k, stride, pad):
+    return (n + 2 * pad - k) // stride + 1
+
+
+def model_flops(model):
+    """2 * multiply-adds of one image (padding taps counted) as (conv, fc)."""
+    shape = {"x": tuple(model.in_shape)}
+    conv = fc = 0
+    for nd in model.nodes:
+        a = nd.attr
+        if nd.op == "conv":
+            C, H, W = shape[nd.src]
+            P, Q = _extent(H, a["k"], a["stride"], a["pad"]), _extent(W, a["k"], a["stride"], a["pad"])
+            conv += 2 * P * Q * a["K"] * C * a["k"] * a["k"]
+            shape[nd.dst] = (a["K"], P, Q)
+        elif nd.op == "maxpool":
+            C, H, W = shape[nd.src]
+            shape[nd.dst] = (C, _extent(H, a["k"], a["stride"], a["pad"]), _extent(W, a["k"], a["stride"], a["pad"]))
+        elif nd.op == "gavgpool":
+            shape[nd.dst] = (shape[nd.src][0], 1, 1)
+        elif nd.op == "fc":
+            fc += 2 * a["In"] * a["Out"]
+            shape[nd.dst] = (a["Out"], 1, 1)
+        elif nd.op == "concat":
+            parts = [shape[s] for s in nd.src]
+            shape[nd.dst] = (sum(p[0] for p in parts),) + parts[0][1:]
+    return conv, fc
+
+
+def mask_hex(words):
+    return "".join("%08x" % w for w in reversed(words))
+
+
+class Bound:
+    """A device model with input, output and workspace for one batch size."""
+
+    def __init__(self, dm, batch, seed=0):
+        self.dm, self.batch = dm, batch
+        self.x = lowering.nchw_to_nhwc(workloads.batch_input(dm.model, batch, seed), dm.device)
+        self.y = dm.alloc_output(batch)
+        self.ws, self.ws_bytes = dm.workspace(batch)
+
+    def args(self, part):
+        return (self.dm.desc, self.batch, part, self.x, self.y, self.ws, self.ws_bytes)
+
+
+def measure(bound, part, warmup=20, iters=200, sync_each=True):
+    """One row of the L(b, p) table for ``bound`` on gpu-let ``part``."""
+    import torch
+    torch.cuda.synchronize()
+    lat, _ = gpulet.profile_model(*bound.args(part), warmup=warmup, iters=iters, sync_each=sync_each)
+    mean, p50, p99 = gpulet.latency_stats(lat)
+    # throughput with batches enqueued back to back (no host wait in between)
+    n_tp = max(10, iters // 4)
+    _, total = gpulet.profile_model(*bound.args(part), warmup=2, iters=n_tp, sync_each=False)
+    conv, fc = model_flops(bound.dm.model)
+    flops = (conv + fc) * bound.batch
+    tp_ms = total / n_tp
+    tflops = flops / (tp_ms * 1e-3) / 1e12
+    return {
+        "model": bound.dm.model.name, "batch": bound.batch, "pct": part.pct, "which": part.which,
+        "n_cu": part.n_cu, "mask": mask_hex(part.mask), "iters": iters,
+        "mean_ms": mean, "p50_ms": p50, "p99_ms": p99,
+        "images_per_s": bound.batch / (tp_ms * 1e-3), "ms_per_batch_back_to_back": tp_ms,
+        "tflops": tflops, "mfma_frac_of_masked_peak": tflops / (part.n_cu * PEAK_TFLOPS_PER_CU),
+    }
+
+
+def sweep(model, batches, pcts, seed=0, warmup=20, iters=200, device="cuda:0", log=None):
+    """L(b, p) rows of one model over batch sizes and gpu-let sizes."""
+    dm = lowering.DeviceModel(model, workloads.parameters(model, seed), device)
+    rows = []
+    for b in batches:
+        bound = Bound(dm, b, seed)
+        for pct in pcts:
+            with gpulet.Partition(0, pct, 0) as part:
+                row = measure(bound, part, warmup, iters)
+            rows.append(row)
+            if log:
+                log("%(model)s b=%(batch)d p=%(pct)d%% (%(n_cu)d CUs): mean %(mean_ms).3f ms  p99 %(p99_ms).3f ms  "
+                    "%(images_per_s).0f img/s  %(tflops).1f TFLOP/s  %(mfma_frac_of_masked_peak).3f of masked peak"
+                    % row)
+    return rows
+
+
+def corun(model_a, batch_a, model_b, batch_b, pct_a=50, seed=0, warmup=5, window_ms=2000.0, device="cuda:0"):
+    """Two gpu-lets at once: model A on ``pct_a``, model B on the Split partner.
+    Returns per-model alone and co-run latency statistics and the slowdown
+    (median co-run latency over median alone latency on the same mask)."""
+    import torch
+    da = lowering.DeviceModel(model_a, workloads.parameters(model_a, seed), device)
+    db = lowering.DeviceModel(model_b, workloads.parameters(model_b, seed), device)
+    ba, bb = Bound(da, batch_a, seed), Bound(db, batch_b, seed)
+    out = {}
+    with gpulet.Partition(0, pct_a, 0) as pa, gpulet.Partition(0, 100 - pct_a, 1) as pb:
+        torch.cuda.synchronize()
+        n_alone = 50
+        alone = {}
+        for key, bd, part in (("a", ba, pa), ("b", bb, pb)):
+            lat, _ = gpulet.profile_model(*bd.args(part), warmup=warmup, iters=n_alone, sync_each=True)
+            alone[key] = gpulet.latency_stats(lat)
+        la, lb = gpulet.profile_corun(ba.args(pa), bb.args(pb), warmup, window_ms)
+        for key, bd, part, lat in (("a", ba, pa, la), ("b", bb, pb, lb)):
+            mean, p50, p99 = gpulet.latency_stats(lat)
+            am, a50, a99 = alone[key]
+            out[key] = {
+                "model": bd.dm.model.name, "batch": bd.batch, "pct": part.pct, "n_cu": part.n_cu,
+                "mask": mask_hex(part.mask), "alone_p50_ms": a50, "alone_p99_ms": a99, "alone_mean_ms": am,
+                "corun_batches": len(lat), "corun_p50_ms": p50, "corun_p99_ms": p99, "corun_mean_ms": mean,
+                "slowdown_p50": p50 / a50, "slowdown_p99": p99 / a99,
+            }
+    return out
+
+
+def write_atomic(path, text):
+    """Writes ``text`` to ``path`` through a temporary file and a rename, so a
+    killed sweep never leaves a half-written table."""
+    d = os.path.dirname(os.path.abspath(path))
+    os.makedirs(d, exist_ok=True)
+    fd, tmp = tempfile.mkstemp(dir=d, prefix=".tmp_table_")
+    with os.fdopen(fd, "w") as fh:
+        fh.write(text)
+    os.replace(tmp, path)
+
+
+COLUMNS = ["model", "batch", "pct", "n_cu", "mask", "iters", "mean_ms", "p50_ms", "p99_ms", "images_per_s",
+           "tflops", "mfma_frac_of_masked_peak"]
+
+
+def table_csv(rows):
+    lines = [",".join(COLUMNS)]
+    for r in rows:
+        lines.append(",".join(("%.6g" % r[c]) if isinstance(r[c], float) else str(r[c]) for c in COLUMNS))
+    return "\n".join(lines) + "\n"
+
+
+CONFIGS = {
+    "lenet5": (workloads.lenet5, [32], [100]),
+    "conv": (workloads.single_conv, [32], [20, 40, 50, 60, 80, 100]),
+    "resnet50": (workloads.resnet50, [1, 8, 32], [25, 50, 100]),
+    "vgg16": (workloads.vgg16, [16], [50, 100]),
+    "googlenet": (workloads.googlenet, [32], [50, 100]),
+}
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description="L(b, p) latency table and co-run interference on one MI355X")
+    ap.add_argument("--config", default="conv", choices=sorted(CONFIGS) + ["corun", "all"])
+    ap.add_argument("--iters", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--window-ms", type=float, default=2000.0)
+    ap.add_argument("--out", default=None, help="CSV (or JSON for corun) path; default prints only")
+    args = ap.parse_args(argv)
+    log = lambda s: print(s, flush=True)
+    names = sorted(CONFIGS) if args.config == "all" else [args.config]
+    rows = []
+    for name in names:
+        if name == "corun":
+            continue
+        make, batches, pcts = CONFIGS[name]
+        rows += sweep(make(), batches, pcts, warmup=args.warmup, iters=args.iters, log=log)
+        if args.out:
+            write_atomic(args.out, table_csv(rows))
+    if args.config in ("corun", "all"):
+        res = corun(workloads.resnet50(), 16, workloads.googlenet(), 32, 50, window_ms=args.window_ms)
+        for k in ("a", "b"):
+            log("corun %(model)s b=%(batch)d on %(n_cu)d CUs: alone p50 %(alone_p50_ms).3f ms, co-run p50 "
+                "%(corun_p50_ms).3f ms (x%(slowdown_p50).3f), p99 x%(slowdown_p99).3f, %(corun_batches)d batches"
+                % res[k])
+        if args.out:
+            write_atomic(os.path.splitext(args.out)[0] + "_corun.json", json.dumps(res, indent=1) + "\n")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
