@@ -139,7 +139,7 @@ gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_b
  * and P = (H + 2*pad - R) / stride + 1, Q likewise from W and S.
  * x: N*H*W*C bf16, w: K*R*S*C bf16, b: K fp32 (NULL = no bias), y: N*P*Q*K bf16.
  * Errors: GPULET_EINVAL for NULL x/w/y, non-positive sizes, pad < 0, empty
- * output, or any tensor of 2^31 or more elements.
+ * output, or any tensor of 2^30 or more elements (byte offsets are 32-bit).
  */
 gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const float *b, void *y, int N,
                                 int C, int H, int W, int K, int R, int S, int stride, int pad,

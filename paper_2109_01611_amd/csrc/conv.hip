@@ -10,13 +10,17 @@
 //
 // One workgroup of four wavefronts owns a BM x BN output tile and walks the
 // depth in slices of 64.  Each slice is gathered from global memory as 16-byte
-// chunks (8 channels of one tap; zero for padding taps and ragged edges) into
-// a double-buffered, XOR-swizzled LDS tile; the next slice's loads are issued
-// before the MFMAs of the current one.  Wavefronts read 8-element fragments
-// back with ds_read_b128 and feed v_mfma_f32_32x32x16_bf16; accumulators stay
+// chunks (8 channels of one tap) with buffer loads whose hardware range check
+// returns zeros for padding taps and ragged edges, so the gather is branch
+// free.  Chunks pass through a two-slice-deep register pipeline into a
+// double-buffered, XOR-swizzled LDS tile; wavefronts read 8-element fragments
+// back with ds_read_b128 and feed v_mfma_f32_32x32x16_bf16.  Accumulators stay
 // in registers for the whole depth.  The epilogue adds bias and the optional
 // residual in fp32, applies ReLU, rounds once to bf16 and stores, optionally
 // at a channel offset inside a wider (concatenated) tensor.
+//
+// Channel counts that are not multiples of 8 (image stems, LeNet) take a
+// scalar-gather variant of the same tiling.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -28,10 +32,13 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-constexpr int BK = 64;        // depth slice per main-loop step (elements)
-constexpr int CHUNK = 8;      // elements per 16-byte chunk
-constexpr int NTHREADS = 256; // four wavefronts
+constexpr int BK = 64;         // depth slice per main-loop step (elements)
+constexpr int CHUNK = 8;       // elements per 16-byte chunk
+constexpr int NTHREADS = 256;  // four wavefronts
+constexpr unsigned OOB = 0x80000000u;      // byte offset past every buffer: the load returns zeros
+constexpr int RSRC_FLAGS = 0x00020000;     // raw buffer descriptor, 32-bit data format
 
 struct ConvParams {
     const __bf16 *x, *w;
@@ -42,6 +49,7 @@ struct ConvParams {
     int M, Kg;          // GEMM rows and depth
     int ldy, y_off;     // channels per output pixel of the destination, first channel
     int tiles_n, n_tiles, tiles_per_xcd;
+    unsigned x_bytes, w_bytes;
 };
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
@@ -51,9 +59,44 @@ __device__ __forceinline__ int lds_pos(int row, int chunk) {
     return row * BK + ((chunk ^ ((row >> 1) & 7)) * CHUNK);
 }
 
-__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
+// Workgroups are dealt round-robin to the eight dies, each with its own L2.
+// Give every die a contiguous run of tiles so that tiles sharing a pixel block
+// (all their channel tiles) hit the same L2.
+__device__ __forceinline__ int tile_of_block(const ConvParams &p) {
+    return (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+}
 
-template <int BM, int BN, int WGM, int WGN, bool VEC>
+// Epilogue shared by both kernels.  Accumulator register v of a lane holds row
+// 8*(v/4) + 4*(lane/32) + v%4 and column lane%32 of its 32x32 tile.
+template <int MT, int NT>
+__device__ __forceinline__ void store_tile(const ConvParams &p, const f32x16 (&acc)[MT][NT], int m_base,
+                                           int n_base, int lane) {
+    const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int k = n_base + j * 32 + frow;
+        if (k >= p.K) continue;
+        const float bias = p.b ? p.b[k] : 0.f;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m_base + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
+                if (m >= p.M) continue;
+                float val = acc[i][j][v] + bias;
+                if (p.res) val += static_cast<float>(p.res[m * p.K + k]);
+                if (p.relu) val = val > 0.f ? val : 0.f;
+                p.y[m * p.ldy + p.y_off + k] = static_cast<__bf16>(val);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Main kernel: C % 8 == 0.  POINTWISE = 1x1 filter without padding (no bounds
+// tests at all; a strided 1x1 is pointwise too).
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, bool POINTWISE>
 __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p) {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int WM = BM / WGM, WN = BN / WGN;  // wavefront tile
@@ -64,10 +107,7 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
     __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM * BK];
     __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN * BK];
 
-    // Workgroups are dealt round-robin to the eight dies, each with its own L2.
-    // Give every die a contiguous run of tiles so that tiles sharing a pixel
-    // block (all their channel tiles) hit the same L2.
-    const int tile = (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+    const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
     const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
@@ -76,11 +116,18 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
     const int lane = tid & 63, wave = tid >> 6;
     const int wy = wave / WGN, wx = wave - wy * WGN;
 
+    const __amdgpu_buffer_rsrc_t rx =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(p.x), 0, static_cast<int>(p.x_bytes), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rw =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(p.w), 0, static_cast<int>(p.w_bytes), RSRC_FLAGS);
+
     // ---- staging roles: this thread always carries depth chunk `cc` of rows lrow + 32*i
     const int cc = tid & 7;
     const int lrow = tid >> 3;
 
-    int a_base[AROWS], a_h0[AROWS], a_w0[AROWS];
+    // Byte offset of tap (0, 0), channel 0 of each pixel row (may be negative before
+    // the tap offset is added), and the pixel's top-left corner for the bounds tests.
+    int a_off[AROWS], a_h0[AROWS], a_w0[AROWS];
 #pragma unroll
     for (int i = 0; i < AROWS; ++i) {
         const int m = m0 + lrow + 32 * i;
@@ -90,92 +137,74 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
             const int pp = pq / p.Q, qq = pq - pp * p.Q;
             a_h0[i] = pp * p.stride - p.pad;
             a_w0[i] = qq * p.stride - p.pad;
-            a_base[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C;
+            a_off[i] = (((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C) * 2;
         } else {
-            a_h0[i] = -(1 << 28);  // fails every bounds test below
+            a_h0[i] = -(1 << 28);  // fails every bounds test
             a_w0[i] = -(1 << 28);
-            a_base[i] = 0;
+            a_off[i] = static_cast<int>(OOB);
         }
     }
-    int b_base[BROWS];
-    bool b_ok[BROWS];
+    unsigned b_off[BROWS];
 #pragma unroll
     for (int i = 0; i < BROWS; ++i) {
         const int k = n0 + lrow + 32 * i;
-        b_ok[i] = k < p.K;
-        b_base[i] = (b_ok[i] ? k : 0) * p.Kg;
+        b_off[i] = k < p.K ? static_cast<unsigned>((k * p.Kg + cc * CHUNK) * 2) : OOB;
     }
 
-    uint4 ra[AROWS], rb[BROWS];
-
-    // Gathers depth slice `kt` into registers.
-    auto load_slice = [&](int kt) {
-        const int g0 = kt * BK + cc * CHUNK;
-        if (VEC) {
-            // C % 8 == 0: the 8 elements of a chunk are 8 channels of one tap.
-            const int rs = g0 / p.C;
-            const int c = g0 - rs * p.C;
-            const int r = rs / p.S, s = rs - r * p.S;
-            const bool g_ok = g0 < p.Kg;
-            const int tap = (r * p.W + s) * p.C + c;
-#pragma unroll
-            for (int i = 0; i < AROWS; ++i) {
-                const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
-                                (unsigned)(a_w0[i] + s) < (unsigned)p.W;
-                ra[i] = ok ? *reinterpret_cast<const uint4 *>(p.x + (a_base[i] + tap)) : zero4();
+    // Depth position of the chunk this thread gathers next: element index g, its
+    // filter tap (r, s), channel c, and the tap's byte offset inside the image.
+    // Advancing s by one and c by -C leaves the address unchanged (a filter row
+    // covers a contiguous span of the image row), so the offset only jumps when
+    // the filter moves to its next row.
+    int g = cc * CHUNK, r = 0, s = 0, c = cc * CHUNK, tap = cc * CHUNK * 2;
+    auto normalise = [&]() {
+        while (c >= p.C) {
+            c -= p.C;
+            if (++s == p.S) {
+                s = 0;
+                ++r;
+                tap += (p.W - p.S) * p.C * 2;
             }
-#pragma unroll
-            for (int i = 0; i < BROWS; ++i)
-                rb[i] = (g_ok && b_ok[i]) ? *reinterpret_cast<const uint4 *>(p.w + (b_base[i] + g0))
-                                          : zero4();
-        } else {
-            // Any C: every element is decoded on its own.
-            int rs = g0 / p.C;
-            int c = g0 - rs * p.C;
-            int r = rs / p.S, s = rs - r * p.S;
-            unsigned short ea[AROWS][CHUNK], eb[BROWS][CHUNK];
-#pragma unroll
-            for (int e = 0; e < CHUNK; ++e) {
-                const bool g_ok = g0 + e < p.Kg;
-                const int tap = (r * p.W + s) * p.C + c;
-#pragma unroll
-                for (int i = 0; i < AROWS; ++i) {
-                    const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
-                                    (unsigned)(a_w0[i] + s) < (unsigned)p.W;
-                    ea[i][e] = ok ? reinterpret_cast<const unsigned short *>(p.x)[a_base[i] + tap]
-                                  : (unsigned short)0;
-                }
-#pragma unroll
-                for (int i = 0; i < BROWS; ++i)
-                    eb[i][e] = (g_ok && b_ok[i])
-                                   ? reinterpret_cast<const unsigned short *>(p.w)[b_base[i] + g0 + e]
-                                   : (unsigned short)0;
-                if (++c == p.C) {
-                    c = 0;
-                    if (++s == p.S) {
-                        s = 0;
-                        ++r;
-                    }
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < AROWS; ++i)
-                ra[i] = make_uint4(ea[i][0] | ((unsigned)ea[i][1] << 16), ea[i][2] | ((unsigned)ea[i][3] << 16),
-                                   ea[i][4] | ((unsigned)ea[i][5] << 16), ea[i][6] | ((unsigned)ea[i][7] << 16));
-#pragma unroll
-            for (int i = 0; i < BROWS; ++i)
-                rb[i] = make_uint4(eb[i][0] | ((unsigned)eb[i][1] << 16), eb[i][2] | ((unsigned)eb[i][3] << 16),
-                                   eb[i][4] | ((unsigned)eb[i][5] << 16), eb[i][6] | ((unsigned)eb[i][7] << 16));
         }
     };
+    if (!POINTWISE) normalise();
 
-    auto store_slice = [&](int buf) {
+    // Two register sets: slice j+1 waits in one while slice j+2 is still in flight in the other.
+    u32x4 ra0[AROWS], rb0[BROWS], ra1[AROWS], rb1[BROWS];
+
+    // Issues the gather of the next depth slice into a register set and advances the position.
+    auto load_next = [&](u32x4 (&ra)[AROWS], u32x4 (&rb)[BROWS]) {
+        const bool g_ok = g < p.Kg;
+#pragma unroll
+        for (int i = 0; i < AROWS; ++i) {
+            unsigned off;
+            if (POINTWISE) {
+                off = g_ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
+            } else {
+                const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
+                                (unsigned)(a_w0[i] + s) < (unsigned)p.W;
+                off = ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
+            }
+            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, static_cast<int>(off), 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < BROWS; ++i) {
+            const unsigned off = g_ok ? b_off[i] + static_cast<unsigned>(g - cc * CHUNK) * 2u : OOB;
+            rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, static_cast<int>(off), 0, 0);
+        }
+        g += BK;
+        c += BK;
+        tap += BK * 2;
+        if (!POINTWISE) normalise();
+    };
+
+    auto store_slice = [&](int buf, const u32x4 (&ra)[AROWS], const u32x4 (&rb)[BROWS]) {
 #pragma unroll
         for (int i = 0; i < AROWS; ++i)
-            *reinterpret_cast<uint4 *>(&sA[buf][lds_pos(lrow + 32 * i, cc)]) = ra[i];
+            *reinterpret_cast<u32x4 *>(&sA[buf][lds_pos(lrow + 32 * i, cc)]) = ra[i];
 #pragma unroll
         for (int i = 0; i < BROWS; ++i)
-            *reinterpret_cast<uint4 *>(&sB[buf][lds_pos(lrow + 32 * i, cc)]) = rb[i];
+            *reinterpret_cast<u32x4 *>(&sB[buf][lds_pos(lrow + 32 * i, cc)]) = rb[i];
     };
 
     f32x16 acc[MT][NT];
@@ -187,16 +216,10 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = (p.Kg + BK - 1) / BK;
-    const int frow = lane & 31;  // row of an MFMA operand this lane supplies
-    const int fhalf = lane >> 5; // which 8 of the 16 depth elements of a step
+    const int frow = lane & 31;   // row of an MFMA operand this lane supplies
+    const int fhalf = lane >> 5;  // which 8 of the 16 depth elements of a step
 
-    load_slice(0);
-    store_slice(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_slice(kt + 1);
+    auto compute_slice = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[MT], fb[NT];
@@ -214,30 +237,171 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
                 for (int j = 0; j < NT; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
+    };
+
+    // Software pipeline, two slices deep: while slice j is multiplied out of LDS
+    // buffer j&1, slice j+1 sits in a register set and slice j+2 is still in
+    // flight.  After the MFMAs of slice j, slice j+1 goes to the other LDS buffer
+    // and the gather of slice j+3 is issued into the freed set.  Gathers past the
+    // end of the depth return zeros and are never multiplied.
+    load_next(ra0, rb0);
+    store_slice(0, ra0, rb0);
+    load_next(ra1, rb1);
+    load_next(ra0, rb0);
+    __syncthreads();
+
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+        compute_slice(0);
+        store_slice(1, ra1, rb1);
+        load_next(ra1, rb1);
+        __syncthreads();
+        compute_slice(1);
+        store_slice(0, ra0, rb0);
+        load_next(ra0, rb0);
+        __syncthreads();
+    }
+    if (kt < nk) compute_slice(0);
+
+    store_tile<MT, NT>(p, acc, m0 + wy * WM, n0 + wx * WN, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Any channel count: every element of a chunk is decoded and loaded on its own.
+// Used by the image stems (C = 3) and LeNet (C = 1, 6); one slice of prefetch.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(NTHREADS) void conv_igemm_any_kernel(const ConvParams p) {
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int AROWS = BM / 32, BROWS = BN / 32;
+
+    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM * BK];
+    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN * BK];
+
+    const int tile = tile_of_block(p);
+    if (tile >= p.n_tiles) return;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wy = wave / WGN, wx = wave - wy * WGN;
+    const int cc = tid & 7;
+    const int lrow = tid >> 3;
+
+    int a_base[AROWS], a_h0[AROWS], a_w0[AROWS];
+#pragma unroll
+    for (int i = 0; i < AROWS; ++i) {
+        const int m = m0 + lrow + 32 * i;
+        if (m < p.M) {
+            const int n = m / (p.P * p.Q);
+            const int pq = m - n * (p.P * p.Q);
+            const int pp = pq / p.Q, qq = pq - pp * p.Q;
+            a_h0[i] = pp * p.stride - p.pad;
+            a_w0[i] = qq * p.stride - p.pad;
+            a_base[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C;
+        } else {
+            a_h0[i] = -(1 << 28);
+            a_w0[i] = -(1 << 28);
+            a_base[i] = 0;
+        }
+    }
+    int b_base[BROWS];
+    bool b_ok[BROWS];
+#pragma unroll
+    for (int i = 0; i < BROWS; ++i) {
+        const int k = n0 + lrow + 32 * i;
+        b_ok[i] = k < p.K;
+        b_base[i] = (b_ok[i] ? k : 0) * p.Kg;
+    }
+
+    uint4 ra[AROWS], rb[BROWS];
+    const unsigned short *xs = reinterpret_cast<const unsigned short *>(p.x);
+    const unsigned short *ws = reinterpret_cast<const unsigned short *>(p.w);
+
+    auto load_slice = [&](int kt) {
+        const int g0 = kt * BK + cc * CHUNK;
+        int rs = g0 / p.C;
+        int c = g0 - rs * p.C;
+        int r = rs / p.S, s = rs - r * p.S;
+        unsigned short ea[AROWS][CHUNK], eb[BROWS][CHUNK];
+#pragma unroll
+        for (int e = 0; e < CHUNK; ++e) {
+            const bool g_ok = g0 + e < p.Kg;
+            const int tap = (r * p.W + s) * p.C + c;
+#pragma unroll
+            for (int i = 0; i < AROWS; ++i) {
+                const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
+                                (unsigned)(a_w0[i] + s) < (unsigned)p.W;
+                ea[i][e] = ok ? xs[a_base[i] + tap] : (unsigned short)0;
+            }
+#pragma unroll
+            for (int i = 0; i < BROWS; ++i)
+                eb[i][e] = (g_ok && b_ok[i]) ? ws[b_base[i] + g0 + e] : (unsigned short)0;
+            if (++c == p.C) {
+                c = 0;
+                if (++s == p.S) {
+                    s = 0;
+                    ++r;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < AROWS; ++i)
+            ra[i] = make_uint4(ea[i][0] | ((unsigned)ea[i][1] << 16), ea[i][2] | ((unsigned)ea[i][3] << 16),
+                               ea[i][4] | ((unsigned)ea[i][5] << 16), ea[i][6] | ((unsigned)ea[i][7] << 16));
+#pragma unroll
+        for (int i = 0; i < BROWS; ++i)
+            rb[i] = make_uint4(eb[i][0] | ((unsigned)eb[i][1] << 16), eb[i][2] | ((unsigned)eb[i][3] << 16),
+                               eb[i][4] | ((unsigned)eb[i][5] << 16), eb[i][6] | ((unsigned)eb[i][7] << 16));
+    };
+
+    auto store_slice = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < AROWS; ++i) *reinterpret_cast<uint4 *>(&sA[buf][lds_pos(lrow + 32 * i, cc)]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < BROWS; ++i) *reinterpret_cast<uint4 *>(&sB[buf][lds_pos(lrow + 32 * i, cc)]) = rb[i];
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = (p.Kg + BK - 1) / BK;
+    const int frow = lane & 31, fhalf = lane >> 5;
+
+    load_slice(0);
+    store_slice(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_slice(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[MT], fb[NT];
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8 *>(&sA[buf][lds_pos(wy * WM + i * 32 + frow, ks * 2 + fhalf)]);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8 *>(&sB[buf][lds_pos(wx * WN + j * 32 + frow, ks * 2 + fhalf)]);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
         if (kt + 1 < nk) store_slice(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue.  Accumulator register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4
-    // and column lane%32 of the 32x32 tile.
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int k = n0 + wx * WN + j * 32 + frow;
-        if (k >= p.K) continue;
-        const float bias = p.b ? p.b[k] : 0.f;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wy * WM + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
-                if (m >= p.M) continue;
-                float val = acc[i][j][v] + bias;
-                if (p.res) val += static_cast<float>(p.res[m * p.K + k]);
-                if (p.relu) val = val > 0.f ? val : 0.f;
-                p.y[m * p.ldy + p.y_off + k] = static_cast<__bf16>(val);
-            }
-        }
-    }
+    store_tile<MT, NT>(p, acc, m0 + wy * WM, n0 + wx * WN, lane);
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -247,10 +411,13 @@ hipError_t launch_tile(ConvParams p, bool vec, hipStream_t stream) {
     p.n_tiles = tiles_m * p.tiles_n;
     p.tiles_per_xcd = (p.n_tiles + 7) / 8;
     const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8));
-    if (vec)
+    const bool pointwise = p.R == 1 && p.S == 1 && p.pad == 0;
+    if (vec && pointwise)
         hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, WGM, WGN, true>), grid, dim3(NTHREADS), 0, stream, p);
-    else
+    else if (vec)
         hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, WGM, WGN, false>), grid, dim3(NTHREADS), 0, stream, p);
+    else
+        hipLaunchKernelGGL((conv_igemm_any_kernel<BM, BN, WGM, WGN>), grid, dim3(NTHREADS), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -270,13 +437,14 @@ gpulet_status check_conv(const ConvArgs &a) {
         return GPULET_EINVAL;
     if (a.P < 1 || a.Q < 1) return GPULET_EINVAL;
     if (a.y_ch_offset < 0 || a.y_ch_offset + a.K > a.y_ch_stride) return GPULET_EINVAL;
-    const long long lim = 1LL << 31;
+    // Byte offsets are 32-bit with the top bit reserved as the out-of-range marker.
+    const long long lim = 1LL << 30;
     const long long xe = 1LL * a.N * a.H * a.W * a.C;
     const long long we = 1LL * a.K * a.R * a.S * a.C;
     const long long ye = 1LL * a.N * a.P * a.Q * a.y_ch_stride;
-    // The gather indexes from (h, w) = (-pad, -pad); keep that offset inside int32 too.
-    const long long slack = (1LL * a.pad * a.W + a.pad + a.R * 1LL * a.W + a.S) * a.C;
-    if (xe + slack >= lim || we >= lim || ye >= lim) return GPULET_EINVAL;
+    // The gather indexes from (h, w) = (-pad, -pad) and may step past the last tap.
+    const long long slack = (1LL * (a.pad + a.R) * a.W + a.pad + a.S) * a.C + 64;
+    if (xe + slack >= lim || we + 64 >= lim || ye >= lim) return GPULET_EINVAL;
     return GPULET_OK;
 }
 
@@ -294,6 +462,8 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
     p.ldy = a.y_ch_stride;
     p.y_off = a.y_ch_offset;
     p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
+    p.x_bytes = static_cast<unsigned>(2LL * a.N * a.H * a.W * a.C);
+    p.w_bytes = static_cast<unsigned>(2LL * a.K * a.R * a.S * a.C);
 
     const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
