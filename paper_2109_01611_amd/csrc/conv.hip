@@ -95,17 +95,59 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, const f32x16 (&a
 // ---------------------------------------------------------------------------
 // Main kernel: C % 8 == 0.  POINTWISE = 1x1 filter without padding (no bounds
 // tests at all; a strided 1x1 is pointwise too).
+//
+// Staging uses buffer loads that write straight into LDS (no registers, no
+// ds_write): one wavefront instruction moves 64 x 16 bytes into a contiguous
+// 1 KB span = 8 tile rows of 128 bytes, lane i landing at byte 16*i.  The XOR
+// swizzle is therefore applied on the global side: the lane that fills
+// physical chunk q of row t fetches logical chunk q ^ swizzle(t).  Offsets
+// past the buffer make the hardware write zeros (padding, ragged edges).
+// Three LDS stages form a ring: while slice j is multiplied, slices j+1 and
+// j+2 are in flight.
 // ---------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are
+// outstanding and leaves the other counters alone (gfx9 encoding).
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+// Raw buffer descriptor over `bytes` bytes at `ptr`: offsets at or past `bytes` read as zero.
+__device__ __forceinline__ i32x4 make_rsrc(const void *ptr, unsigned bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(ptr);
+    return i32x4{static_cast<int>(a), static_cast<int>((a >> 32) & 0xFFFF), static_cast<int>(bytes), RSRC_FLAGS};
+}
+
+// LDS byte address of a __shared__ object.
+__device__ __forceinline__ unsigned lds_addr(const void *p) {
+    return static_cast<unsigned>(reinterpret_cast<unsigned long long>(
+        (const __attribute__((address_space(3))) char *)p));
+}
+
+// One wavefront-wide transfer of 64 x 16 bytes from a buffer into LDS: lane i's
+// 16 bytes at byte offset `voff` land at LDS address `lds_base` + 16*i
+// (`lds_base` is the same for the whole wavefront and travels in M0).  Issued
+// as assembly so that waiting for it stays under this kernel's control: the
+// transfers of later ring stages must remain in flight across LDS reads.
+__device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsigned voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
 template <int BM, int BN, int WGM, int WGN, bool POINTWISE>
 __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p) {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
     constexpr int WM = BM / WGM, WN = BN / WGN;  // wavefront tile
     constexpr int MT = WM / 32, NT = WN / 32;    // MFMA tiles per wavefront
     static_assert(MT >= 1 && NT >= 1 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
-    constexpr int AROWS = BM / 32, BROWS = BN / 32;  // chunks each thread stages per slice
+    constexpr int AROWS = BM / 32, BROWS = BN / 32;  // staging instructions per wavefront and slice
+    constexpr int STAGE = (BM + BN) * BK;            // elements per LDS stage: A rows, then B rows
 
-    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM * BK];
-    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN * BK];
+    // One array per stage so that the compiler can tell the stages apart.
+    __shared__ __attribute__((aligned(1024))) __bf16 st0[STAGE];
+    __shared__ __attribute__((aligned(1024))) __bf16 st1[STAGE];
+    __shared__ __attribute__((aligned(1024))) __bf16 st2[STAGE];
 
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
@@ -113,17 +155,18 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wy = wave / WGN, wx = wave - wy * WGN;
 
-    const __amdgpu_buffer_rsrc_t rx =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(p.x), 0, static_cast<int>(p.x_bytes), RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t rw =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(p.w), 0, static_cast<int>(p.w_bytes), RSRC_FLAGS);
+    const i32x4 rx = make_rsrc(p.x, p.x_bytes);
+    const i32x4 rw = make_rsrc(p.w, p.w_bytes);
 
-    // ---- staging roles: this thread always carries depth chunk `cc` of rows lrow + 32*i
-    const int cc = tid & 7;
-    const int lrow = tid >> 3;
+    // ---- staging roles.  Instruction u of this wavefront fills tile rows
+    // u*32 + wave*8 .. +8; this lane fills physical chunk lane&7 of row
+    // u*32 + lrow, i.e. fetches logical chunk cc (the same for every u).
+    const int lrow = wave * 8 + (lane >> 3);
+    const int cc = (lane & 7) ^ ((lrow >> 1) & 7);
 
     // Byte offset of tap (0, 0), channel 0 of each pixel row (may be negative before
     // the tap offset is added), and the pixel's top-left corner for the bounds tests.
@@ -151,7 +194,7 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
         b_off[i] = k < p.K ? static_cast<unsigned>((k * p.Kg + cc * CHUNK) * 2) : OOB;
     }
 
-    // Depth position of the chunk this thread gathers next: element index g, its
+    // Depth position of the chunk this thread fetches next: element index g, its
     // filter tap (r, s), channel c, and the tap's byte offset inside the image.
     // Advancing s by one and c by -C leaves the address unchanged (a filter row
     // covers a contiguous span of the image row), so the offset only jumps when
@@ -169,42 +212,28 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
     };
     if (!POINTWISE) normalise();
 
-    // Two register sets: slice j+1 waits in one while slice j+2 is still in flight in the other.
-    u32x4 ra0[AROWS], rb0[BROWS], ra1[AROWS], rb1[BROWS];
-
-    // Issues the gather of the next depth slice into a register set and advances the position.
-    auto load_next = [&](u32x4 (&ra)[AROWS], u32x4 (&rb)[BROWS]) {
+    // Starts the transfer of the next depth slice into `stage` and advances the position.
+    auto issue_next = [&](__bf16 *stage) {
         const bool g_ok = g < p.Kg;
+        unsigned base = lds_addr(stage) + wave * 8 * (BK * 2);
 #pragma unroll
         for (int i = 0; i < AROWS; ++i) {
-            unsigned off;
-            if (POINTWISE) {
-                off = g_ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
-            } else {
-                const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&
-                                (unsigned)(a_w0[i] + s) < (unsigned)p.W;
-                off = ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
-            }
-            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, static_cast<int>(off), 0, 0);
+            bool ok = g_ok;
+            if (!POINTWISE)
+                ok = ok & ((unsigned)(a_h0[i] + r) < (unsigned)p.H) & ((unsigned)(a_w0[i] + s) < (unsigned)p.W);
+            const unsigned off = ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
+            dma16(rx, base + i * 32 * (BK * 2), off);
         }
+        base += BM * (BK * 2);
 #pragma unroll
         for (int i = 0; i < BROWS; ++i) {
             const unsigned off = g_ok ? b_off[i] + static_cast<unsigned>(g - cc * CHUNK) * 2u : OOB;
-            rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, static_cast<int>(off), 0, 0);
+            dma16(rw, base + i * 32 * (BK * 2), off);
         }
         g += BK;
         c += BK;
         tap += BK * 2;
         if (!POINTWISE) normalise();
-    };
-
-    auto store_slice = [&](int buf, const u32x4 (&ra)[AROWS], const u32x4 (&rb)[BROWS]) {
-#pragma unroll
-        for (int i = 0; i < AROWS; ++i)
-            *reinterpret_cast<u32x4 *>(&sA[buf][lds_pos(lrow + 32 * i, cc)]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < BROWS; ++i)
-            *reinterpret_cast<u32x4 *>(&sB[buf][lds_pos(lrow + 32 * i, cc)]) = rb[i];
     };
 
     f32x16 acc[MT][NT];
@@ -219,18 +248,17 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
     const int frow = lane & 31;   // row of an MFMA operand this lane supplies
     const int fhalf = lane >> 5;  // which 8 of the 16 depth elements of a step
 
-    auto compute_slice = [&](int buf) {
+    auto compute_slice = [&](const __bf16 *stage) {
+        const __bf16 *sA = stage, *sB = stage + BM * BK;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[MT], fb[NT];
 #pragma unroll
             for (int i = 0; i < MT; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8 *>(
-                    &sA[buf][lds_pos(wy * WM + i * 32 + frow, ks * 2 + fhalf)]);
+                fa[i] = *reinterpret_cast<const bf16x8 *>(&sA[lds_pos(wy * WM + i * 32 + frow, ks * 2 + fhalf)]);
 #pragma unroll
             for (int j = 0; j < NT; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8 *>(
-                    &sB[buf][lds_pos(wx * WN + j * 32 + frow, ks * 2 + fhalf)]);
+                fb[j] = *reinterpret_cast<const bf16x8 *>(&sB[lds_pos(wx * WN + j * 32 + frow, ks * 2 + fhalf)]);
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -239,29 +267,30 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
         }
     };
 
-    // Software pipeline, two slices deep: while slice j is multiplied out of LDS
-    // buffer j&1, slice j+1 sits in a register set and slice j+2 is still in
-    // flight.  After the MFMAs of slice j, slice j+1 goes to the other LDS buffer
-    // and the gather of slice j+3 is issued into the freed set.  Gathers past the
-    // end of the depth return zeros and are never multiplied.
-    load_next(ra0, rb0);
-    store_slice(0, ra0, rb0);
-    load_next(ra1, rb1);
-    load_next(ra0, rb0);
-    __syncthreads();
+    // One ring step: slice j sits in `cur`; `nxt2` is the stage slice j-1 was
+    // read from.  Wait until this thread's transfers of slice j have landed
+    // (those of slice j+1 may stay in flight), meet the other wavefronts, start
+    // slice j+2 into the stage everybody has just left, multiply slice j.
+    // Transfers past the end of the depth write zeros that are never read.
+    auto step = [&](const __bf16 *cur, __bf16 *nxt2) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(AROWS + BROWS));
+        __syncthreads();
+        issue_next(nxt2);
+        compute_slice(cur);
+    };
 
+    issue_next(st0);
+    issue_next(st1);
     int kt = 0;
-    for (; kt + 2 <= nk; kt += 2) {
-        compute_slice(0);
-        store_slice(1, ra1, rb1);
-        load_next(ra1, rb1);
-        __syncthreads();
-        compute_slice(1);
-        store_slice(0, ra0, rb0);
-        load_next(ra0, rb0);
-        __syncthreads();
+    for (; kt + 3 <= nk; kt += 3) {
+        step(st0, st2);
+        step(st1, st0);
+        step(st2, st1);
     }
-    if (kt < nk) compute_slice(0);
+    if (kt < nk) step(st0, st2);
+    if (kt + 1 < nk) step(st1, st0);
+    // Nothing may still be writing LDS when the workgroup's LDS is handed on.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 
     store_tile<MT, NT>(p, acc, m0 + wy * WM, n0 + wx * WN, lane);
 }
@@ -469,12 +498,12 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
 
     // Pick the tile that minimises (workgroups the busiest CU runs) x (tile area) / efficiency.
-    static const TileChoice kTiles[] = {{128, 128, 1.00f}, {128, 64, 0.85f}, {64, 128, 0.85f},
-                                        {64, 64, 0.70f},   {128, 32, 0.60f}, {32, 128, 0.60f}};
+    static const TileChoice kTiles[] = {{128, 128, 1.00f}, {128, 64, 0.85f}, {64, 128, 0.85f}, {64, 64, 0.70f},
+                                        {128, 32, 0.60f},  {32, 128, 0.60f}, {256, 128, 1.15f}};
     int best = 0;
     double best_cost = 0.0;
     if (n_cu < 1) n_cu = 1;
-    for (int i = 0; i < 6; ++i) {
+    for (int i = 0; i < GPULET_CONV_TILES; ++i) {
         const TileChoice &t = kTiles[i];
         const long long blocks = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
         const long long per_cu = (blocks + n_cu - 1) / n_cu;
@@ -485,14 +514,15 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
         }
     }
     const int forced = g_tile_override.load();
-    if (forced >= 0 && forced < 6) best = forced;
+    if (forced >= 0 && forced < GPULET_CONV_TILES) best = forced;
     switch (best) {
         case 0: return launch_tile<128, 128, 2, 2>(p, vec, stream);
         case 1: return launch_tile<128, 64, 2, 2>(p, vec, stream);
         case 2: return launch_tile<64, 128, 2, 2>(p, vec, stream);
         case 3: return launch_tile<64, 64, 2, 2>(p, vec, stream);
         case 4: return launch_tile<128, 32, 4, 1>(p, vec, stream);
-        default: return launch_tile<32, 128, 1, 4>(p, vec, stream);
+        case 5: return launch_tile<32, 128, 1, 4>(p, vec, stream);
+        default: return launch_tile<256, 128, 2, 2>(p, vec, stream);
     }
 }
 

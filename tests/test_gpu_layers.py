@@ -47,7 +47,7 @@ def test_conv_parity_every_tile(part, case):
     x, w, b = conv_tensors(11, N, C, H, W, K, R)
     ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
     first = None
-    for tile in range(-1, 6):
+    for tile in range(-1, 7):
         got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
         whole, per_img = oracle.rel_err(got, ref)
         assert max(whole, per_img) <= LAYER_TOL, (tile, whole, per_img)
@@ -86,7 +86,7 @@ def test_conv_delta_kernel_copies_input_exactly(part):
     assert np.array_equal(got, x.astype(np.float64))
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 3, 4])
+@pytest.mark.parametrize("tile", [-1, 0, 3, 4, 6])
 def test_conv_residual_and_channel_slice(part, tile):
     N, C, H, W, K, R = 2, 32, 10, 10, 40, 3
     x, w, b = conv_tensors(15, N, C, H, W, K, R)
