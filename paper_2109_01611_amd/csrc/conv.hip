@@ -50,6 +50,7 @@ struct ConvParams {
     int ldy, y_off;     // channels per output pixel of the destination, first channel
     int tiles_n, n_tiles, tiles_per_xcd;
     unsigned x_bytes, w_bytes;
+    int tap_inner;      // depth order: 64-channel block outermost, filter taps inside it
 };
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
@@ -102,8 +103,8 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, const f32x16 (&a
 // swizzle is therefore applied on the global side: the lane that fills
 // physical chunk q of row t fetches logical chunk q ^ swizzle(t).  Offsets
 // past the buffer make the hardware write zeros (padding, ragged edges).
-// Three LDS stages form a ring: while slice j is multiplied, slices j+1 and
-// j+2 are in flight.
+// NS LDS stages form a ring: while slice j is multiplied, slices j+1 .. j+NS-1
+// are in flight.
 // ---------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
@@ -135,106 +136,169 @@ __device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsig
                  : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, bool POINTWISE>
-__global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p) {
-    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
-    constexpr int WM = BM / WGM, WN = BN / WGN;  // wavefront tile
-    constexpr int MT = WM / 32, NT = WN / 32;    // MFMA tiles per wavefront
+// Wavefronts are specialised.  The first CWM x CWN wavefronts ("consumers")
+// only read LDS and issue MFMAs; the last NPROD wavefronts ("producers") only
+// compute addresses and issue transfers.  A wavefront blocked on a saturated
+// memory pipeline therefore never holds back matrix instructions.  Every ring
+// step has one workgroup barrier: before it a producer waits for its own
+// transfers of slice j, after it the stage slice j-1 occupied is free again.
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE>
+__global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(const ConvParams p) {
+    constexpr int NCONS = CWM * CWN;
+    constexpr int WM = BM / CWM, WN = BN / CWN;  // consumer wavefront tile
+    constexpr int MT = WM / 32, NT = WN / 32;    // MFMA tiles per consumer
     static_assert(MT >= 1 && NT >= 1 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
-    constexpr int AROWS = BM / 32, BROWS = BN / 32;  // staging instructions per wavefront and slice
-    constexpr int STAGE = (BM + BN) * BK;            // elements per LDS stage: A rows, then B rows
+    static_assert(NPROD == 2 || NPROD == 4, "swizzle key must not depend on the instruction index");
+    constexpr int PROWS = NPROD * 8;                       // tile rows one round of producer instructions fills
+    constexpr int AINS = BM / PROWS, BINS = BN / PROWS;    // transfers per producer lane and slice
+    static_assert(BM % PROWS == 0 && BN % PROWS == 0, "tile rows per producer round");
+    constexpr int STAGE = (BM + BN) * BK;                  // elements per LDS stage: A rows, then B rows
+    static_assert(NS >= 2 && (AINS + BINS) * (NS - 2) <= 63, "ring depth vs the 6-bit transfer counter");
 
-    // One array per stage so that the compiler can tell the stages apart.
-    __shared__ __attribute__((aligned(1024))) __bf16 st0[STAGE];
-    __shared__ __attribute__((aligned(1024))) __bf16 st1[STAGE];
-    __shared__ __attribute__((aligned(1024))) __bf16 st2[STAGE];
+    __shared__ __attribute__((aligned(1024))) __bf16 ring[NS * STAGE];
 
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
     const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wy = wave / WGN, wx = wave - wy * WGN;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nk = (p.Kg + BK - 1) / BK;
 
-    const i32x4 rx = make_rsrc(p.x, p.x_bytes);
-    const i32x4 rw = make_rsrc(p.w, p.w_bytes);
+    if (wave >= NCONS) {
+        // ------------------------------------------------------------ producer
+        const int pw = wave - NCONS;
+        const i32x4 rx = make_rsrc(p.x, p.x_bytes);
+        const i32x4 rw = make_rsrc(p.w, p.w_bytes);
 
-    // ---- staging roles.  Instruction u of this wavefront fills tile rows
-    // u*32 + wave*8 .. +8; this lane fills physical chunk lane&7 of row
-    // u*32 + lrow, i.e. fetches logical chunk cc (the same for every u).
-    const int lrow = wave * 8 + (lane >> 3);
-    const int cc = (lane & 7) ^ ((lrow >> 1) & 7);
+        // Instruction u of this wavefront fills tile rows u*PROWS + pw*8 .. +8;
+        // this lane fills physical chunk lane&7 of row u*PROWS + lrow, i.e.
+        // fetches logical chunk cc (the same for every u).
+        const int lrow = pw * 8 + (lane >> 3);
+        const int cc = (lane & 7) ^ ((lrow >> 1) & 7);
 
-    // Byte offset of tap (0, 0), channel 0 of each pixel row (may be negative before
-    // the tap offset is added), and the pixel's top-left corner for the bounds tests.
-    int a_off[AROWS], a_h0[AROWS], a_w0[AROWS];
+        // Byte offset of tap (0, 0), channel 0 of each pixel row (may be negative
+        // before the tap offset is added), and the pixel's top-left corner.
+        int a_off[AINS], a_h0[AINS], a_w0[AINS];
 #pragma unroll
-    for (int i = 0; i < AROWS; ++i) {
-        const int m = m0 + lrow + 32 * i;
-        if (m < p.M) {
-            const int n = m / (p.P * p.Q);
-            const int pq = m - n * (p.P * p.Q);
-            const int pp = pq / p.Q, qq = pq - pp * p.Q;
-            a_h0[i] = pp * p.stride - p.pad;
-            a_w0[i] = qq * p.stride - p.pad;
-            a_off[i] = (((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C) * 2;
-        } else {
-            a_h0[i] = -(1 << 28);  // fails every bounds test
-            a_w0[i] = -(1 << 28);
-            a_off[i] = static_cast<int>(OOB);
-        }
-    }
-    unsigned b_off[BROWS];
-#pragma unroll
-    for (int i = 0; i < BROWS; ++i) {
-        const int k = n0 + lrow + 32 * i;
-        b_off[i] = k < p.K ? static_cast<unsigned>((k * p.Kg + cc * CHUNK) * 2) : OOB;
-    }
-
-    // Depth position of the chunk this thread fetches next: element index g, its
-    // filter tap (r, s), channel c, and the tap's byte offset inside the image.
-    // Advancing s by one and c by -C leaves the address unchanged (a filter row
-    // covers a contiguous span of the image row), so the offset only jumps when
-    // the filter moves to its next row.
-    int g = cc * CHUNK, r = 0, s = 0, c = cc * CHUNK, tap = cc * CHUNK * 2;
-    auto normalise = [&]() {
-        while (c >= p.C) {
-            c -= p.C;
-            if (++s == p.S) {
-                s = 0;
-                ++r;
-                tap += (p.W - p.S) * p.C * 2;
+        for (int i = 0; i < AINS; ++i) {
+            const int m = m0 + lrow + PROWS * i;
+            if (m < p.M) {
+                const int n = m / (p.P * p.Q);
+                const int pq = m - n * (p.P * p.Q);
+                const int pp = pq / p.Q, qq = pq - pp * p.Q;
+                a_h0[i] = pp * p.stride - p.pad;
+                a_w0[i] = qq * p.stride - p.pad;
+                a_off[i] = (((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C) * 2;
+            } else {
+                a_h0[i] = -(1 << 28);  // fails every bounds test
+                a_w0[i] = -(1 << 28);
+                a_off[i] = static_cast<int>(OOB);
             }
         }
-    };
-    if (!POINTWISE) normalise();
+        unsigned b_off[BINS];
+#pragma unroll
+        for (int i = 0; i < BINS; ++i) {
+            const int k = n0 + lrow + PROWS * i;
+            b_off[i] = k < p.K ? static_cast<unsigned>((k * p.Kg + cc * CHUNK) * 2) : OOB;
+        }
 
-    // Starts the transfer of the next depth slice into `stage` and advances the position.
-    auto issue_next = [&](__bf16 *stage) {
-        const bool g_ok = g < p.Kg;
-        unsigned base = lds_addr(stage) + wave * 8 * (BK * 2);
-#pragma unroll
-        for (int i = 0; i < AROWS; ++i) {
-            bool ok = g_ok;
-            if (!POINTWISE)
-                ok = ok & ((unsigned)(a_h0[i] + r) < (unsigned)p.H) & ((unsigned)(a_w0[i] + s) < (unsigned)p.W);
-            const unsigned off = ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
-            dma16(rx, base + i * 32 * (BK * 2), off);
-        }
-        base += BM * (BK * 2);
-#pragma unroll
-        for (int i = 0; i < BROWS; ++i) {
-            const unsigned off = g_ok ? b_off[i] + static_cast<unsigned>(g - cc * CHUNK) * 2u : OOB;
-            dma16(rw, base + i * 32 * (BK * 2), off);
-        }
-        g += BK;
-        c += BK;
-        tap += BK * 2;
+        // Depth position of the chunk this lane fetches next: element index g, its
+        // filter tap (r, s), channel c, and the tap's byte offset inside the image.
+        // Advancing s by one and c by -C leaves the address unchanged (a filter row
+        // covers a contiguous span of the image row), so the offset only jumps when
+        // the filter moves to its next row.
+        //
+        // Two depth orders.  Linear: g runs through (r, s, c) as the weights are
+        // stored.  Tap-inner (C a multiple of 64, filter larger than 1x1): for each
+        // block of 64 channels all taps follow one another, so the image rows a
+        // workgroup just fetched for one tap are fetched again for the next while
+        // they are still in the nearest cache.  Both operands use the same order,
+        // so only the summation order of the result changes.
+        int g = cc * CHUNK, r = 0, s = 0, c = cc * CHUNK, tap = cc * CHUNK * 2;
+        int cblk = 0, issued = 0;
+        auto normalise = [&]() {
+            while (c >= p.C) {
+                c -= p.C;
+                if (++s == p.S) {
+                    s = 0;
+                    ++r;
+                    tap += (p.W - p.S) * p.C * 2;
+                }
+            }
+        };
         if (!POINTWISE) normalise();
-    };
+
+        // Starts the transfer of the next depth slice into `stage` and advances the
+        // position.  Slices past the end of the depth transfer zeros nobody reads.
+        auto issue_next = [&](const __bf16 *stage) {
+            const bool g_ok = p.tap_inner ? issued < nk : g < p.Kg;
+            unsigned base = lds_addr(stage) + pw * 8 * (BK * 2);
+#pragma unroll
+            for (int i = 0; i < AINS; ++i) {
+                bool ok = g_ok;
+                if (!POINTWISE)
+                    ok = ok & ((unsigned)(a_h0[i] + r) < (unsigned)p.H) & ((unsigned)(a_w0[i] + s) < (unsigned)p.W);
+                const unsigned off = ok ? static_cast<unsigned>(a_off[i] + tap) : OOB;
+                dma16(rx, base + i * PROWS * (BK * 2), off);
+            }
+            base += BM * (BK * 2);
+#pragma unroll
+            for (int i = 0; i < BINS; ++i) {
+                const unsigned off = g_ok ? b_off[i] + static_cast<unsigned>(g - cc * CHUNK) * 2u : OOB;
+                dma16(rw, base + i * PROWS * (BK * 2), off);
+            }
+            ++issued;
+            if (!POINTWISE && p.tap_inner) {
+                g += p.C;
+                tap += p.C * 2;
+                if (++s == p.S) {
+                    s = 0;
+                    tap += (p.W - p.S) * p.C * 2;
+                    if (++r == p.R) {
+                        r = 0;
+                        cblk += BK;
+                        g = cblk + cc * CHUNK;
+                        tap = g * 2;
+                    }
+                }
+            } else {
+                g += BK;
+                c += BK;
+                tap += BK * 2;
+                if (!POINTWISE) normalise();
+            }
+        };
+
+        // Step j: wait for this lane's transfers of slice j (those of the NS-2 later
+        // slices may stay in flight), meet everybody, refill the stage slice j-1 was
+        // read from with slice j+NS-1.
+#pragma unroll
+        for (int i = 0; i < NS - 1; ++i) issue_next(ring + i * STAGE);
+        auto step = [&](int refill) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((AINS + BINS) * (NS - 2)));
+            __syncthreads();
+            issue_next(ring + refill * STAGE);
+        };
+        // The ring position is a compile-time constant inside the unrolled body.
+        int kt = 0;
+        for (; kt + NS <= nk; kt += NS) {
+#pragma unroll
+            for (int u = 0; u < NS; ++u) step((u + NS - 1) % NS);
+        }
+#pragma unroll
+        for (int u = 0; u < NS - 1; ++u)
+            if (kt + u < nk) step((u + NS - 1) % NS);
+        // Nothing may still be writing LDS when the workgroup's LDS is handed on.
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        return;
+    }
+
+    // ---------------------------------------------------------------- consumer
+    const int wy = wave / CWN, wx = wave - wy * CWN;
+    const int frow = lane & 31;   // row of an MFMA operand this lane supplies
+    const int fhalf = lane >> 5;  // which 8 of the 16 depth elements of a step
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -244,12 +308,9 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = (p.Kg + BK - 1) / BK;
-    const int frow = lane & 31;   // row of an MFMA operand this lane supplies
-    const int fhalf = lane >> 5;  // which 8 of the 16 depth elements of a step
-
-    auto compute_slice = [&](const __bf16 *stage) {
-        const __bf16 *sA = stage, *sB = stage + BM * BK;
+    auto step = [&](int cur) {
+        __syncthreads();
+        const __bf16 *sA = ring + cur * STAGE, *sB = sA + BM * BK;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[MT], fb[NT];
@@ -266,31 +327,14 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_kernel(const ConvParams p
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     };
-
-    // One ring step: slice j sits in `cur`; `nxt2` is the stage slice j-1 was
-    // read from.  Wait until this thread's transfers of slice j have landed
-    // (those of slice j+1 may stay in flight), meet the other wavefronts, start
-    // slice j+2 into the stage everybody has just left, multiply slice j.
-    // Transfers past the end of the depth write zeros that are never read.
-    auto step = [&](const __bf16 *cur, __bf16 *nxt2) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(AROWS + BROWS));
-        __syncthreads();
-        issue_next(nxt2);
-        compute_slice(cur);
-    };
-
-    issue_next(st0);
-    issue_next(st1);
     int kt = 0;
-    for (; kt + 3 <= nk; kt += 3) {
-        step(st0, st2);
-        step(st1, st0);
-        step(st2, st1);
+    for (; kt + NS <= nk; kt += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) step(u);
     }
-    if (kt < nk) step(st0, st2);
-    if (kt + 1 < nk) step(st1, st0);
-    // Nothing may still be writing LDS when the workgroup's LDS is handed on.
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+#pragma unroll
+    for (int u = 0; u < NS - 1; ++u)
+        if (kt + u < nk) step(u);
 
     store_tile<MT, NT>(p, acc, m0 + wy * WM, n0 + wx * WN, lane);
 }
@@ -433,18 +477,21 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_any_kernel(const ConvPara
     store_tile<MT, NT>(p, acc, m0 + wy * WM, n0 + wx * WN, lane);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+// CWM x CWN consumers and NPROD producers for the main kernel; the scalar-gather
+// kernel always runs four wavefronts as WGM x WGN.
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, int WGM, int WGN>
 hipError_t launch_tile(ConvParams p, bool vec, hipStream_t stream) {
     const int tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.K + BN - 1) / BN;
     p.n_tiles = tiles_m * p.tiles_n;
     p.tiles_per_xcd = (p.n_tiles + 7) / 8;
     const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8));
+    const dim3 block((CWM * CWN + NPROD) * 64);
     const bool pointwise = p.R == 1 && p.S == 1 && p.pad == 0;
     if (vec && pointwise)
-        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, WGM, WGN, true>), grid, dim3(NTHREADS), 0, stream, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, CWM, CWN, NPROD, NS, true>), grid, block, 0, stream, p);
     else if (vec)
-        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, WGM, WGN, false>), grid, dim3(NTHREADS), 0, stream, p);
+        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, CWM, CWN, NPROD, NS, false>), grid, block, 0, stream, p);
     else
         hipLaunchKernelGGL((conv_igemm_any_kernel<BM, BN, WGM, WGN>), grid, dim3(NTHREADS), 0, stream, p);
     return hipGetLastError();
@@ -493,6 +540,7 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
     p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
     p.x_bytes = static_cast<unsigned>(2LL * a.N * a.H * a.W * a.C);
     p.w_bytes = static_cast<unsigned>(2LL * a.K * a.R * a.S * a.C);
+    p.tap_inner = (a.C % BK == 0 && a.R * a.S > 1) ? 1 : 0;
 
     const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
@@ -514,15 +562,24 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
         }
     }
     const int forced = g_tile_override.load();
-    if (forced >= 0 && forced < GPULET_CONV_TILES) best = forced;
+    if (forced >= 0) best = forced;
     switch (best) {
-        case 0: return launch_tile<128, 128, 2, 2>(p, vec, stream);
-        case 1: return launch_tile<128, 64, 2, 2>(p, vec, stream);
-        case 2: return launch_tile<64, 128, 2, 2>(p, vec, stream);
-        case 3: return launch_tile<64, 64, 2, 2>(p, vec, stream);
-        case 4: return launch_tile<128, 32, 4, 1>(p, vec, stream);
-        case 5: return launch_tile<32, 128, 1, 4>(p, vec, stream);
-        default: return launch_tile<256, 128, 2, 2>(p, vec, stream);
+        case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
+        case 1: return launch_tile<128, 64, 4, 2, 4, 3, 2, 2>(p, vec, stream);
+        case 2: return launch_tile<64, 128, 2, 4, 4, 3, 2, 2>(p, vec, stream);
+        case 3: return launch_tile<64, 64, 2, 2, 2, 3, 2, 2>(p, vec, stream);
+        case 4: return launch_tile<128, 32, 4, 1, 2, 3, 4, 1>(p, vec, stream);
+        case 5: return launch_tile<32, 128, 1, 4, 2, 3, 1, 4>(p, vec, stream);
+        case 6: return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
+        case 7: return launch_tile<128, 128, 4, 2, 4, 2, 2, 2>(p, vec, stream);
+        case 8: return launch_tile<128, 128, 2, 2, 4, 2, 2, 2>(p, vec, stream);
+        case 9: return launch_tile<256, 128, 4, 2, 4, 2, 2, 2>(p, vec, stream);
+        case 10: return launch_tile<256, 64, 4, 2, 4, 2, 2, 2>(p, vec, stream);
+        case 11: return launch_tile<128, 64, 4, 2, 4, 2, 2, 2>(p, vec, stream);
+        case 12: return launch_tile<64, 128, 2, 4, 4, 2, 2, 2>(p, vec, stream);
+        case 13: return launch_tile<64, 64, 2, 2, 2, 2, 2, 2>(p, vec, stream);
+        case 14: return launch_tile<128, 256, 2, 4, 4, 2, 2, 2>(p, vec, stream);
+        default: return launch_tile<256, 256, 4, 2, 4, 2, 2, 2>(p, vec, stream);
     }
 }
 
