@@ -51,6 +51,7 @@ struct ConvParams {
     int tiles_n, n_tiles, tiles_per_xcd;
     unsigned x_bytes, w_bytes;
     int tap_inner;      // depth order: 64-channel block outermost, filter taps inside it
+    int vec_store;      // output (and residual) rows allow aligned 16-byte accesses
 };
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
@@ -155,7 +156,9 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     constexpr int STAGE = (BM + BN) * BK;                  // elements per LDS stage: A rows, then B rows
     static_assert(NS >= 2 && (AINS + BINS) * (NS - 2) <= 63, "ring depth vs the 6-bit transfer counter");
 
-    __shared__ __attribute__((aligned(1024))) __bf16 ring[NS * STAGE];
+    constexpr int LDT = BN + 8;  // padded row of the fp32 epilogue tile that reuses the ring
+    constexpr int RING = NS * STAGE > BM * LDT * 2 ? NS * STAGE : BM * LDT * 2;
+    __shared__ __attribute__((aligned(1024))) __bf16 ring[RING];
 
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
@@ -165,6 +168,8 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nk = (p.Kg + BK - 1) / BK;
+
+    f32x16 acc[MT][NT];  // consumers only
 
     if (wave >= NCONS) {
         // ------------------------------------------------------------ producer
@@ -290,17 +295,14 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
 #pragma unroll
         for (int u = 0; u < NS - 1; ++u)
             if (kt + u < nk) step((u + NS - 1) % NS);
-        // Nothing may still be writing LDS when the workgroup's LDS is handed on.
+        // Every transfer has landed before the ring is reused by the epilogue.
         __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        return;
-    }
-
+    } else {
     // ---------------------------------------------------------------- consumer
     const int wy = wave / CWN, wx = wave - wy * CWN;
     const int frow = lane & 31;   // row of an MFMA operand this lane supplies
     const int fhalf = lane >> 5;  // which 8 of the 16 depth elements of a step
 
-    f32x16 acc[MT][NT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -336,7 +338,77 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     for (int u = 0; u < NS - 1; ++u)
         if (kt + u < nk) step(u);
 
-    store_tile<MT, NT>(p, acc, m0 + wy * WM, n0 + wx * WN, lane);
+    }
+
+    // ------------------------------------------------------------------ epilogue
+    // The accumulators hold one column (channel) and 16 scattered rows per lane,
+    // which would mean 2-byte stores.  They go through LDS instead: consumers
+    // drop acc + bias as fp32 into the (now idle) ring, then every wavefront of
+    // the workgroup picks up 8 consecutive channels of a pixel, adds the
+    // residual, applies ReLU, rounds once to bf16 and stores 16 bytes.
+    // Rows are padded by 8 floats so that lanes 32..63 (4 rows further down) use
+    // the other half of the banks.
+    float *stg = reinterpret_cast<float *>(ring);
+    __syncthreads();  // all LDS reads of the main loop are done, all transfers have landed
+    if (wave < NCONS) {
+        const int wy = wave / CWN, wx = wave - wy * CWN;
+        const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int col = wx * WN + j * 32 + frow;
+            const int k = n0 + col;
+            const float bias = (p.b && k < p.K) ? p.b[k] : 0.f;
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = wy * WM + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
+                    stg[row * LDT + col] = acc[i][j][v] + bias;
+                }
+        }
+    }
+    __syncthreads();
+    constexpr int VPR = BN / 8;  // 8-channel groups per tile row
+    const bool vec_ok = p.vec_store;
+    for (int it = threadIdx.x; it < BM * VPR; it += (NCONS + NPROD) * 64) {
+        const int row = it / VPR, cv = it - row * VPR;
+        const int m = m0 + row, k = n0 + cv * 8;
+        if (m >= p.M || k >= p.K) continue;
+        const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
+        const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
+        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        if (vec_ok && k + 8 <= p.K) {
+            if (p.res) {
+                const uint4 rr = *reinterpret_cast<const uint4 *>(p.res + (m * p.K + k));
+                const unsigned ru[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] += __uint_as_float(ru[e] << 16);
+                    v[2 * e + 1] += __uint_as_float(ru[e] & 0xFFFF0000u);
+                }
+            }
+            unsigned pk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float a = v[2 * e], b = v[2 * e + 1];
+                if (p.relu) {
+                    a = a > 0.f ? a : 0.f;
+                    b = b > 0.f ? b : 0.f;
+                }
+                const __bf16 ha = static_cast<__bf16>(a), hb = static_cast<__bf16>(b);
+                pk[e] = static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&ha)) |
+                        (static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&hb)) << 16);
+            }
+            *reinterpret_cast<uint4 *>(p.y + (m * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        } else {
+            for (int e = 0; e < 8 && k + e < p.K; ++e) {
+                float a = v[e];
+                if (p.res) a += static_cast<float>(p.res[m * p.K + k + e]);
+                if (p.relu) a = a > 0.f ? a : 0.f;
+                p.y[m * p.ldy + p.y_off + k + e] = static_cast<__bf16>(a);
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -541,6 +613,10 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
     p.x_bytes = static_cast<unsigned>(2LL * a.N * a.H * a.W * a.C);
     p.w_bytes = static_cast<unsigned>(2LL * a.K * a.R * a.S * a.C);
     p.tap_inner = (a.C % BK == 0 && a.R * a.S > 1) ? 1 : 0;
+    p.vec_store = (a.y_ch_stride % 8 == 0 && a.y_ch_offset % 8 == 0 && reinterpret_cast<uintptr_t>(a.y) % 16 == 0 &&
+                   (!a.residual || (a.K % 8 == 0 && reinterpret_cast<uintptr_t>(a.residual) % 16 == 0)))
+                      ? 1
+                      : 0;
 
     const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
@@ -562,7 +638,7 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
         }
     }
     const int forced = g_tile_override.load();
-    if (forced >= 0) best = forced;
+    if (forced >= 0 && forced < GPULET_CONV_TILES) best = forced;
     switch (best) {
         case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
         case 1: return launch_tile<128, 64, 4, 2, 4, 3, 2, 2>(p, vec, stream);
@@ -570,16 +646,7 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
         case 3: return launch_tile<64, 64, 2, 2, 2, 3, 2, 2>(p, vec, stream);
         case 4: return launch_tile<128, 32, 4, 1, 2, 3, 4, 1>(p, vec, stream);
         case 5: return launch_tile<32, 128, 1, 4, 2, 3, 1, 4>(p, vec, stream);
-        case 6: return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
-        case 7: return launch_tile<128, 128, 4, 2, 4, 2, 2, 2>(p, vec, stream);
-        case 8: return launch_tile<128, 128, 2, 2, 4, 2, 2, 2>(p, vec, stream);
-        case 9: return launch_tile<256, 128, 4, 2, 4, 2, 2, 2>(p, vec, stream);
-        case 10: return launch_tile<256, 64, 4, 2, 4, 2, 2, 2>(p, vec, stream);
-        case 11: return launch_tile<128, 64, 4, 2, 4, 2, 2, 2>(p, vec, stream);
-        case 12: return launch_tile<64, 128, 2, 4, 4, 2, 2, 2>(p, vec, stream);
-        case 13: return launch_tile<64, 64, 2, 2, 2, 2, 2, 2>(p, vec, stream);
-        case 14: return launch_tile<128, 256, 2, 4, 4, 2, 2, 2>(p, vec, stream);
-        default: return launch_tile<256, 256, 4, 2, 4, 2, 2, 2>(p, vec, stream);
+        default: return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
     }
 }
 

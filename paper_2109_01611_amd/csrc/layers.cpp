@@ -44,7 +44,7 @@ extern "C" gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const f
 }
 
 extern "C" gpulet_status gpulet_set_conv_tile(int tile) {
-    if (tile < -1 || tile >= 16) return GPULET_EINVAL;
+    if (tile < -1 || tile >= GPULET_CONV_TILES) return GPULET_EINVAL;
     set_conv_tile(tile);
     return GPULET_OK;
 }
