@@ -622,17 +622,21 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
 
     // Pick the tile that minimises (workgroups the busiest CU runs) x (tile area) / efficiency.
-    static const TileChoice kTiles[] = {{128, 128, 1.00f}, {128, 64, 0.85f}, {64, 128, 0.85f}, {64, 64, 0.70f},
-                                        {128, 32, 0.60f},  {32, 128, 0.60f}, {256, 128, 1.15f}};
+    // The efficiencies are measured throughput ratios on MI355X (large layers, all CUs busy);
+    // on a tie the earlier entry wins.
+    static const TileChoice kTiles[] = {{128, 128, 0.90f}, {128, 64, 0.72f}, {64, 128, 0.72f}, {64, 64, 0.58f},
+                                        {128, 32, 0.30f},  {32, 128, 0.40f}, {256, 128, 1.00f}};
+    static const int kOrder[] = {6, 0, 2, 1, 3, 5, 4};
     int best = 0;
     double best_cost = 0.0;
     if (n_cu < 1) n_cu = 1;
-    for (int i = 0; i < GPULET_CONV_TILES; ++i) {
+    for (int o = 0; o < GPULET_CONV_TILES; ++o) {
+        const int i = kOrder[o];
         const TileChoice &t = kTiles[i];
         const long long blocks = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
         const long long per_cu = (blocks + n_cu - 1) / n_cu;
         const double cost = static_cast<double>(per_cu) * t.bm * t.bn / t.eff;
-        if (i == 0 || cost < best_cost) {
+        if (o == 0 || cost < best_cost) {
             best = i;
             best_cost = cost;
         }
