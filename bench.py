@@ -103,9 +103,13 @@ def main():
         rows = []
         for pct in (20, 40, 50, 60, 80, 100):
             with gpulet.Partition(0, pct, 0) as part:
+                # throughput: launches back to back on the gpu-let's stream, one event pair around all of them
+                ms = gpulet.time_conv2d(*conv_args, stream=part.stream, warmup=50, iters=1000)
+                # latency: one batch in flight at a time, each bracketed by its own event pair
                 r = profiler.measure(bound, part, warmup=50, iters=1000)
-            rows.append({"pct": pct, "n_cu": r["n_cu"], "images_per_s": r["images_per_s"], "tflops": r["tflops"],
-                         "mfma_frac_of_masked_peak": r["mfma_frac_of_masked_peak"],
+            tf = flops / (ms * 1e-3) / 1e12
+            rows.append({"pct": pct, "n_cu": r["n_cu"], "images_per_s": N / (ms * 1e-3), "tflops": tf,
+                         "mfma_frac_of_masked_peak": tf / (r["n_cu"] * profiler.PEAK_TFLOPS_PER_CU),
                          "mean_batch_latency_us": r["mean_ms"] * 1e3, "p99_batch_latency_us": r["p99_ms"] * 1e3})
         full = rows[-1]["images_per_s"]
         for r in rows:

@@ -11,6 +11,11 @@ Layout conversions
   * FC weights whose input is a (C, H, W) feature map: columns go from the
     channel-major flatten order to the NHWC one.
 
+The model input is stored with its channel count padded up to a multiple of 8
+(zeros), and the first convolution's weights are padded to match, so image
+stems (C = 3) and LeNet (C = 1) use the same 16-byte gathers as every other
+layer; the extra channels contribute exact zeros.
+
 Buffers are reused once their last reader has run, which keeps the working
 set small enough to stay in the last-level cache between layers.  A concat
 node costs nothing: its source convolutions store straight into channel
@@ -52,6 +57,9 @@ class DeviceModel:
         self.in_shape = tuple(model.in_shape)
         self._keep = []  # device tensors the layer records point into
         nodes = [nd for nd in model.nodes]
+        # channel padding of the model input (only convolutions may read it then)
+        c_in = model.in_shape[0]
+        self.in_pad = (-c_in) % 8 if all(nd.op == "conv" for nd in nodes if nd.src == "x") else 0
 
         # channels of every named tensor, straight from the table
         chans = {"x": model.in_shape[0]}
@@ -110,10 +118,14 @@ class DeviceModel:
             a = nd.attr
             if nd.op == "conv":
                 w, b = params[nd.name]
+                C = a["C"]
+                if nd.src == "x" and self.in_pad:
+                    w = np.pad(np.asarray(w), ((0, 0), (0, self.in_pad), (0, 0), (0, 0)))
+                    C += self.in_pad
                 wd = kcrs_to_krsc(w, self.device)
                 bd = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(self.device)
                 self._keep += [wd, bd]
-                L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, a["C"], a["K"], a["k"], a["k"]
+                L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, C, a["K"], a["k"], a["k"]
                 L.stride, L.pad, L.relu = a["stride"], a["pad"], int(a["relu"])
                 if a["residual"]:
                     L.res_buf = buf_of[storage(a["residual"])]
@@ -151,12 +163,19 @@ class DeviceModel:
         self.layers = (gpulet.Layer * len(layers))(*layers)
         d = gpulet.ModelDesc()
         d.n_layers, d.n_bufs = len(layers), n_bufs
-        d.in_C, d.in_H, d.in_W = self.in_shape
+        d.in_C, d.in_H, d.in_W = self.in_shape[0] + self.in_pad, self.in_shape[1], self.in_shape[2]
         d.in_buf, d.out_buf = 0, 1
         d.layers = self.layers
         self.desc = d
         self.out_fp32 = producers[model.out].op == "fc"
         self._ws = {}
+
+    def input_to_device(self, x_nchw):
+        """Host batch (N, C, H, W) -> device NHWC bf16 with the channel padding the model expects."""
+        x = np.asarray(x_nchw)
+        if self.in_pad:
+            x = np.pad(x, ((0, 0), (0, self.in_pad), (0, 0), (0, 0)))
+        return nchw_to_nhwc(x, self.device)
 
     def output_shape(self, batch):
         C, H, W, _, _ = gpulet.model_buffer_info(self.desc, batch, 1)

@@ -60,7 +60,7 @@ class Bound:
 
     def __init__(self, dm, batch, seed=0):
         self.dm, self.batch = dm, batch
-        self.x = lowering.nchw_to_nhwc(workloads.batch_input(dm.model, batch, seed), dm.device)
+        self.x = dm.input_to_device(workloads.batch_input(dm.model, batch, seed))
         self.y = dm.alloc_output(batch)
         self.ws, self.ws_bytes = dm.workspace(batch)
 

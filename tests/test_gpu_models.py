@@ -21,7 +21,7 @@ def _run(model, batch, pct=100, which=0, seed=0, reuse=True, images=None):
     x = workloads.batch_input(model, batch, seed)
     dm = lowering.DeviceModel(model, params, DEV, reuse=reuse)
     with gpulet.Partition(0, pct, which) as p:
-        y, ms = dm.run(p, lowering.nchw_to_nhwc(x, DEV), timed=True)
+        y, ms = dm.run(p, dm.input_to_device(x), timed=True)
         assert ms > 0
         assert p.counters() == (1, batch)
     got = y.to(torch.float32).cpu().numpy().astype(np.float64).reshape(batch, -1)
@@ -124,7 +124,7 @@ def test_corun_two_gpulets_gives_same_results_and_counts():
     pa_, pb_ = workloads.parameters(ma, 8), workloads.parameters(mb, 8)
     xa, xb = workloads.batch_input(ma, 4, 8), workloads.batch_input(mb, 6, 8)
     da, db = lowering.DeviceModel(ma, pa_, DEV), lowering.DeviceModel(mb, pb_, DEV)
-    xad, xbd = lowering.nchw_to_nhwc(xa, DEV), lowering.nchw_to_nhwc(xb, DEV)
+    xad, xbd = da.input_to_device(xa), db.input_to_device(xb)
     ya, yb = da.alloc_output(4), db.alloc_output(6)
     (wsa, na), (wsb, nb) = da.workspace(4), db.workspace(6)
     torch.cuda.synchronize()

@@ -87,11 +87,11 @@ def test_request_counters_are_exact():
         assert p.counters() == (0, 0)
         total = 0
         for i, batch in enumerate([1, 7, 32, 5], 1):
-            x = lowering.nchw_to_nhwc(workloads.batch_input(m, batch, 0), DEV)
+            x = dm.input_to_device(workloads.batch_input(m, batch, 0))
             dm.run(p, x)
             total += batch
             assert p.counters() == (i, total)
-        x = lowering.nchw_to_nhwc(workloads.batch_input(m, 4, 0), DEV)
+        x = dm.input_to_device(workloads.batch_input(m, 4, 0))
         ws, n = dm.workspace(4)
         y = dm.alloc_output(4)
         torch.cuda.synchronize()
