@@ -128,6 +128,11 @@ gpulet_status gpulet_partition_sync(gpulet_partition *p);
  */
 gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_blocks);
 
+/* The same probe, launched through a captured HIP graph when via_graph != 0:
+ * checks that graph replays on a gpu-let's stream honour its CU mask too. */
+gpulet_status gpulet_partition_probe_ex(gpulet_partition *p, uint32_t *out, int n_blocks,
+                                        int via_graph);
+
 /* ------------------------------------------------------------------------
  * Layers of the forward pass (Sec. 5; models of Table 4).
  * ------------------------------------------------------------------------ */
@@ -266,6 +271,37 @@ gpulet_status gpulet_model_buffer_info(const gpulet_model_desc *m, int batch, in
 gpulet_status gpulet_run_model(const gpulet_model_desc *m, int batch, gpulet_partition *p,
                                const void *in, void *out, void *workspace,
                                size_t workspace_bytes, float *latency_ms);
+
+/*
+ * The same forward pass as a HIP graph: all layers of one batch are captured
+ * once on the gpu-let's stream and replayed with a single launch, which takes
+ * the per-layer host launch cost off the latency of small batches (Sec. 3.1:
+ * small batches cannot use the whole GPU; here they are launch bound too).
+ * The graph is bound to the pointers, batch size and gpu-let given at creation;
+ * the caller keeps all of them alive and unchanged until the graph is
+ * destroyed, and destroys the graph before its gpu-let.
+ */
+typedef struct gpulet_graph gpulet_graph; /* opaque, library-owned */
+
+/* Captures and instantiates the graph.  Errors as gpulet_run_model.  *out is set
+ * only on success.  Must not be called while another thread is capturing. */
+gpulet_status gpulet_model_graph_create(const gpulet_model_desc *m, int batch, gpulet_partition *p,
+                                        const void *in, void *out_buf, void *workspace,
+                                        size_t workspace_bytes, gpulet_graph **out);
+
+/* Replays the graph once on its gpu-let's stream.  latency_ms as in
+ * gpulet_run_model (NULL: enqueue only).  Counts one batch on the gpu-let. */
+gpulet_status gpulet_model_graph_launch(gpulet_graph *g, float *latency_ms);
+
+/* Replays the graph `warmup` + `iters` times, each timed replay bracketed by its
+ * own event pair and waited for (one batch in flight), latencies as in
+ * gpulet_profile_model.  total_ms may be NULL. */
+gpulet_status gpulet_model_graph_profile(gpulet_graph *g, int warmup, int iters, float *latency_ms,
+                                         float *total_ms);
+
+/* Waits for the gpu-let's stream, then frees the graph.  NULL or an unknown
+ * handle returns GPULET_EINVAL. */
+gpulet_status gpulet_model_graph_destroy(gpulet_graph *g);
 
 /* ------------------------------------------------------------------------
  * Profiling: the L(b, p) table and co-run interference (Sec. 3.1, 3.2, 4.1).

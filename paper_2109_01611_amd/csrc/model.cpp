@@ -6,6 +6,7 @@
 #include <atomic>
 #include <chrono>
 #include <cmath>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -296,6 +297,117 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
     for (int i = 0; i < iters; ++i)
         GPULET_HIP(hipEventElapsedTime(&latency_ms[i], ev[static_cast<size_t>(i)].a, ev[static_cast<size_t>(i)].b));
     if (total_ms) GPULET_HIP(hipEventElapsedTime(total_ms, ev.front().a, ev.back().b));
+    return GPULET_OK;
+}
+
+// A captured forward pass (one batch) bound to a gpu-let.
+struct gpulet_graph {
+    gpulet_partition *part;
+    int batch;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+namespace {
+
+std::mutex g_graph_mu;
+std::vector<gpulet_graph *> g_graphs;
+
+bool graph_live(gpulet_graph *g) {
+    if (!g) return false;
+    std::lock_guard<std::mutex> lk(g_graph_mu);
+    return std::find(g_graphs.begin(), g_graphs.end(), g) != g_graphs.end();
+}
+
+hipError_t timed_replay(gpulet_graph *g, EventPair &ev, float *ms) {
+    gpulet_partition *p = g->part;
+    hipError_t e = hipEventRecord(ev.a, p->stream);
+    if (e == hipSuccess) e = hipGraphLaunch(g->exec, p->stream);
+    if (e == hipSuccess) e = hipEventRecord(ev.b, p->stream);
+    if (e == hipSuccess) e = hipEventSynchronize(ev.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(ms, ev.a, ev.b);
+    if (e == hipSuccess) {
+        p->batches_run.fetch_add(1);
+        p->images_run.fetch_add(static_cast<uint64_t>(g->batch));
+    }
+    return e;
+}
+
+}  // namespace
+
+extern "C" gpulet_status gpulet_model_graph_create(const gpulet_model_desc *m, int batch,
+                                                   gpulet_partition *p, const void *in, void *out_buf,
+                                                   void *workspace, size_t workspace_bytes,
+                                                   gpulet_graph **out) {
+    if (!out || !live(p)) return GPULET_EINVAL;
+    Plan plan;
+    gpulet_status st = build_plan(m, batch, plan);
+    if (st != GPULET_OK) return st;
+    st = check_run_args(plan, in, out_buf, workspace, workspace_bytes);
+    if (st != GPULET_OK) return st;
+    const Bound bd{&plan, in, out_buf, static_cast<char *>(workspace)};
+    GPULET_HIP(hipStreamSynchronize(p->stream));
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    GPULET_HIP(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
+    hipError_t e = enqueue(bd, p->n_cu, p->stream);
+    hipError_t e2 = hipStreamEndCapture(p->stream, &graph);  // always end the capture
+    if (e == hipSuccess) e = e2;
+    if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return hip_fail(e);
+    }
+    gpulet_graph *g = new gpulet_graph{p, batch, graph, exec};
+    {
+        std::lock_guard<std::mutex> lk(g_graph_mu);
+        g_graphs.push_back(g);
+    }
+    *out = g;
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_model_graph_launch(gpulet_graph *g, float *latency_ms) {
+    if (!graph_live(g) || !live(g->part)) return GPULET_EINVAL;
+    if (latency_ms) {
+        EventPair ev;
+        GPULET_HIP(ev.create());
+        GPULET_HIP(timed_replay(g, ev, latency_ms));
+        return GPULET_OK;
+    }
+    GPULET_HIP(hipGraphLaunch(g->exec, g->part->stream));
+    g->part->batches_run.fetch_add(1);
+    g->part->images_run.fetch_add(static_cast<uint64_t>(g->batch));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_model_graph_profile(gpulet_graph *g, int warmup, int iters,
+                                                    float *latency_ms, float *total_ms) {
+    if (!graph_live(g) || !live(g->part) || !latency_ms || iters < 1 || warmup < 0) return GPULET_EINVAL;
+    EventPair ev;
+    GPULET_HIP(ev.create());
+    float ms = 0.f;
+    for (int i = 0; i < warmup; ++i) GPULET_HIP(timed_replay(g, ev, &ms));
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int i = 0; i < iters; ++i) GPULET_HIP(timed_replay(g, ev, &latency_ms[i]));
+    if (total_ms)
+        *total_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_model_graph_destroy(gpulet_graph *g) {
+    if (!g) return GPULET_EINVAL;
+    {
+        std::lock_guard<std::mutex> lk(g_graph_mu);
+        auto it = std::find(g_graphs.begin(), g_graphs.end(), g);
+        if (it == g_graphs.end()) return GPULET_EINVAL;
+        g_graphs.erase(it);
+    }
+    hipError_t e = live(g->part) ? hipStreamSynchronize(g->part->stream) : hipSuccess;
+    (void)hipGraphExecDestroy(g->exec);
+    (void)hipGraphDestroy(g->graph);
+    delete g;
+    if (e != hipSuccess) return hip_fail(e);
     return GPULET_OK;
 }
 

@@ -187,9 +187,30 @@ extern "C" gpulet_status gpulet_partition_sync(gpulet_partition *p) {
     return GPULET_OK;
 }
 
-extern "C" gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_blocks) {
+extern "C" gpulet_status gpulet_partition_probe_ex(gpulet_partition *p, uint32_t *out, int n_blocks,
+                                                   int via_graph) {
     if (!live(p) || !out || n_blocks < 1) return GPULET_EINVAL;
-    GPULET_HIP(launch_probe(out, n_blocks, p->stream));
+    if (!via_graph) {
+        GPULET_HIP(launch_probe(out, n_blocks, p->stream));
+        GPULET_HIP(hipStreamSynchronize(p->stream));
+        return GPULET_OK;
+    }
     GPULET_HIP(hipStreamSynchronize(p->stream));
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    GPULET_HIP(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
+    hipError_t e = launch_probe(out, n_blocks, p->stream);
+    hipError_t e2 = hipStreamEndCapture(p->stream, &graph);
+    if (e == hipSuccess) e = e2;
+    if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e == hipSuccess) e = hipGraphLaunch(exec, p->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(p->stream);
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return hip_fail(e);
     return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_blocks) {
+    return gpulet_partition_probe_ex(p, out, n_blocks, 0);
 }

@@ -67,6 +67,11 @@ def _load():
         "gpulet_partition_counters": ([P, POINTER(c_uint64), POINTER(c_uint64)], c_int32),
         "gpulet_partition_sync": ([P], c_int32),
         "gpulet_partition_probe": ([P, P, I], c_int32),
+        "gpulet_partition_probe_ex": ([P, P, I, I], c_int32),
+        "gpulet_model_graph_create": ([POINTER(ModelDesc), I, P, P, P, P, c_size_t, POINTER(P)], c_int32),
+        "gpulet_model_graph_launch": ([P, FP], c_int32),
+        "gpulet_model_graph_profile": ([P, I, I, FP, FP], c_int32),
+        "gpulet_model_graph_destroy": ([P], c_int32),
         "gpulet_conv2d_fwd": ([P, P, P, P] + [I] * 10 + [P], c_int32),
         "gpulet_conv2d_fwd_ex": ([P, P, P, P] + [I] * 10 + [P, I, I, P], c_int32),
         "gpulet_set_conv_tile": ([I], c_int32),
@@ -151,8 +156,9 @@ class Partition:
     def sync(self):
         _check(lib.gpulet_partition_sync(self.handle), "gpulet_partition_sync")
 
-    def probe(self, out, n_blocks):
-        _check(lib.gpulet_partition_probe(self.handle, ptr(out), n_blocks), "gpulet_partition_probe")
+    def probe(self, out, n_blocks, via_graph=False):
+        _check(lib.gpulet_partition_probe_ex(self.handle, ptr(out), n_blocks, int(via_graph)),
+               "gpulet_partition_probe_ex")
 
     def destroy(self):
         if self.handle is not None:
@@ -221,6 +227,41 @@ def run_model(desc, batch, partition, x, y, workspace, workspace_bytes, timed=Fa
     _check(lib.gpulet_run_model(byref(desc), batch, partition.handle, ptr(x), ptr(y), ptr(workspace),
                                 workspace_bytes, byref(ms) if timed else None), "gpulet_run_model")
     return ms.value if timed else None
+
+
+class ModelGraph:
+    """A forward pass captured as a HIP graph: ``model_graph_create`` .. ``model_graph_destroy``.
+    Keeps references to the tensors it is bound to."""
+
+    def __init__(self, desc, batch, partition, x, y, workspace, workspace_bytes):
+        h = c_void_p()
+        _check(lib.gpulet_model_graph_create(byref(desc), batch, partition.handle, ptr(x), ptr(y), ptr(workspace),
+                                             workspace_bytes, byref(h)), "gpulet_model_graph_create")
+        self.handle = h
+        self._keep = (desc, partition, x, y, workspace)
+
+    def launch(self, timed=False):
+        ms = c_float()
+        _check(lib.gpulet_model_graph_launch(self.handle, byref(ms) if timed else None), "gpulet_model_graph_launch")
+        return ms.value if timed else None
+
+    def profile(self, warmup, iters):
+        lat = (c_float * iters)()
+        total = c_float()
+        _check(lib.gpulet_model_graph_profile(self.handle, warmup, iters, lat, byref(total)),
+               "gpulet_model_graph_profile")
+        return list(lat), total.value
+
+    def destroy(self):
+        if self.handle is not None:
+            h, self.handle = self.handle, None
+            _check(lib.gpulet_model_graph_destroy(h), "gpulet_model_graph_destroy")
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
 
 
 def profile_model(desc, batch, partition, x, y, workspace, workspace_bytes, warmup, iters,
