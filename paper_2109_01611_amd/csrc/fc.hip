@@ -3,10 +3,10 @@
 //
 // At serving batch sizes (1-32, Fig. 3) this GEMM has as many rows as the
 // batch, so it is bound by streaming the [Out][In] weights from HBM once.
-// A workgroup owns 16 outputs and up to 32 batch rows; its four wavefronts each
-// stream a contiguous quarter of the In range straight from global memory into
+// A workgroup owns 16 outputs and up to 32 batch rows; its wavefronts (4, or 16
+// for long rows) each stream a contiguous share of the In range straight from global memory into
 // v_mfma_f32_16x16x32_bf16 operands (no LDS staging: every weight is used
-// once), then the four partial accumulators are summed through LDS and the
+// once), then the partial accumulators are summed through LDS and the
 // first wavefront adds bias, applies ReLU and stores bf16 or fp32.
 #include <hip/hip_runtime.h>
 
@@ -46,10 +46,12 @@ __device__ __forceinline__ uint4 load_chunk(const __bf16 *row_ptr, int k, int In
                       e[4] | ((unsigned)e[5] << 16), e[6] | ((unsigned)e[7] << 16));
 }
 
-// NB = batch tiles of 16 rows handled per workgroup (1 or 2).
-template <int NB, bool VEC>
-__global__ __launch_bounds__(256) void fc_kernel(const FcParams p) {
-    __shared__ float red[3][NB][64][4];
+// NB = batch tiles of 16 rows handled per workgroup (1 or 2); NW = wavefronts
+// that split the In range (4, or 16 for long rows so that enough loads are in
+// flight per CU to keep HBM busy).
+template <int NB, int NW, bool VEC>
+__global__ __launch_bounds__(NW * 64) void fc_kernel(const FcParams p) {
+    __shared__ float red[NW - 1][NB][64][4];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int o0 = blockIdx.x * 16;
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcParams p) {
     }
 
     const int steps = (p.In + 31) / 32;
-    const int per_wave = (steps + 3) / 4;
+    const int per_wave = (steps + NW - 1) / NW;
     const int s_begin = wave * per_wave;
     const int s_end = min(steps, s_begin + per_wave);
 
@@ -111,7 +113,9 @@ __global__ __launch_bounds__(256) void fc_kernel(const FcParams p) {
     for (int t = 0; t < NB; ++t) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            float val = acc[t][v] + red[0][t][lane][v] + red[1][t][lane][v] + red[2][t][lane][v];
+            float val = acc[t][v];
+#pragma unroll
+            for (int w = 0; w < NW - 1; ++w) val += red[w][t][lane][v];
             const int n = n0 + t * 16 + 4 * kq + v;
             if (!o_ok || n >= p.N) continue;
             val += bias;
@@ -145,19 +149,18 @@ hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int 
     const bool vec = (In % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(w) % 16 == 0);
     const unsigned gx = static_cast<unsigned>((Out + 15) / 16);
+    const bool wide = In >= 8192;  // long rows: 16 wavefronts per workgroup
+    const dim3 grid(gx, N <= 16 ? 1u : static_cast<unsigned>((N + 31) / 32));
+#define GPULET_FC_LAUNCH(NB, NW, V) \
+    hipLaunchKernelGGL((fc_kernel<NB, NW, V>), grid, dim3(NW * 64), 0, stream, p)
     if (N <= 16) {
-        const dim3 grid(gx, 1);
-        if (vec)
-            hipLaunchKernelGGL((fc_kernel<1, true>), grid, dim3(256), 0, stream, p);
-        else
-            hipLaunchKernelGGL((fc_kernel<1, false>), grid, dim3(256), 0, stream, p);
+        if (wide) { if (vec) GPULET_FC_LAUNCH(1, 16, true); else GPULET_FC_LAUNCH(1, 16, false); }
+        else { if (vec) GPULET_FC_LAUNCH(1, 4, true); else GPULET_FC_LAUNCH(1, 4, false); }
     } else {
-        const dim3 grid(gx, static_cast<unsigned>((N + 31) / 32));
-        if (vec)
-            hipLaunchKernelGGL((fc_kernel<2, true>), grid, dim3(256), 0, stream, p);
-        else
-            hipLaunchKernelGGL((fc_kernel<2, false>), grid, dim3(256), 0, stream, p);
+        if (wide) { if (vec) GPULET_FC_LAUNCH(2, 16, true); else GPULET_FC_LAUNCH(2, 16, false); }
+        else { if (vec) GPULET_FC_LAUNCH(2, 4, true); else GPULET_FC_LAUNCH(2, 4, false); }
     }
+#undef GPULET_FC_LAUNCH
     return hipGetLastError();
 }
 
