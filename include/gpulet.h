@@ -174,6 +174,19 @@ gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b,
 enum { GPULET_CONV_TILES = 7 };
 gpulet_status gpulet_set_conv_tile(int tile);
 
+/*
+ * Largest number of workgroups that may share one output tile by splitting the
+ * depth (1..8; default 1 = splitting off).  When allowed, splitting is used on a
+ * gpu-let's stream when a layer has too few tiles for the gpu-let's CUs; partial
+ * tiles meet in scratch memory owned by the gpu-let and are summed in fp32 in a
+ * fixed order, so results are reproducible run to run, but they differ in the
+ * last bits from the unsplit sum.  With splitting off, an image's result does
+ * not depend on the batch it is part of or on the gpu-let's size.  A forced tile
+ * (gpulet_set_conv_tile) never splits.  Launches on streams that do not belong
+ * to a gpu-let never split.
+ */
+gpulet_status gpulet_set_conv_split_k(int max_split);
+
 enum { GPULET_POOL_MAX = 0, GPULET_POOL_AVG = 1, GPULET_POOL_GLOBAL_AVG = 2 };
 
 /*

@@ -52,6 +52,10 @@ struct ConvParams {
     unsigned x_bytes, w_bytes;
     int tap_inner;      // depth order: 64-channel block outermost, filter taps inside it
     int vec_store;      // output (and residual) rows allow aligned 16-byte accesses
+    int split_k;        // workgroups sharing one output tile, each taking a contiguous range of slices
+    int sps;            // slices per split
+    float *part;        // split-K scratch: [n_tiles * split_k][BM * BN] fp32 partial tiles
+    unsigned *cnt;      // split-K scratch: arrival counter per tile (zero between launches)
 };
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
@@ -160,14 +164,19 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     constexpr int RING = NS * STAGE > BM * LDT * 2 ? NS * STAGE : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 ring[RING];
 
-    const int tile = tile_of_block(p);
-    if (tile >= p.n_tiles) return;
+    // Split-K: consecutive work items share an output tile and each takes a
+    // contiguous range of depth slices.
+    const int item = tile_of_block(p);
+    if (item >= p.n_tiles * p.split_k) return;
+    const int tile = item / p.split_k, ks = item - tile * p.split_k;
     const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nk = (p.Kg + BK - 1) / BK;
+    const int nk_all = (p.Kg + BK - 1) / BK;
+    const int k_first = ks * p.sps;                                  // first slice of this workgroup
+    const int nk = max(0, min(nk_all, k_first + p.sps) - k_first);  // slices of this workgroup
 
     f32x16 acc[MT][NT];  // consumers only
 
@@ -221,8 +230,24 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         // workgroup just fetched for one tap are fetched again for the next while
         // they are still in the nearest cache.  Both operands use the same order,
         // so only the summation order of the result changes.
-        int g = cc * CHUNK, r = 0, s = 0, c = cc * CHUNK, tap = cc * CHUNK * 2;
-        int cblk = 0, issued = 0;
+        int g, r, s, c, tap, cblk = 0, issued = 0;
+        if (!POINTWISE && p.tap_inner) {
+            const int rs = p.R * p.S;
+            const int cb = k_first / rs, t = k_first - cb * rs;
+            r = t / p.S;
+            s = t - r * p.S;
+            cblk = cb * BK;
+            c = cblk + cc * CHUNK;
+            g = t * p.C + c;
+            tap = ((r * p.W + s) * p.C + c) * 2;
+        } else {
+            g = k_first * BK + cc * CHUNK;
+            const int t = g / p.C;
+            c = g - t * p.C;
+            r = t / p.S;
+            s = t - r * p.S;
+            tap = ((r * p.W + s) * p.C + c) * 2;
+        }
         auto normalise = [&]() {
             while (c >= p.C) {
                 c -= p.C;
@@ -233,12 +258,11 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
                 }
             }
         };
-        if (!POINTWISE) normalise();
 
         // Starts the transfer of the next depth slice into `stage` and advances the
         // position.  Slices past the end of the depth transfer zeros nobody reads.
         auto issue_next = [&](const __bf16 *stage) {
-            const bool g_ok = p.tap_inner ? issued < nk : g < p.Kg;
+            const bool g_ok = issued < nk && g < p.Kg;
             unsigned base = lds_addr(stage) + pw * 8 * (BK * 2);
 #pragma unroll
             for (int i = 0; i < AINS; ++i) {
@@ -356,21 +380,89 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             const int col = wx * WN + j * 32 + frow;
-            const int k = n0 + col;
-            const float bias = (p.b && k < p.K) ? p.b[k] : 0.f;
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = wy * WM + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
-                    stg[row * LDT + col] = acc[i][j][v] + bias;
+                    stg[row * LDT + col] = acc[i][j][v];
                 }
         }
     }
     __syncthreads();
+    constexpr int NTHR = (NCONS + NPROD) * 64;
     constexpr int VPR = BN / 8;  // 8-channel groups per tile row
+
+    // Split-K: every workgroup but the last to arrive parks its partial tile in
+    // scratch and leaves; the last one adds the others' tiles to its own, always
+    // in split order so the sum does not depend on who came last.  Arrival is
+    // counted with one atomic per workgroup; nobody ever waits.
+    //
+    // The dies' L2 caches are not coherent with one another, and a device-wide
+    // fence would write back and invalidate a whole L2.  So the partial tiles and
+    // the counter are accessed with device-scope (cache-bypassing) loads and
+    // stores only, and a workgroup waits for its own stores to be acknowledged
+    // before it counts itself in.
+    if (p.split_k > 1) {
+        constexpr int DEVICE_SCOPE = 16;  // cache policy sc1: device scope, bypasses the die-local caches
+        const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+            p.part, 0, p.n_tiles * p.split_k * (BM * BN * 4), RSRC_FLAGS);
+        const int mine = (tile * p.split_k + ks) * (BM * BN * 4);  // byte offset of this workgroup's tile
+        for (int it = threadIdx.x; it < BM * VPR; it += NTHR) {
+            const int row = it / VPR, cv = it - row * VPR;
+            const u32x4 lo = *reinterpret_cast<const u32x4 *>(&stg[row * LDT + cv * 8]);
+            const u32x4 hi = *reinterpret_cast<const u32x4 *>(&stg[row * LDT + cv * 8 + 4]);
+            __builtin_amdgcn_raw_buffer_store_b128(lo, rp, mine + (row * BN + cv * 8) * 4, 0, DEVICE_SCOPE);
+            __builtin_amdgcn_raw_buffer_store_b128(hi, rp, mine + (row * BN + cv * 8 + 4) * 4, 0, DEVICE_SCOPE);
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this lane's partial-tile stores have reached memory
+        __syncthreads();
+        __shared__ unsigned arrived;
+        if (threadIdx.x == 0) {
+            arrived = __hip_atomic_fetch_add(&p.cnt[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (arrived == static_cast<unsigned>(p.split_k - 1))  // ready for the next launch
+                __hip_atomic_store(&p.cnt[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (arrived != static_cast<unsigned>(p.split_k - 1)) return;
+        const int base = tile * p.split_k * (BM * BN * 4);
+        constexpr int ITEMS = (BM * VPR + NTHR - 1) / NTHR;  // 8-channel groups per thread
+        float sum[ITEMS][8];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[i][e] = 0.f;
+        for (int q = 0; q < p.split_k; ++q) {
+            u32x4 a[ITEMS], b[ITEMS];
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {  // all loads of one partial tile in flight together
+                const int it = threadIdx.x + i * NTHR;
+                const int row = it / VPR, cv = it - row * VPR;
+                const int off = it < BM * VPR ? base + q * (BM * BN * 4) + (row * BN + cv * 8) * 4 : static_cast<int>(OOB);
+                a[i] = __builtin_amdgcn_raw_buffer_load_b128(rp, off, 0, DEVICE_SCOPE);
+                b[i] = __builtin_amdgcn_raw_buffer_load_b128(rp, off + 16, 0, DEVICE_SCOPE);
+            }
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    sum[i][e] += __uint_as_float(a[i][e]);
+                    sum[i][4 + e] += __uint_as_float(b[i][e]);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int it = threadIdx.x + i * NTHR;
+            if (it < BM * VPR) {
+                const int row = it / VPR, cv = it - row * VPR;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) stg[row * LDT + cv * 8 + e] = sum[i][e];
+            }
+        }
+        // each thread re-reads only what it wrote itself, in the same iteration order
+    }
     const bool vec_ok = p.vec_store;
-    for (int it = threadIdx.x; it < BM * VPR; it += (NCONS + NPROD) * 64) {
+    for (int it = threadIdx.x; it < BM * VPR; it += NTHR) {
         const int row = it / VPR, cv = it - row * VPR;
         const int m = m0 + row, k = n0 + cv * 8;
         if (m >= p.M || k >= p.K) continue;
@@ -378,6 +470,12 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         if (vec_ok && k + 8 <= p.K) {
+            if (p.b) {
+                const float4 b0 = *reinterpret_cast<const float4 *>(p.b + k);
+                const float4 b1 = *reinterpret_cast<const float4 *>(p.b + k + 4);
+                v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+            }
             if (p.res) {
                 const uint4 rr = *reinterpret_cast<const uint4 *>(p.res + (m * p.K + k));
                 const unsigned ru[4] = {rr.x, rr.y, rr.z, rr.w};
@@ -402,7 +500,7 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
             *reinterpret_cast<uint4 *>(p.y + (m * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         } else {
             for (int e = 0; e < 8 && k + e < p.K; ++e) {
-                float a = v[e];
+                float a = v[e] + (p.b ? p.b[k + e] : 0.f);
                 if (p.res) a += static_cast<float>(p.res[m * p.K + k + e]);
                 if (p.relu) a = a > 0.f ? a : 0.f;
                 p.y[m * p.ldy + p.y_off + k + e] = static_cast<__bf16>(a);
@@ -552,11 +650,14 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_any_kernel(const ConvPara
 // CWM x CWN consumers and NPROD producers for the main kernel; the scalar-gather
 // kernel always runs four wavefronts as WGM x WGN.
 template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, int WGM, int WGN>
-hipError_t launch_tile(ConvParams p, bool vec, hipStream_t stream) {
+hipError_t launch_tile(ConvParams p, bool vec, int split_k, hipStream_t stream) {
     const int tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.K + BN - 1) / BN;
     p.n_tiles = tiles_m * p.tiles_n;
-    p.tiles_per_xcd = (p.n_tiles + 7) / 8;
+    const int nk = (p.Kg + BK - 1) / BK;
+    p.split_k = vec ? split_k : 1;
+    p.sps = (nk + p.split_k - 1) / p.split_k;
+    p.tiles_per_xcd = (p.n_tiles * p.split_k + 7) / 8;  // work items per die
     const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8));
     const dim3 block((CWM * CWN + NPROD) * 64);
     const bool pointwise = p.R == 1 && p.S == 1 && p.pad == 0;
@@ -568,6 +669,10 @@ hipError_t launch_tile(ConvParams p, bool vec, hipStream_t stream) {
         hipLaunchKernelGGL((conv_igemm_any_kernel<BM, BN, WGM, WGN>), grid, dim3(NTHREADS), 0, stream, p);
     return hipGetLastError();
 }
+
+// Off by default: the partial tiles cross dies through memory, which costs about 8 us per
+// launch on MI355X and only pays for layers with very few tiles and a very long depth.
+std::atomic<int> g_max_split_k{1};
 
 std::atomic<int> g_tile_override{-1};
 
@@ -596,7 +701,7 @@ gpulet_status check_conv(const ConvArgs &a) {
     return GPULET_OK;
 }
 
-hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
+hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream) {
     ConvParams p;
     p.x = static_cast<const __bf16 *>(a.x);
     p.w = static_cast<const __bf16 *>(a.w);
@@ -614,45 +719,69 @@ hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream) {
     p.w_bytes = static_cast<unsigned>(2LL * a.K * a.R * a.S * a.C);
     p.tap_inner = (a.C % BK == 0 && a.R * a.S > 1) ? 1 : 0;
     p.vec_store = (a.y_ch_stride % 8 == 0 && a.y_ch_offset % 8 == 0 && reinterpret_cast<uintptr_t>(a.y) % 16 == 0 &&
+                   reinterpret_cast<uintptr_t>(a.b) % 16 == 0 &&
                    (!a.residual || (a.K % 8 == 0 && reinterpret_cast<uintptr_t>(a.residual) % 16 == 0)))
                       ? 1
                       : 0;
+    p.split_k = 1;
+    p.sps = 0;
+    p.part = ctx.scratch;
+    p.cnt = ctx.counters;
 
     const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
 
-    // Pick the tile that minimises (workgroups the busiest CU runs) x (tile area) / efficiency.
+    // Pick the tile and the split of the depth that minimise
+    //   (work items on the busiest CU) x (tile area) x (share of the depth + fixed cost of a split) / efficiency.
     // The efficiencies are measured throughput ratios on MI355X (large layers, all CUs busy);
-    // on a tie the earlier entry wins.
+    // on a tie the earlier entry wins.  A split needs the gpu-let's scratch, at least four
+    // slices per workgroup, and pays for parking and re-reading fp32 partial tiles.
     static const TileChoice kTiles[] = {{128, 128, 0.90f}, {128, 64, 0.72f}, {64, 128, 0.72f}, {64, 64, 0.58f},
                                         {128, 32, 0.30f},  {32, 128, 0.40f}, {256, 128, 1.00f}};
     static const int kOrder[] = {6, 0, 2, 1, 3, 5, 4};
-    int best = 0;
+    const int nk = (p.Kg + BK - 1) / BK;
+    const int forced = g_tile_override.load();
+    const int max_split = (vec && ctx.scratch && forced < 0) ? g_max_split_k.load() : 1;
+    int best = 0, best_split = 1;
     double best_cost = 0.0;
-    if (n_cu < 1) n_cu = 1;
+    const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
     for (int o = 0; o < GPULET_CONV_TILES; ++o) {
         const int i = kOrder[o];
         const TileChoice &t = kTiles[i];
-        const long long blocks = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
-        const long long per_cu = (blocks + n_cu - 1) / n_cu;
-        const double cost = static_cast<double>(per_cu) * t.bm * t.bn / t.eff;
-        if (o == 0 || cost < best_cost) {
-            best = i;
-            best_cost = cost;
+        const long long tiles = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
+        for (int sk = 1; sk <= max_split; ++sk) {
+            if (sk > 1) {
+                const int sps = (nk + sk - 1) / sk;
+                if (sps < 4 || (sk - 1) * sps >= nk) continue;                         // too thin, or an empty split
+                if (tiles > ctx.n_counters) continue;
+                if (static_cast<size_t>(tiles) * sk * t.bm * t.bn * 4 > ctx.scratch_bytes) continue;
+            }
+            const long long per_cu = (tiles * sk + n_cu - 1) / n_cu;
+            const double share = 1.0 / sk + (sk > 1 ? 0.06 + 0.02 * sk : 0.0);
+            const double cost = static_cast<double>(per_cu) * t.bm * t.bn * share / t.eff;
+            if ((o == 0 && sk == 1) || cost < best_cost) {
+                best = i;
+                best_split = sk;
+                best_cost = cost;
+            }
         }
     }
-    const int forced = g_tile_override.load();
-    if (forced >= 0 && forced < GPULET_CONV_TILES) best = forced;
+    if (forced >= 0 && forced < GPULET_CONV_TILES) {
+        best = forced;
+        best_split = 1;
+    }
     switch (best) {
-        case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
-        case 1: return launch_tile<128, 64, 4, 2, 4, 3, 2, 2>(p, vec, stream);
-        case 2: return launch_tile<64, 128, 2, 4, 4, 3, 2, 2>(p, vec, stream);
-        case 3: return launch_tile<64, 64, 2, 2, 2, 3, 2, 2>(p, vec, stream);
-        case 4: return launch_tile<128, 32, 4, 1, 2, 3, 4, 1>(p, vec, stream);
-        case 5: return launch_tile<32, 128, 1, 4, 2, 3, 1, 4>(p, vec, stream);
-        default: return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, stream);
+        case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
+        case 1: return launch_tile<128, 64, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
+        case 2: return launch_tile<64, 128, 2, 4, 4, 3, 2, 2>(p, vec, best_split, stream);
+        case 3: return launch_tile<64, 64, 2, 2, 2, 3, 2, 2>(p, vec, best_split, stream);
+        case 4: return launch_tile<128, 32, 4, 1, 2, 3, 4, 1>(p, vec, best_split, stream);
+        case 5: return launch_tile<32, 128, 1, 4, 2, 3, 1, 4>(p, vec, best_split, stream);
+        default: return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
     }
 }
+
+void set_conv_split_k(int max_split) { g_max_split_k.store(max_split); }
 
 void set_conv_tile(int tile) { g_tile_override.store(tile); }
 

@@ -34,6 +34,10 @@ struct gpulet_partition {
     int n_words;
     uint32_t mask[gpulet::kMaxMaskWords];
     hipStream_t stream;
+    void *scratch;          // device memory for split-K partial tiles, owned by the gpu-let
+    size_t scratch_bytes;
+    unsigned *counters;     // device arrival counters for split-K, zero between launches
+    int n_counters;
     std::atomic<uint64_t> batches_run;
     std::atomic<uint64_t> images_run;
 };
@@ -50,9 +54,18 @@ inline int out_extent(int in, int k, int stride, int pad) {
     return span < 0 ? 0 : span / stride + 1;
 }
 
-// Number of CUs a launch on `stream` may use: the owning gpu-let's CU count if the
-// stream belongs to one, else the device's.  Tile selection keys on it.
-int stream_cu_count(hipStream_t stream);
+// What a launch on a stream may use: the CU count tile selection keys on and, for
+// a gpu-let's stream, the gpu-let's private split-K scratch (none otherwise, which
+// switches split-K off).  Work on one stream is serial, so the scratch is never shared.
+struct LaunchCtx {
+    int n_cu = 256;
+    float *scratch = nullptr;
+    size_t scratch_bytes = 0;
+    unsigned *counters = nullptr;
+    int n_counters = 0;
+};
+LaunchCtx stream_ctx(hipStream_t stream);
+LaunchCtx partition_ctx(const gpulet_partition *p);
 
 // Kernel launchers (conv.hip, pool.hip, fc.hip).  Arguments are validated by the callers.
 struct ConvArgs {
@@ -62,8 +75,9 @@ struct ConvArgs {
     const void *residual;
     int N, C, H, W, K, R, S, stride, pad, relu, P, Q, y_ch_stride, y_ch_offset;
 };
-hipError_t launch_conv(const ConvArgs &a, int n_cu, hipStream_t stream);
+hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 void set_conv_tile(int tile);
+void set_conv_split_k(int max_split);
 hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P, int Q, int mode,
                        int k, int stride, int pad, hipStream_t stream);
 hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,

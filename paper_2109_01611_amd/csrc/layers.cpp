@@ -32,7 +32,7 @@ extern "C" gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, cons
                                       y_ch_stride, y_ch_offset);
     if (st != GPULET_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    GPULET_HIP(launch_conv(a, stream_cu_count(s), s));
+    GPULET_HIP(launch_conv(a, stream_ctx(s), s));
     return GPULET_OK;
 }
 
@@ -46,6 +46,12 @@ extern "C" gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const f
 extern "C" gpulet_status gpulet_set_conv_tile(int tile) {
     if (tile < -1 || tile >= GPULET_CONV_TILES) return GPULET_EINVAL;
     set_conv_tile(tile);
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_set_conv_split_k(int max_split) {
+    if (max_split < 1 || max_split > 8) return GPULET_EINVAL;
+    set_conv_split_k(max_split);
     return GPULET_OK;
 }
 
@@ -80,8 +86,8 @@ extern "C" gpulet_status gpulet_time_conv2d(const void *x, const void *w, const 
                                       y_ch_stride, y_ch_offset);
     if (st != GPULET_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int n_cu = stream_cu_count(s);
-    for (int i = 0; i < warmup; ++i) GPULET_HIP(launch_conv(a, n_cu, s));
+    const LaunchCtx ctx = stream_ctx(s);
+    for (int i = 0; i < warmup; ++i) GPULET_HIP(launch_conv(a, ctx, s));
     hipEvent_t e0 = nullptr, e1 = nullptr;
     GPULET_HIP(hipEventCreate(&e0));
     hipError_t e = hipEventCreate(&e1);
@@ -90,7 +96,7 @@ extern "C" gpulet_status gpulet_time_conv2d(const void *x, const void *w, const 
         return hip_fail(e);
     }
     e = hipEventRecord(e0, s);
-    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_conv(a, n_cu, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_conv(a, ctx, s);
     if (e == hipSuccess) e = hipEventRecord(e1, s);
     if (e == hipSuccess) e = hipEventSynchronize(e1);
     float ms = 0.f;

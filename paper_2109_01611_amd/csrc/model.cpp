@@ -148,7 +148,7 @@ struct Bound {
 };
 
 // Enqueues every layer of one batch on `stream`; no host synchronisation.
-hipError_t enqueue(const Bound &bd, int n_cu, hipStream_t stream) {
+hipError_t enqueue(const Bound &bd, const LaunchCtx &ctx, hipStream_t stream) {
     for (const Step &s : bd.plan->steps) {
         hipError_t e;
         if (s.op == GPULET_OP_CONV) {
@@ -156,7 +156,7 @@ hipError_t enqueue(const Bound &bd, int n_cu, hipStream_t stream) {
             a.x = bd.ptr(s.in_buf);
             a.y = bd.ptr(s.out_buf);
             a.residual = s.res_buf >= 0 ? bd.ptr(s.res_buf) : nullptr;
-            e = launch_conv(a, n_cu, stream);
+            e = launch_conv(a, ctx, stream);
         } else if (s.op == GPULET_OP_POOL) {
             e = launch_pool(bd.ptr(s.in_buf), bd.ptr(s.out_buf), s.N, s.C, s.H, s.W, s.P, s.Q, s.mode, s.k,
                             s.stride, s.pad, stream);
@@ -200,7 +200,7 @@ struct EventPair {
 // One timed batch, waited for: returns its elapsed milliseconds.
 hipError_t timed_batch(const Bound &bd, gpulet_partition *p, int batch, EventPair &ev, float *ms) {
     hipError_t e = hipEventRecord(ev.a, p->stream);
-    if (e == hipSuccess) e = enqueue(bd, p->n_cu, p->stream);
+    if (e == hipSuccess) e = enqueue(bd, partition_ctx(p), p->stream);
     if (e == hipSuccess) e = hipEventRecord(ev.b, p->stream);
     if (e == hipSuccess) e = hipEventSynchronize(ev.b);
     if (e == hipSuccess) e = hipEventElapsedTime(ms, ev.a, ev.b);
@@ -256,7 +256,7 @@ extern "C" gpulet_status gpulet_run_model(const gpulet_model_desc *m, int batch,
         GPULET_HIP(timed_batch(bd, p, batch, ev, latency_ms));
         return GPULET_OK;
     }
-    GPULET_HIP(enqueue(bd, p->n_cu, p->stream));
+    GPULET_HIP(enqueue(bd, partition_ctx(p), p->stream));
     p->batches_run.fetch_add(1);
     p->images_run.fetch_add(static_cast<uint64_t>(batch));
     return GPULET_OK;
@@ -276,7 +276,7 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
     const Bound bd{&plan, in, out, static_cast<char *>(workspace)};
 
     for (int i = 0; i < warmup; ++i) {
-        GPULET_HIP(enqueue(bd, p->n_cu, p->stream));
+        GPULET_HIP(enqueue(bd, partition_ctx(p), p->stream));
         p->batches_run.fetch_add(1);
         p->images_run.fetch_add(static_cast<uint64_t>(batch));
     }
@@ -287,7 +287,7 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
     for (int i = 0; i < iters; ++i) {
         EventPair &e = ev[static_cast<size_t>(i)];
         GPULET_HIP(hipEventRecord(e.a, p->stream));
-        GPULET_HIP(enqueue(bd, p->n_cu, p->stream));
+        GPULET_HIP(enqueue(bd, partition_ctx(p), p->stream));
         GPULET_HIP(hipEventRecord(e.b, p->stream));
         p->batches_run.fetch_add(1);
         p->images_run.fetch_add(static_cast<uint64_t>(batch));
@@ -350,7 +350,7 @@ extern "C" gpulet_status gpulet_model_graph_create(const gpulet_model_desc *m, i
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
     GPULET_HIP(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
-    hipError_t e = enqueue(bd, p->n_cu, p->stream);
+    hipError_t e = enqueue(bd, partition_ctx(p), p->stream);
     hipError_t e2 = hipStreamEndCapture(p->stream, &graph);  // always end the capture
     if (e == hipSuccess) e = e2;
     if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);

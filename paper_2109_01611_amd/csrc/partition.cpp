@@ -58,17 +58,28 @@ bool live(const gpulet_partition *p) {
     return false;
 }
 
-int stream_cu_count(hipStream_t stream) {
+LaunchCtx partition_ctx(const gpulet_partition *p) {
+    LaunchCtx c;
+    c.n_cu = p->n_cu;
+    c.scratch = static_cast<float *>(p->scratch);
+    c.scratch_bytes = p->scratch_bytes;
+    c.counters = p->counters;
+    c.n_counters = p->n_counters;
+    return c;
+}
+
+LaunchCtx stream_ctx(hipStream_t stream) {
     {
         std::lock_guard<std::mutex> lk(g_mu);
         for (const gpulet_partition *p : g_live)
-            if (p->stream == stream) return p->n_cu;
+            if (p->stream == stream) return partition_ctx(p);
     }
+    LaunchCtx c;
     int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-        return 256;
-    return n;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+        c.n_cu = n;
+    return c;
 }
 
 }  // namespace gpulet
@@ -109,8 +120,23 @@ extern "C" gpulet_status gpulet_partition_create(int device, int pct, int which,
     GPULET_HIP(hipSetDevice(device));
     hipStream_t stream = nullptr;
     hipError_t e = hipExtStreamCreateWithCUMask(&stream, static_cast<uint32_t>(n_words), words);
+    // Split-K scratch of the gpu-let: partial tiles and zeroed arrival counters.
+    constexpr size_t kScratchBytes = 64u << 20;
+    constexpr int kCounters = 4096;
+    void *scratch = nullptr;
+    unsigned *counters = nullptr;
+    if (e == hipSuccess) e = hipMalloc(&scratch, kScratchBytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&counters), kCounters * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(counters, 0, kCounters * sizeof(unsigned));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        if (scratch) (void)hipFree(scratch);
+        if (counters) (void)hipFree(counters);
+        if (stream) (void)hipStreamDestroy(stream);
+        (void)hipSetDevice(prev);
+        return hip_fail(e);
+    }
     (void)hipSetDevice(prev);
-    if (e != hipSuccess) return hip_fail(e);
 
     gpulet_partition *p = new gpulet_partition();
     p->device = device;
@@ -121,6 +147,10 @@ extern "C" gpulet_status gpulet_partition_create(int device, int pct, int which,
     p->n_words = n_words;
     std::memcpy(p->mask, words, sizeof words);
     p->stream = stream;
+    p->scratch = scratch;
+    p->scratch_bytes = kScratchBytes;
+    p->counters = counters;
+    p->n_counters = kCounters;
     p->batches_run.store(0);
     p->images_run.store(0);
     g_live.push_back(p);
@@ -142,6 +172,8 @@ extern "C" gpulet_status gpulet_partition_destroy(gpulet_partition *p) {
     }
     hipError_t e1 = hipStreamSynchronize(stream);
     hipError_t e2 = hipStreamDestroy(stream);
+    (void)hipFree(p->scratch);
+    (void)hipFree(p->counters);
     delete p;
     if (e1 != hipSuccess) return hip_fail(e1);
     if (e2 != hipSuccess) return hip_fail(e2);

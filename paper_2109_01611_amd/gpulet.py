@@ -75,6 +75,7 @@ def _load():
         "gpulet_conv2d_fwd": ([P, P, P, P] + [I] * 10 + [P], c_int32),
         "gpulet_conv2d_fwd_ex": ([P, P, P, P] + [I] * 10 + [P, I, I, P], c_int32),
         "gpulet_set_conv_tile": ([I], c_int32),
+        "gpulet_set_conv_split_k": ([I], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
         "gpulet_model_workspace_bytes": ([POINTER(ModelDesc), I, POINTER(c_size_t)], c_int32),
@@ -186,6 +187,10 @@ def conv2d_fwd_ex(x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual=N
 
 def set_conv_tile(tile):
     _check(lib.gpulet_set_conv_tile(tile), "gpulet_set_conv_tile")
+
+
+def set_conv_split_k(max_split):
+    _check(lib.gpulet_set_conv_split_k(max_split), "gpulet_set_conv_split_k")
 
 
 def pool(x, y, N, C, H, W, mode, k=1, stride=1, pad=0, stream=None):

@@ -113,10 +113,17 @@ def test_serving_batch_sizes_on_sampled_images(name, batch, pct, which):
 
 
 def test_batch_size_does_not_change_an_images_result():
+    # default: no depth splitting, so an image's logits are independent of its batch and gpu-let
     model = workloads.resnet50(width_div=2, in_hw=96, n_class=50)
     a, _, _, _, _, _ = _run(model, 2, seed=7, images=[0])
     b, _, _, _, _, _ = _run(model, 9, 40, 0, seed=7, images=[0])
     assert np.array_equal(a[:2], b[:2])
+    gpulet.set_conv_split_k(4)       # splitting allowed: sums may be regrouped, equal to rounding noise only
+    try:
+        c, _, _, _, _, _ = _run(model, 9, 40, 0, seed=7, images=[0])
+    finally:
+        gpulet.set_conv_split_k(1)
+    assert oracle.rel_err(c[:2], a[:2])[1] <= MODEL_TOL
 
 
 def test_corun_two_gpulets_gives_same_results_and_counts():
