@@ -8,19 +8,27 @@
 // x is NHWC and w is KRSC, so both operands are contiguous along the depth
 // and neither the im2col matrix nor a transposed weight is ever built.
 //
-// One workgroup of four wavefronts owns a BM x BN output tile and walks the
-// depth in slices of 64.  Each slice is gathered from global memory as 16-byte
-// chunks (8 channels of one tap) with buffer loads whose hardware range check
-// returns zeros for padding taps and ragged edges, so the gather is branch
-// free.  Chunks pass through a two-slice-deep register pipeline into a
-// double-buffered, XOR-swizzled LDS tile; wavefronts read 8-element fragments
-// back with ds_read_b128 and feed v_mfma_f32_32x32x16_bf16.  Accumulators stay
-// in registers for the whole depth.  The epilogue adds bias and the optional
-// residual in fp32, applies ReLU, rounds once to bf16 and stores, optionally
-// at a channel offset inside a wider (concatenated) tensor.
+// One workgroup owns a BM x BN output tile and walks the depth in slices of 64.
+// Its wavefronts are specialised.  Producer wavefronts only compute addresses
+// and issue 16-byte buffer loads (8 channels of one tap) that land directly in
+// LDS without passing through registers; the hardware range check of the
+// buffer descriptor returns zeros for padding taps and ragged edges, so the
+// gather has no branches.  Consumer wavefronts only read 8-element fragments
+// back from the XOR-swizzled LDS tile with ds_read_b128 and feed
+// v_mfma_f32_32x32x16_bf16; accumulators stay in registers for the whole
+// depth.  Slices travel through a ring of three LDS stages, two loads ahead of
+// the one being multiplied, with one workgroup barrier per slice.  When the
+// channel count is a multiple of 64 the depth is walked with the filter taps
+// innermost, so a producer's lane keeps its channel offset and only steps the
+// tap.  The epilogue parks the fp32 tile in the idle ring, adds bias and the
+// optional residual, applies ReLU, rounds once to bf16 and writes 16-byte
+// rows, optionally at a channel offset inside a wider (concatenated) tensor.
+// Optionally several workgroups share a tile by splitting the depth; partial
+// tiles meet in device scratch and the last one to arrive reduces them in a
+// fixed order.
 //
 // Channel counts that are not multiples of 8 (image stems, LeNet) take a
-// scalar-gather variant of the same tiling.
+// scalar-gather variant of the same tiling with four wavefronts.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
@@ -36,7 +44,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 constexpr int BK = 64;         // depth slice per main-loop step (elements)
 constexpr int CHUNK = 8;       // elements per 16-byte chunk
-constexpr int NTHREADS = 256;  // four wavefronts
+constexpr int NTHREADS = 256;  // scalar-gather variant: four wavefronts
 constexpr unsigned OOB = 0x80000000u;      // byte offset past every buffer: the load returns zeros
 constexpr int RSRC_FLAGS = 0x00020000;     // raw buffer descriptor, 32-bit data format
 
