@@ -35,11 +35,13 @@ closed forms.  The readings taken here:
   other gpu-let of the same GPU is occupied (largest value over the models
   there).  A placement is also refused when it would push a model already on
   the partner gpu-let over its own budget or below the rate assigned to it.
-* Temporally sharable / Merge: a set of models can share one gpu-let when a
-  duty cycle d exists such that, with b_i the smallest profiled batch size
-  >= r_i * d, sum_i L_i(b_i) <= d and d + L_i(b_i) <= SLO_i for every i.
-  Candidate cycles are the times at which some model completes a profiled
-  batch (d = k / r_i); the shortest feasible one is taken.
+* Temporally sharable / Merge: models share a gpu-let round-robin.  A round
+  of length d runs, for every model i, the smallest profiled batch size b_i
+  that covers the requests arriving during d (at least the smallest profiled
+  batch); busy(d) = sum_i L_i(b_i).  The duty cycle is the least d with
+  busy(d) <= d (iterate d <- busy(d) from 0) and the set is sharable iff it
+  exists within the profiled batch sizes and d + L_i(b_i) <= SLO_i for every
+  i.  For a single model this reduces to the budget above.
 * Order: gpu-lets of equal size are visited by GPU index, then by position on
   the GPU; models of equal rate by index.
 """
@@ -181,9 +183,11 @@ def _slowdown(prob, m, other):
     return max(prob.F[m][a[0]] for a in other.alloc)
 
 
-def _cycle_feasible(prob, size, members, f_of, d):
-    """Batches (indices) of each member for duty cycle d on a gpu-let of ``size``, or None."""
-    total, picks = 0.0, []
+def _cycle_load(prob, size, members, f_of, d):
+    """Batches one round of length d collects on a gpu-let of ``size``: per member
+    the smallest profiled batch size covering the requests that arrive during d.
+    Returns (batch indices, slowed-down latencies) or None past the profile."""
+    picks, lats = [], []
     for m, r in members:
         need = r * d / 1000.0
         j = -1
@@ -193,25 +197,43 @@ def _cycle_feasible(prob, size, members, f_of, d):
                 break
         if j < 0:
             return None
-        lat = prob.row(m, size)[j] * (1.0 + f_of(m))
+        picks.append(j)
+        lats.append(prob.row(m, size)[j] * (1.0 + f_of(m)))
+    return picks, lats
+
+
+def _cycle_feasible(prob, size, members, f_of, d):
+    """Batch indices if ``members`` fit a duty cycle of d within their SLOs, else None."""
+    load = _cycle_load(prob, size, members, f_of, d)
+    if load is None:
+        return None
+    picks, lats = load
+    total = 0.0
+    for (m, r), lat in zip(members, lats):
         if d + lat > prob.slo[m]:
             return None
         total += lat
-        picks.append(j)
     return picks if total <= d else None
 
 
 def temporally_sharable(prob, size, members, f_of):
-    """Shortest feasible duty cycle for ``members`` = [(model, rate)] time-sharing
-    one gpu-let of ``size``: (d, batch indices) or None."""
-    cands = []
-    for m, r in members:
-        for b in prob.batches:
-            cands.append(1000.0 * b / r)
-    for d in sorted(cands):
-        picks = _cycle_feasible(prob, size, members, f_of, d)
-        if picks is not None:
-            return d, picks
+    """Shortest duty cycle for ``members`` = [(model, rate)] time-sharing one
+    gpu-let of ``size``: the least d with busy(d) <= d, found by iterating
+    d <- busy(d) from 0, where busy(d) is the time to run every member's batch
+    of one round.  Returns (d, batch indices), or None when the iteration
+    leaves the profiled batch sizes, does not settle, or an SLO breaks."""
+    d = 0.0
+    for _ in range(len(members) * len(prob.batches) + 2):
+        load = _cycle_load(prob, size, members, f_of, d)
+        if load is None:
+            return None
+        busy = 0.0
+        for lat in load[1]:
+            busy += lat
+        if busy <= d:
+            picks = _cycle_feasible(prob, size, members, f_of, d)
+            return (d, picks) if picks is not None else None
+        d = busy
     return None
 
 

@@ -205,17 +205,83 @@ def test_slo_too_tight_for_any_batch_is_not_schedulable():
 
 
 def test_light_models_merge_onto_one_gpulet_by_time_sharing():
-    # two models of 0.1 ms per image: 20% sustains 2000 req/s each; at 100 req/s both share one 20% gpu-let
+    # two models of 0.1 ms per image: L(1, 20%) = 0.5 ms each; at 100 req/s both share one 20% gpu-let
     tabs = [scaling_table(0.1), scaling_table(0.1)]
     prob = S.Problem(SIZES, BATCHES, tabs, [100.0, 100.0], [50.0, 50.0], 1)
     ok, entries = S.elastic_partitioning(prob)
     assert ok and [(e[0], e[1], e[2], e[3]) for e in entries] == [(0, 20, 0, 0), (0, 20, 0, 1)]
-    d = entries[0][6]
-    assert d == entries[1][6] == pytest.approx(10.0)       # shortest cycle: one request each (b=1 at 100 req/s)
+    # shortest round: one batch of 1 each, 0.5 + 0.5 ms; 0.1 requests arrive per round
+    assert entries[0][6] == entries[1][6] == pytest.approx(1.0)
     assert [e[4] for e in entries] == [1, 1]
     prob.merge = False
     ok, entries = S.elastic_partitioning(prob)
     assert ok and [(e[1], e[2], e[3]) for e in entries] == [(20, 0, 0), (80, 1, 1)]
+
+
+def test_duty_cycle_is_the_least_fixed_point_of_the_round_length():
+    # one model, L(b) = 1 + b ms on every size, 1500 req/s: b >= 1.5 * (1 + b) never holds up to 32 -> not sharable
+    tab = [[1.0 + b for b in BATCHES] for _ in SIZES]
+    prob = S.Problem(SIZES, BATCHES, [tab], [1500.0], [1000.0], 1)
+    assert S.temporally_sharable(prob, 100, [(0, 1500.0)], lambda m: 0.0) is None
+    # 800 req/s: b >= 0.8 * (1 + b) first holds at b = 4 (5 ms covers 4 requests); the iteration
+    # walks 0 -> 2 (b=1) -> 3 (b=2) -> 5 (b=4) -> settles
+    d, picks = S.temporally_sharable(prob, 100, [(0, 800.0)], lambda m: 0.0)
+    assert (d, [BATCHES[j] for j in picks]) == (5.0, [4])
+    # the same round breaks an SLO shorter than d + L
+    prob.slo = [9.9]
+    assert S.temporally_sharable(prob, 100, [(0, 800.0)], lambda m: 0.0) is None
+    prob.slo = [10.0]
+    assert S.temporally_sharable(prob, 100, [(0, 800.0)], lambda m: 0.0) is not None
+    # a slowdown stretches every execution
+    prob.slo = [1000.0]
+    d, picks = S.temporally_sharable(prob, 100, [(0, 400.0)], lambda m: 0.5)
+    # L' = 1.5 (1 + b): b >= 0.4 * 1.5 * (1 + b) = 0.6 + 0.6 b -> b >= 1.5 -> b = 2, d = 4.5
+    assert (d, [BATCHES[j] for j in picks]) == (4.5, [2])
+
+
+def replay_round_robin(members, duty_ms, rounds):
+    """Event-by-event replay of time sharing: ``members`` = [(rate, batch, latency)],
+    each with a fixed slot per round of ``duty_ms`` (slots back to back in list
+    order).  A slot runs the requests that arrived since the model's previous
+    slot began.  Returns per member (largest batch seen, worst request latency)."""
+    out, offset = [], 0.0
+    for rate, batch, lat in members:
+        gap = 1000.0 / rate
+        phase = 0.37 * gap                      # arrival phase, arbitrary
+        worst_lat, worst_b = 0.0, 0
+        nxt = 0                                 # index of the next request not yet served
+        for k in range(rounds):
+            start = offset + k * duty_ms
+            n = int(math.floor((start - phase) / gap)) + 1 - nxt if start >= phase else 0
+            if n > 0:
+                first = phase + nxt * gap
+                worst_lat = max(worst_lat, start + lat - first)
+                worst_b = max(worst_b, n)
+                nxt += n
+        out.append((worst_b, worst_lat))
+        offset += lat
+    return out, offset
+
+
+def test_replay_of_merged_gpulets_stays_within_batch_sizes_and_slos():
+    seen = 0
+    for seed in range(300):
+        prob = random_problem(seed, 2 + seed % 4, 1 + seed % 3, False, True, load=0.08)
+        ok, entries = S.elastic_partitioning(prob)
+        groups = {}
+        for e in entries:
+            if e[6] > 0:
+                groups.setdefault((e[0], e[2]), []).append(e)
+        for (gpu, which), es in groups.items():
+            size, d = es[0][1], es[0][6]
+            members = [(e[5], e[4], prob.L[e[3]][SIZES.index(size)][BATCHES.index(e[4])]) for e in es]
+            res, busy = replay_round_robin(members, d, 3000)
+            assert busy <= d * (1 + 1e-12)
+            for (worst_b, worst_lat), e in zip(res, es):
+                assert worst_b <= e[4]
+                assert worst_lat <= prob.slo[e[3]] * (1 + 1e-9)
+            seen += 1
+    assert seen > 30
 
 
 def test_interference_refuses_a_neighbour_that_breaks_the_budget():
@@ -279,7 +345,7 @@ def check_schedule(prob, ok, entries):
             assert served[m] <= prob.rate[m] * (1 + 1e-9)
 
 
-def random_problem(seed, n_models, n_gpu, with_intf, merge=True):
+def random_problem(seed, n_models, n_gpu, with_intf, merge=True, load=1.5):
     from paper_2109_01611_amd import inputs
     tabs = [scenarios.synthetic_table(seed, "m%d" % i) for i in range(n_models)]
     slos = [scenarios.slo_from_table(t) for t in tabs]
@@ -287,7 +353,7 @@ def random_problem(seed, n_models, n_gpu, with_intf, merge=True):
     rates = []
     for i in range(n_models):
         full = 1000.0 * 32 / tabs[i][-1][-1]
-        rates.append(0.0 if u[i] < 0.15 else float(full * 1.5 * u[i]))
+        rates.append(0.0 if u[i] < 0.15 else float(full * load * u[i]))
     F = None
     if with_intf:
         F = [[float(0.3 * u[n_models + a * n_models + b] ** 3) for b in range(n_models)] for a in range(n_models)]
