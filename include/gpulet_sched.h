@@ -1,0 +1,132 @@
+/*
+ * gpulet_sched.h - C ABI of the scheduler side of gpu-lets: host-only, fp64,
+ * no GPU call anywhere in this header.
+ *
+ * Paper: arXiv 2109.01611, Sec. 4.3.  The scheduler consumes, per model, the
+ * profiled latency L(b, p) of batch b on a gpu-let of p percent (Table 2), a
+ * per-model SLO (Table 4) and an interference function, and each period maps
+ * models to gpu-lets (Algorithm 1: ElasticPartitioning, FindBestFit, Split,
+ * Merge, RevertSplit).  Its two helper curves are the affordable request rate
+ * of a gpu-let size and the knee of that curve (MaxEfficientPartition, Fig. 8)
+ * and the smallest size that covers a rate (MinRequiredPartition).
+ *
+ * Where the paper leaves a step open this library takes the following
+ * readings (the same ones its test oracle takes, so that both can be compared
+ * decision by decision):
+ *   - Execution budget (Sec. 2.2: batch building time plus execution time
+ *     must stay within the SLO).  A gpu-let that runs batches of b back to
+ *     back at latency L sustains b/L requests per unit time and its worst
+ *     request waits one building period plus one execution, 2L.  A batch size
+ *     is admissible iff L(b, p) * (1 + f) <= SLO / 2, f being the fractional
+ *     slowdown from the neighbour gpu-let.
+ *   - Affordable rate of a size: the best sustained rate over admissible
+ *     profiled batch sizes.
+ *   - Knee: both axes scaled to [0, 1]; y' and y'' at each interior profiled
+ *     size from the parabola through the point and its two neighbours;
+ *     curvature -y'' / (1 + y'^2)^1.5; the size of largest positive curvature
+ *     (the smaller size on ties), the largest size if there is none.
+ *   - Temporal sharing (Merge): models share a gpu-let round-robin.  A round
+ *     of length d runs, for every model i, the smallest profiled batch b_i
+ *     covering the requests that arrive during d; busy(d) = sum_i L_i(b_i).
+ *     The duty cycle is the least d with busy(d) <= d (iterate d <- busy(d)
+ *     from 0); the models are sharable iff it exists within the profiled
+ *     batch sizes and d + L_i(b_i) <= SLO_i for every i.
+ *   - A placement is refused when it would push the models on the partner
+ *     gpu-let of the same GPU over their budget or below their assigned rate.
+ *   - Visiting order: gpu-lets by (size, gpu, position); models by
+ *     (rate descending, index).
+ *
+ * All arrays are HOST memory owned by the caller and only read during the
+ * call (outputs only written).  Rates are requests per second, times are
+ * milliseconds, sizes are percent.  Calls are pure and thread safe.
+ * Errors: GPULET_EINVAL for NULL pointers, non-positive counts, sizes or
+ * batches that are not strictly ascending and positive, sizes that do not end
+ * at 100, non-finite or non-positive latencies or SLOs, negative rates or
+ * slowdowns; GPULET_ENOMEM when an output array is too small.
+ */
+#ifndef GPULET_SCHED_H
+#define GPULET_SCHED_H
+
+#include "gpulet.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Affordable rate of one gpu-let size (Sec. 4.3, the curve of Fig. 8).
+ * latency_ms[j] = L(batch[j], p).  `slowdown` is the fraction f above (0 when
+ * the gpu-let has no neighbour).  Writes the rate (0 if no batch size is
+ * admissible) and the batch size that reaches it (0 if none).
+ */
+gpulet_status gpulet_affordable_rate(const int *batch, const double *latency_ms, int n_batch, double slo_ms,
+                                     double slowdown, double *rate, int *best_batch);
+
+/*
+ * The whole curve: latency_ms is [n_size][n_batch] row-major, rate gets
+ * n_size values, one per profiled size, without slowdown.
+ */
+gpulet_status gpulet_rate_curve(const int *batch, int n_batch, int n_size, const double *latency_ms,
+                                double slo_ms, double *rate);
+
+/*
+ * MaxEfficientPartition (Sec. 4.3): p_eff = profiled size at the knee of the
+ * affordable-rate curve.  `curvature` may be NULL; otherwise it receives
+ * n_size values (0 at both ends).
+ */
+gpulet_status gpulet_max_efficient_partition(const int *size, const double *rate, int n_size, int *p_eff,
+                                             double *curvature);
+
+/*
+ * MinRequiredPartition (Sec. 4.3): p_req = smallest profiled size whose
+ * affordable rate is >= want, the largest size if none is.
+ */
+gpulet_status gpulet_min_required_partition(const int *size, const double *rate, int n_size, double want,
+                                            int *p_req);
+
+/* One model of a scheduling problem. */
+typedef struct gpulet_sched_model {
+    double rate;              /* incoming request rate, req/s (0 = idle this period) */
+    double slo_ms;            /* Table 4 */
+    const double *latency_ms; /* L(b, p): [n_size][n_batch] row-major */
+} gpulet_sched_model;
+
+/*
+ * One scheduling period's input.  For every profiled size s < 100 the
+ * remainder 100 - s must be profiled too (Split hands it back as a gpu-let).
+ */
+typedef struct gpulet_sched_problem {
+    int n_model, n_size, n_batch, n_gpu;
+    const int *size;                 /* ascending, last = 100 */
+    const int *batch;                /* ascending */
+    const gpulet_sched_model *model; /* n_model */
+    const double *slowdown;          /* [n_model][n_model] row-major: [victim][aggressor] fraction, or NULL = 0 */
+    int merge;                       /* non-zero: try temporal sharing (Merge) after every best-fit */
+} gpulet_sched_problem;
+
+/* One (gpu-let, model) assignment of the result. */
+typedef struct gpulet_sched_entry {
+    int gpu;        /* 0 .. n_gpu-1 */
+    int size;       /* percent */
+    int which;      /* 0 = first part of the split (or the whole GPU), 1 = the remainder */
+    int model;
+    int batch;      /* batch size the model runs with on this gpu-let */
+    double rate;    /* share of the model's rate served here, req/s */
+    double duty_ms; /* 0 when the model has the gpu-let to itself, else the duty cycle it shares */
+} gpulet_sched_entry;
+
+/*
+ * ElasticPartitioning (Algorithm 1), one period.  Entries come out grouped by
+ * gpu-let in order of first allocation, models within a gpu-let in order of
+ * assignment.  *schedulable is 1 when every model's rate was placed; when it
+ * is 0 the entries hold what had been placed when the gpu-lets ran out.
+ * GPULET_ENOMEM if more than max_entries would be written (*n_entries then
+ * holds the number needed).
+ */
+gpulet_status gpulet_elastic_partitioning(const gpulet_sched_problem *problem, gpulet_sched_entry *entries,
+                                          int max_entries, int *n_entries, int *schedulable);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPULET_SCHED_H */

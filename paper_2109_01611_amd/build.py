@@ -12,8 +12,11 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpulet.so")
 
-SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "conv.hip", "pool.hip", "fc.hip",
-           "probe.hip"]
+SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "conv.hip", "pool.hip",
+           "fc.hip", "probe.hip"]
+
+# The scheduler's fp64 decisions must not depend on fused multiply-adds.
+EXTRA = {"sched.cpp": ["-ffp-contract=off"]}
 
 # Packed-fp32 VALU forms are switched off for device code on purpose.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -23,7 +26,7 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-paramet
 
 def _compile(src):
     obj = os.path.join(OBJ, src + ".o")
-    cmd = ["hipcc"] + COMMON + DEVICE_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc"] + COMMON + DEVICE_FLAGS + EXTRA.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # hipcc's host pass does not know the device-only feature flag; drop that note.
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l).strip()

@@ -42,6 +42,24 @@ class Layer(ctypes.Structure):
         "out_ch_total", "out_ch_offset", "out_fp32", "reserved")] + [("w", c_void_p), ("b", c_void_p)]
 
 
+class SchedModel(ctypes.Structure):
+    """Mirror of ``gpulet_sched_model``."""
+    _fields_ = [("rate", c_double), ("slo_ms", c_double), ("latency_ms", POINTER(c_double))]
+
+
+class SchedProblem(ctypes.Structure):
+    """Mirror of ``gpulet_sched_problem``."""
+    _fields_ = [("n_model", c_int), ("n_size", c_int), ("n_batch", c_int), ("n_gpu", c_int),
+                ("size", POINTER(c_int)), ("batch", POINTER(c_int)), ("model", POINTER(SchedModel)),
+                ("slowdown", POINTER(c_double)), ("merge", c_int)]
+
+
+class SchedEntry(ctypes.Structure):
+    """Mirror of ``gpulet_sched_entry``."""
+    _fields_ = [("gpu", c_int), ("size", c_int), ("which", c_int), ("model", c_int), ("batch", c_int),
+                ("rate", c_double), ("duty_ms", c_double)]
+
+
 class ModelDesc(ctypes.Structure):
     """Mirror of ``gpulet_model_desc``."""
     _fields_ = [(n, c_int32) for n in (
@@ -55,6 +73,7 @@ def _load():
                           "(needs hipcc; there is no fallback path)")
     L = ctypes.CDLL(LIB_PATH)
     I, P, FP = c_int, c_void_p, POINTER(c_float)
+    IP, DP = POINTER(c_int), POINTER(c_double)
     sig = {
         "gpulet_status_string": ([c_int32], ctypes.c_char_p),
         "gpulet_last_hip_error": ([], c_int),
@@ -88,6 +107,11 @@ def _load():
                                   I, c_double, FP, I, POINTER(I), FP, I, POINTER(I)], c_int32),
         "gpulet_latency_stats": ([FP, I, POINTER(c_double), POINTER(c_double), POINTER(c_double)], c_int32),
         "gpulet_time_conv2d": ([P, P, P, P] + [I] * 10 + [P, I, I, P, I, I, FP], c_int32),
+        "gpulet_affordable_rate": ([IP, DP, I, c_double, c_double, DP, IP], c_int32),
+        "gpulet_rate_curve": ([IP, I, I, DP, c_double, DP], c_int32),
+        "gpulet_max_efficient_partition": ([IP, DP, I, IP, DP], c_int32),
+        "gpulet_min_required_partition": ([IP, DP, I, c_double, IP], c_int32),
+        "gpulet_elastic_partitioning": ([POINTER(SchedProblem), POINTER(SchedEntry), I, IP, IP], c_int32),
     }
     for name, (argtypes, restype) in sig.items():
         fn = getattr(L, name)
