@@ -30,7 +30,9 @@
  *     covering the requests that arrive during d; busy(d) = sum_i L_i(b_i).
  *     The duty cycle is the least d with busy(d) <= d (iterate d <- busy(d)
  *     from 0); the models are sharable iff it exists within the profiled
- *     batch sizes and d + L_i(b_i) <= SLO_i for every i.
+ *     batch sizes and d + L_i(b_i) <= SLO_i for every i.  Merge is also tried
+ *     when no free gpu-let fits; the model then offers the rate a gpu-let of
+ *     the ideal size would have taken.
  *   - A placement is refused when it would push the models on the partner
  *     gpu-let of the same GPU over their budget or below their assigned rate.
  *   - Visiting order: gpu-lets by (size, gpu, position); models by

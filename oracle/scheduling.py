@@ -41,7 +41,9 @@ closed forms.  The readings taken here:
   batch); busy(d) = sum_i L_i(b_i).  The duty cycle is the least d with
   busy(d) <= d (iterate d <- busy(d) from 0) and the set is sharable iff it
   exists within the profiled batch sizes and d + L_i(b_i) <= SLO_i for every
-  i.  For a single model this reduces to the budget above.
+  i.  For a single model this reduces to the budget above.  Merge is also
+  tried when no free gpu-let fits (the listing does not say what happens
+  then); the model then offers the rate a gpu-let of p_ideal would have taken.
 * Order: gpu-lets of equal size are visited by GPU index, then by position on
   the GPU; models of equal rate by index.
 """
@@ -271,10 +273,17 @@ def find_best_fit(prob, gpus, order_alloc, m, p_ideal, want):
             break
         if split:
             gpus[g.gpu] = [Gpulet(g.gpu, 100, 0)]
-    if chosen is None:
+    if chosen is not None:
+        lat = prob.row(m, chosen.size)[b_idx] * (1.0 + f)
+        take = min(want, sustained_rate(prob.batches[b_idx], lat))
+    elif prob.merge:
+        # no free gpu-let fits: time sharing is still tried, with the rate a
+        # gpu-let of the ideal size would have taken
+        take = min(want, affordable_rate(prob.row(m, p_ideal), prob.batches, prob.slo[m])[0])
+        if take <= 0.0:
+            return None
+    else:
         return None
-    lat = prob.row(m, chosen.size)[b_idx] * (1.0 + f)
-    take = min(want, sustained_rate(prob.batches[b_idx], lat))
 
     if prob.merge:
         for a in order_alloc:                         # Merge through temporal sharing
@@ -295,10 +304,13 @@ def find_best_fit(prob, gpus, order_alloc, m, p_ideal, want):
             for e, j in zip(a.alloc, picks):
                 e[1] = prob.batches[j]
             a.duty_ms = d
-            parts = gpus[chosen.gpu]                  # RevertSplit
-            if len(parts) == 2 and not parts[0].alloc and not parts[1].alloc:
-                gpus[chosen.gpu] = [Gpulet(chosen.gpu, 100, 0)]
+            if chosen is not None:
+                parts = gpus[chosen.gpu]              # RevertSplit
+                if len(parts) == 2 and not parts[0].alloc and not parts[1].alloc:
+                    gpus[chosen.gpu] = [Gpulet(chosen.gpu, 100, 0)]
             return a, a.alloc[-1][1], take
+    if chosen is None:
+        return None
 
     chosen.alloc.append([m, prob.batches[b_idx], take])
     order_alloc.append(chosen)

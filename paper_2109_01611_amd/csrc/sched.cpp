@@ -288,7 +288,16 @@ class Period {
                 }
             }
         }
-        if (chosen.gpu < 0) return false;
+        if (chosen.gpu < 0) {
+            // No free gpu-let fits: time sharing is still tried, with the rate a gpu-let of the
+            // ideal size would have taken.
+            if (!P.merge) return false;
+            int arg;
+            const double ideal = best_rate(P.batch, row(m, size_index(p_ideal)), P.n_batch, P.model[m].slo_ms,
+                                           0.0, &arg);
+            *took = std::min(want, ideal);
+            return *took > 0.0 && try_merge(m, *took);
+        }
         Slot &s = gpus[chosen.gpu].slot[chosen.which];
         const double lat = slowed(row(m, size_index(s.size))[b_idx], f);
         const double take = std::min(want, per_second(P.batch[b_idx], lat));

@@ -15,8 +15,9 @@ import json
 import os
 import sys
 import tempfile
+import time
 
-from . import gpulet, lowering, workloads
+from . import gpulet, lowering, scenarios, sched, workloads
 
 # Dense bf16 MFMA peak of one MI355X compute unit: 2.5 PFLOP/s over 256 CUs.
 PEAK_TFLOPS_PER_CU = 2500.0 / 256.0
@@ -91,20 +92,96 @@ def measure(bound, part, warmup=20, iters=200, sync_each=True):
 
 
 def sweep(model, batches, pcts, seed=0, warmup=20, iters=200, device="cuda:0", log=None):
-    """L(b, p) rows of one model over batch sizes and gpu-let sizes."""
+    """L(b, p) rows of one model over batch sizes and gpu-let sizes (one
+    gpu-let per size, every batch size measured on it)."""
     dm = lowering.DeviceModel(model, workloads.parameters(model, seed), device)
-    rows = []
-    for b in batches:
-        bound = Bound(dm, b, seed)
-        for pct in pcts:
-            with gpulet.Partition(0, pct, 0) as part:
+    bounds = [Bound(dm, b, seed) for b in batches]
+    rows = {}
+    for pct in pcts:
+        with gpulet.Partition(0, pct, 0) as part:
+            for bound in bounds:
                 row = measure(bound, part, warmup, iters)
-            rows.append(row)
-            if log:
-                log("%(model)s b=%(batch)d p=%(pct)d%% (%(n_cu)d CUs): mean %(mean_ms).3f ms  p99 %(p99_ms).3f ms  "
-                    "%(images_per_s).0f img/s  %(tflops).1f TFLOP/s  %(mfma_frac_of_masked_peak).3f of masked peak"
-                    % row)
-    return rows
+                rows[(bound.batch, pct)] = row
+                if log:
+                    log("%(model)s b=%(batch)d p=%(pct)d%% (%(n_cu)d CUs): mean %(mean_ms).3f ms  p99 %(p99_ms).3f ms"
+                        "  %(images_per_s).0f img/s  %(tflops).1f TFLOP/s  %(mfma_frac_of_masked_peak).3f of masked"
+                        " peak" % row)
+    return [rows[(b, pct)] for b in batches for pct in pcts]
+
+
+def latency_table(rows, model, sizes, batches, key="mean_ms"):
+    """[size][batch] table of one model out of sweep rows."""
+    cell = {(r["pct"], r["batch"]): r[key] for r in rows if r["model"] == model}
+    return [[cell[(p, b)] for b in batches] for p in sizes]
+
+
+def knee_report(table, sizes, batches):
+    """SLO by the rule of Table 4, affordable-rate curve, curvature and
+    p_eff (Sec. 4.3, Fig. 8) of one model's table; all from the library."""
+    slo = scenarios.slo_from_table(table, list(sizes), list(batches))
+    curve = sched.rate_curve(batches, table, slo)
+    best = [sched.affordable_rate(batches, row, slo)[1] for row in table]
+    p_eff, curv = sched.max_efficient_partition(sizes, curve, with_curvature=True)
+    return {"slo_ms": slo, "sizes": list(sizes), "rate": curve, "batch": best, "curvature": curv, "p_eff": p_eff}
+
+
+def schedulability(tables, slos, n_gpu, rate_sets, sizes, batches, merge=True):
+    """Number of rate sets Algorithm 1 can place on ``n_gpu`` GPUs, and the
+    mean number of GPUs the schedulable ones occupy."""
+    n_ok, gpus = 0, 0
+    for rates in rate_sets:
+        ok, entries = sched.elastic_partitioning(sizes, batches, tables, rates, slos, n_gpu, merge=merge)
+        if ok:
+            n_ok += 1
+            gpus += len(set(e[0] for e in entries))
+    return {"scenarios": len(rate_sets), "schedulable": n_ok, "mean_gpus_used": gpus / n_ok if n_ok else None}
+
+
+def scheduling_study(rows, names, sizes, batches, n_gpus=(1, 2, 4)):
+    """Feeds the measured tables to the scheduler: knees per model, then the
+    scenario grid of Sec. 3.1 at the paper's absolute rates and at rates scaled
+    to each model's whole-GPU capacity, with and without spatial partitioning
+    (the latter: the 100% column only, temporal sharing still allowed)."""
+    tables = [latency_table(rows, n, sizes, batches) for n in names]
+    knees = {n: knee_report(t, sizes, batches) for n, t in zip(names, tables)}
+    slos = [knees[n]["slo_ms"] for n in names]
+    whole = [[t[-1]] for t in tables]
+    out = {"models": names, "knees": knees, "grids": {}}
+    grids = {"paper_rates_0_200_400_600": scenarios.rate_grid(len(names))}
+    for frac in (0.25, 0.5, 1.0):
+        levels = scenarios.rate_grid(len(names), levels=(0.0, 1.0, 2.0, 3.0))
+        cap = [knees[n]["rate"][-1] for n in names]
+        grids["capacity_x_%g_levels_0_to_3_thirds" % frac] = [
+            [l / 3.0 * frac * c for l, c in zip(lv, cap)] for lv in levels]
+    for gname, rate_sets in grids.items():
+        for n_gpu in n_gpus:
+            out["grids"]["%s/%d_gpu" % (gname, n_gpu)] = {
+                "gpulets": schedulability(tables, slos, n_gpu, rate_sets, list(sizes), list(batches)),
+                "gpulets_no_merge": schedulability(tables, slos, n_gpu, rate_sets, list(sizes), list(batches),
+                                                   False),
+                "whole_gpus_only": schedulability(whole, slos, n_gpu, rate_sets, [100], list(batches)),
+            }
+    return out
+
+
+def partition_cost(n=20, pct=50):
+    """Host wall-clock of creating and destroying a gpu-let (CU-masked stream
+    plus its scratch), the counterpart of the paper's 10-15 s partition
+    reorganisation (Sec. 5).  Returns (create_ms, destroy_ms) medians."""
+    import torch
+    torch.cuda.synchronize()
+    create, destroy = [], []
+    for _ in range(n):
+        t0 = time.perf_counter()
+        part = gpulet.Partition(0, pct, 0)
+        t1 = time.perf_counter()
+        part.destroy()
+        t2 = time.perf_counter()
+        create.append((t1 - t0) * 1e3)
+        destroy.append((t2 - t1) * 1e3)
+    create.sort()
+    destroy.sort()
+    return create[n // 2], destroy[n // 2]
 
 
 def corun(model_a, batch_a, model_b, batch_b, pct_a=50, seed=0, warmup=5, window_ms=2000.0, device="cuda:0"):
@@ -166,16 +243,41 @@ CONFIGS = {
     "googlenet": (workloads.googlenet, [32], [50, 100]),
 }
 
+# The scheduler's input: every model over the whole profiled grid (Fig. 3).
+GRID_MODELS = ("lenet5", "googlenet", "resnet50", "vgg16")
+
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description="L(b, p) latency table and co-run interference on one MI355X")
-    ap.add_argument("--config", default="conv", choices=sorted(CONFIGS) + ["corun", "all"])
+    ap.add_argument("--config", default="conv", choices=sorted(CONFIGS) + ["corun", "all", "grid"])
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--window-ms", type=float, default=2000.0)
     ap.add_argument("--out", default=None, help="CSV (or JSON for corun) path; default prints only")
     args = ap.parse_args(argv)
     log = lambda s: print(s, flush=True)
+    if args.config == "grid":
+        sizes, batches = list(scenarios.SIZES), list(scenarios.BATCHES)
+        rows = []
+        for name in GRID_MODELS:
+            rows += sweep(CONFIGS[name][0](), batches, sizes, warmup=args.warmup, iters=args.iters, log=log)
+            if args.out:
+                write_atomic(args.out, table_csv(rows))
+        names = [CONFIGS[n][0]().name for n in GRID_MODELS]
+        study = scheduling_study(rows, names, sizes, batches)
+        study["partition_create_destroy_ms"] = partition_cost()
+        for n in names:
+            k = study["knees"][n]
+            log("%s: SLO %.3f ms, affordable rate per size %s req/s, batch %s, p_eff %d%%"
+                % (n, k["slo_ms"], ["%.0f" % r for r in k["rate"]], k["batch"], k["p_eff"]))
+        for g, res in study["grids"].items():
+            log("%s: %s" % (g, "  ".join("%s %d/%d (%.2f GPUs)" % (k, v["schedulable"], v["scenarios"],
+                                                                    v["mean_gpus_used"] or 0.0)
+                                         for k, v in res.items())))
+        log("gpu-let create %.3f ms, destroy %.3f ms (median)" % tuple(study["partition_create_destroy_ms"]))
+        if args.out:
+            write_atomic(os.path.splitext(args.out)[0] + "_sched.json", json.dumps(study, indent=1) + "\n")
+        return 0
     names = sorted(CONFIGS) if args.config == "all" else [args.config]
     rows = []
     for name in names:

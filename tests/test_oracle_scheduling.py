@@ -218,6 +218,24 @@ def test_light_models_merge_onto_one_gpulet_by_time_sharing():
     assert ok and [(e[1], e[2], e[3]) for e in entries] == [(20, 0, 0), (80, 1, 1)]
 
 
+def test_merge_is_tried_even_when_no_free_gpulet_is_left():
+    # whole GPUs only (one profiled size): the second model has no gpu-let to claim but time-shares the first
+    tabs = [[[0.1 * b for b in BATCHES]], [[0.2 * b for b in BATCHES]]]
+    prob = S.Problem([100], BATCHES, tabs, [100.0, 50.0], [50.0, 50.0], 1)
+    ok, entries = S.elastic_partitioning(prob)
+    assert ok and [(e[0], e[1], e[2], e[3], e[4]) for e in entries] == [(0, 100, 0, 0, 1), (0, 100, 0, 1, 1)]
+    assert entries[0][6] == pytest.approx(0.1 + 0.2)
+    prob.merge = False
+    ok, entries = S.elastic_partitioning(prob)
+    assert not ok and [e[3] for e in entries] == [0]
+    # three models on one split GPU: the third has to share
+    tabs = [scaling_table(0.1)] * 3
+    prob = S.Problem(SIZES, BATCHES, tabs, [1500.0, 1200.0, 100.0], [1000.0] * 3, 1)
+    ok, entries = S.elastic_partitioning(prob)
+    assert ok and sorted(set((e[1], e[2]) for e in entries)) == [(20, 0), (80, 1)]
+    check_schedule(prob, ok, entries)
+
+
 def test_duty_cycle_is_the_least_fixed_point_of_the_round_length():
     # one model, L(b) = 1 + b ms on every size, 1500 req/s: b >= 1.5 * (1 + b) never holds up to 32 -> not sharable
     tab = [[1.0 + b for b in BATCHES] for _ in SIZES]

@@ -86,6 +86,18 @@ def test_elastic_partitioning_matches_the_oracle_on_random_scenarios(with_intf, 
     assert (merged > 20) if merge else (merged == 0)
 
 
+def test_whole_gpus_only_matches_the_oracle():
+    n_ok = 0
+    for seed in range(150):
+        tabs, rates, slos, n_gpu, F, merge = random_problem(seed, 2 + seed % 4, 1 + seed % 3, False, True, load=0.2)
+        tabs = [[t[-1]] for t in tabs]
+        want = S.elastic_partitioning(S.Problem([100], BATCHES, tabs, rates, slos, n_gpu, merge=True))
+        got = sched.elastic_partitioning([100], BATCHES, tabs, rates, slos, n_gpu, merge=True)
+        assert_same(want, got)
+        n_ok += want[0]
+    assert 10 < n_ok < 150
+
+
 def test_hand_worked_cases_match():
     scal = lambda per: [[per * b * 100.0 / p for b in BATCHES] for p in SIZES]
     knee = lambda per, k: [[per * b * 100.0 / min(p, k) for b in BATCHES] for p in SIZES]
