@@ -31,6 +31,7 @@
 // scalar-gather variant of the same tiling with four wavefronts.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 
 #include "gpulet_internal.h"
@@ -64,6 +65,8 @@ struct ConvParams {
     int sps;            // slices per split
     float *part;        // split-K scratch: [n_tiles * split_k][BM * BN] fp32 partial tiles
     unsigned *cnt;      // split-K scratch: arrival counter per tile (zero between launches)
+    // Patch kernel only: output pixels are grouped in column blocks of `tw` pixels.
+    int tw, n_cb;       // block width, blocks per output row
 };
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
@@ -147,6 +150,63 @@ __device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsig
                  :
                  : "s"(lds_base), "v"(voff), "s"(rsrc)
                  : "memory");
+}
+
+// Last step of the epilogue for a BM x BN fp32 tile parked in LDS (rows padded
+// to BN + 8 floats): every thread of the workgroup takes 8 consecutive channels
+// of one tile row, adds bias and residual, applies ReLU, rounds once to bf16
+// and stores 16 bytes.  `pixel_of(row)` gives the output pixel (n*P + p)*Q + q
+// of a tile row, or -1 for rows past the end.
+template <int BM, int BN, int NTHR, typename PixelOf>
+__device__ __forceinline__ void finish_tile(const ConvParams &p, const float *stg, int n0, PixelOf pixel_of) {
+    constexpr int LDT = BN + 8;
+    constexpr int VPR = BN / 8;  // 8-channel groups per tile row
+    const bool vec_ok = p.vec_store;
+    for (int it = threadIdx.x; it < BM * VPR; it += NTHR) {
+        const int row = it / VPR, cv = it - row * VPR;
+        const int m = pixel_of(row), k = n0 + cv * 8;
+        if (m < 0 || k >= p.K) continue;
+        const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
+        const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
+        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        if (vec_ok && k + 8 <= p.K) {
+            if (p.b) {
+                const float4 b0 = *reinterpret_cast<const float4 *>(p.b + k);
+                const float4 b1 = *reinterpret_cast<const float4 *>(p.b + k + 4);
+                v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+            }
+            if (p.res) {
+                const uint4 rr = *reinterpret_cast<const uint4 *>(p.res + (m * p.K + k));
+                const unsigned ru[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] += __uint_as_float(ru[e] << 16);
+                    v[2 * e + 1] += __uint_as_float(ru[e] & 0xFFFF0000u);
+                }
+            }
+            unsigned pk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float a = v[2 * e], b = v[2 * e + 1];
+                if (p.relu) {
+                    a = a > 0.f ? a : 0.f;
+                    b = b > 0.f ? b : 0.f;
+                }
+                const __bf16 ha = static_cast<__bf16>(a), hb = static_cast<__bf16>(b);
+                pk[e] = static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&ha)) |
+                        (static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&hb)) << 16);
+            }
+            *reinterpret_cast<uint4 *>(p.y + (m * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        } else {
+            for (int e = 0; e < 8 && k + e < p.K; ++e) {
+                float a = v[e] + (p.b ? p.b[k + e] : 0.f);
+                if (p.res) a += static_cast<float>(p.res[m * p.K + k + e]);
+                if (p.relu) a = a > 0.f ? a : 0.f;
+                p.y[m * p.ldy + p.y_off + k + e] = static_cast<__bf16>(a);
+            }
+        }
+    }
 }
 
 // Wavefronts are specialised.  The first CWM x CWN wavefronts ("consumers")
@@ -469,52 +529,226 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         }
         // each thread re-reads only what it wrote itself, in the same iteration order
     }
-    const bool vec_ok = p.vec_store;
-    for (int it = threadIdx.x; it < BM * VPR; it += NTHR) {
-        const int row = it / VPR, cv = it - row * VPR;
-        const int m = m0 + row, k = n0 + cv * 8;
-        if (m >= p.M || k >= p.K) continue;
-        const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
-        const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
-        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        if (vec_ok && k + 8 <= p.K) {
-            if (p.b) {
-                const float4 b0 = *reinterpret_cast<const float4 *>(p.b + k);
-                const float4 b1 = *reinterpret_cast<const float4 *>(p.b + k + 4);
-                v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-                v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-            }
-            if (p.res) {
-                const uint4 rr = *reinterpret_cast<const uint4 *>(p.res + (m * p.K + k));
-                const unsigned ru[4] = {rr.x, rr.y, rr.z, rr.w};
+    finish_tile<BM, BN, NTHR>(p, stg, n0, [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
+}
+
+// ---------------------------------------------------------------------------
+// 3x3 filters with stride 1 and C % 64 == 0: input patches stay in LDS.
+//
+// The implicit-GEMM A operand repeats every input pixel up to nine times, once
+// per tap, and the kernel above stages all nine copies.  Here a workgroup
+// stages, per block of 64 channels, the patch of input pixels its 128 output
+// pixels touch (halo included) exactly once, and the nine taps read it at
+// shifted positions.  Only the weights still move once per tap, three taps (one
+// filter row) per ring step, so a step carries three times the arithmetic of a
+// depth slice per workgroup barrier.
+//
+// Output pixels are ordered in column blocks of `tw` pixels: block cb holds
+// columns cb*tw .. cb*tw+tw-1 of every output row, linearised as
+// l = (n*P + p)*tw + tx; a tile is 128 consecutive l of one block.  With
+// tw = Q this is the plain pixel order (tiles may cross rows and images); with
+// tw = 16 a tile is an 8 x 16 pixel rectangle.  The patch is addressed by
+// "virtual rows" v = n*(H+2) + h + pad, so the rows between two images are the
+// zero padding, and holds rows v0 .. v0+prow-1, columns q0-pad .. q0+tw+pad-1
+// of the block: position pos = (v - v0)*(tw+2) + u.  An output pixel with first
+// virtual row v and block column tx reads tap (r, s) at
+// pos = (v - v0 + r)*(tw+2) + tx + s = base + r*(tw+2) + s, base fixed per
+// lane.  Each position is a 128-byte row of 64 channels, XOR-swizzled like the
+// weight tiles (by the position index).  The host guarantees that no tile
+// needs more than PMAX positions.
+//
+// Four consumer wavefronts (one per SIMD) own 32 tile rows x 64 channels each;
+// four producers issue the transfers.  Patch buffers alternate per channel
+// block, weight stages form a ring of three.  A producer's transfers complete
+// in issue order, which the waits below rely on: within a step the pieces of
+// the next patch are issued before the weights of step t+2, so waiting for the
+// weights of step t also covers every patch piece issued earlier.
+// ---------------------------------------------------------------------------
+constexpr int PATCH_BM = 128;
+constexpr int PATCH_PMAX = 256;  // patch positions per buffer (32 KB)
+
+template <int BN, int NPROD>
+__global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const ConvParams p) {
+    constexpr int BM = PATCH_BM, NCONS = 4, NS = 3, PMAX = PATCH_PMAX;
+    constexpr int NT = BN / 32;                    // MFMA tiles per consumer (one row of them)
+    constexpr int PATCH = PMAX * BK;               // elements per patch buffer
+    constexpr int BSTAGE = 3 * BN * BK;            // elements per weight stage: the three taps of a filter row
+    constexpr int POPS = PMAX / 8 / NPROD;         // patch transfers per producer lane and channel block
+    constexpr int BOPS = 3 * BN / 8 / NPROD;       // weight transfers per producer lane and step
+    constexpr int RG = BN / 8;                     // groups of 8 rows per weight tile
+    static_assert(POPS % 2 == 0 && (3 * BN / 8) % NPROD == 0 && BN % 32 == 0, "transfer split");
+    static_assert(POPS / 2 + 2 * BOPS <= 63, "6-bit transfer counter");
+    constexpr int LDT = BN + 8;
+    constexpr int MAIN = 2 * PATCH + NS * BSTAGE;
+    constexpr int LDS_ELEMS = MAIN > BM * LDT * 2 ? MAIN : BM * LDT * 2;
+    __shared__ __attribute__((aligned(1024))) __bf16 lds[LDS_ELEMS];
+    __bf16 *const patch = lds;
+    __bf16 *const wring = lds + 2 * PATCH;
+
+    const int tile = tile_of_block(p);
+    if (tile >= p.n_tiles) return;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int tl = tm / p.n_cb, cb = tm - tl * p.n_cb;
+    const int l0 = tl * BM, n0 = tn * BN, q0 = cb * p.tw;
+    const int NP = p.N * p.P;
+    const int Hp = p.H + 2 * p.pad;       // virtual rows per image
+    const int pwt = p.tw + 2;             // patch width: block columns plus the two halo columns
+    const int nblk = p.C / BK;
+
+    // Virtual row of output row rho at tap row 0.
+    auto vrow = [&](int rho) {
+        const int n = rho / p.P;
+        return n * Hp + (rho - n * p.P);
+    };
+    const int rho_first = l0 / p.tw;
+    const int rho_last = min(NP - 1, (l0 + BM - 1) / p.tw);
+    const int v0 = vrow(rho_first);
+    const int npos = (vrow(rho_last) + 2 - v0 + 1) * pwt;  // positions this tile needs (<= PMAX)
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    f32x16 acc[NT];  // consumers only
+
+    if (wave >= NCONS) {
+        // ------------------------------------------------------------ producer
+        const int pw = wave - NCONS;
+        const i32x4 rx = make_rsrc(p.x, p.x_bytes);
+        const i32x4 rw = make_rsrc(p.w, p.w_bytes);
+
+        // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8;
+        // this lane fills physical chunk lane&7 of one of them.
+        unsigned a_off[POPS];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[2 * e] += __uint_as_float(ru[e] << 16);
-                    v[2 * e + 1] += __uint_as_float(ru[e] & 0xFFFF0000u);
-                }
+        for (int j = 0; j < POPS; ++j) {
+            const int pos = (j * NPROD + pw) * 8 + (lane >> 3);
+            const int cc = (lane & 7) ^ ((pos >> 1) & 7);
+            a_off[j] = OOB;
+            if (pos < npos) {
+                const int vr = pos / pwt, u = pos - vr * pwt;
+                const int v = v0 + vr;
+                const int n = v / Hp;
+                const int h = v - n * Hp - p.pad, w = q0 + u - p.pad;
+                if (n < p.N && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+                    a_off[j] = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C + cc * CHUNK) * 2);
             }
-            unsigned pk[4];
+        }
+        // Weight transfer i fills rows rg*8 .. +8 of tap s of the stage, q = i*NPROD + pw = s*RG + rg.
+        unsigned b_off[BOPS];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float a = v[2 * e], b = v[2 * e + 1];
-                if (p.relu) {
-                    a = a > 0.f ? a : 0.f;
-                    b = b > 0.f ? b : 0.f;
-                }
-                const __bf16 ha = static_cast<__bf16>(a), hb = static_cast<__bf16>(b);
-                pk[e] = static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&ha)) |
-                        (static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&hb)) << 16);
+        for (int i = 0; i < BOPS; ++i) {
+            const int q = i * NPROD + pw;
+            const int s = q / RG, row = (q - s * RG) * 8 + (lane >> 3);
+            const int cc = (lane & 7) ^ ((row >> 1) & 7);
+            const int k = n0 + row;
+            b_off[i] = k < p.K ? static_cast<unsigned>(((k * 9 + s) * p.C + cc * CHUNK) * 2) : OOB;
+        }
+
+        auto issue_patch = [&](int blk, int half) {
+            const unsigned base = lds_addr(patch + (blk & 1) * PATCH) + pw * 1024;
+            const unsigned add = static_cast<unsigned>(blk * BK * 2);
+#pragma unroll
+            for (int j = half * (POPS / 2); j < (half + 1) * (POPS / 2); ++j) {
+                const unsigned off = (blk < nblk && a_off[j] != OOB) ? a_off[j] + add : OOB;
+                dma16(rx, base + j * NPROD * 1024, off);
             }
-            *reinterpret_cast<uint4 *>(p.y + (m * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        } else {
-            for (int e = 0; e < 8 && k + e < p.K; ++e) {
-                float a = v[e] + (p.b ? p.b[k + e] : 0.f);
-                if (p.res) a += static_cast<float>(p.res[m * p.K + k + e]);
-                if (p.relu) a = a > 0.f ? a : 0.f;
-                p.y[m * p.ldy + p.y_off + k + e] = static_cast<__bf16>(a);
+        };
+        // Weights of step t = 3*blk + r into ring stage `stage`.
+        auto issue_weights = [&](int blk, int r, int stage) {
+            const unsigned base = lds_addr(wring + stage * BSTAGE) + pw * 1024;
+            const unsigned add = static_cast<unsigned>((r * 3 * p.C + blk * BK) * 2);
+#pragma unroll
+            for (int i = 0; i < BOPS; ++i) {
+                const unsigned off = (blk < nblk && b_off[i] != OOB) ? b_off[i] + add : OOB;
+                dma16(rw, base + i * NPROD * 1024, off);
+            }
+        };
+
+        issue_patch(0, 0);
+        issue_patch(0, 1);
+        issue_weights(0, 0, 0);
+        issue_weights(0, 1, 1);
+        for (int blk = 0; blk < nblk; ++blk) {
+            // step 3*blk: its weights were followed by those of step 3*blk+1 only
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(BOPS));
+            __syncthreads();
+            issue_patch(blk + 1, 0);
+            issue_weights(blk, 2, 2);
+            // step 3*blk+1: followed by half a patch and the weights of step 3*blk+2
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(POPS / 2 + BOPS));
+            __syncthreads();
+            issue_patch(blk + 1, 1);
+            issue_weights(blk + 1, 0, 0);
+            // step 3*blk+2: followed by the other half and the weights of step 3*blk+3
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(POPS / 2 + BOPS));
+            __syncthreads();
+            issue_weights(blk + 1, 1, 1);
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    } else {
+        // ------------------------------------------------------------ consumer
+        const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+        // Patch position of this lane's tile row at tap (0, 0).
+        int base = 0;
+        {
+            const int l = l0 + wave * 32 + frow;
+            const int rho = l / p.tw;
+            if (rho < NP) base = (vrow(rho) - v0) * pwt + (l - rho * p.tw);
+        }
+        for (int blk = 0; blk < nblk; ++blk) {
+            const __bf16 *pa = patch + (blk & 1) * PATCH;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                __syncthreads();
+                const __bf16 *wb = wring + r * BSTAGE;
+#pragma unroll
+                for (int s = 0; s < 3; ++s) {
+                    const int pos = base + r * pwt + s;
+                    const __bf16 *arow = pa + pos * BK;
+                    const int key = (pos >> 1) & 7;
+#pragma unroll
+                    for (int ks = 0; ks < BK / 16; ++ks) {
+                        const bf16x8 fa =
+                            *reinterpret_cast<const bf16x8 *>(arow + (((ks * 2 + fhalf) ^ key) * CHUNK));
+                        bf16x8 fb[NT];
+#pragma unroll
+                        for (int j = 0; j < NT; ++j)
+                            fb[j] = *reinterpret_cast<const bf16x8 *>(
+                                &wb[s * BN * BK + lds_pos(j * 32 + frow, ks * 2 + fhalf)]);
+#pragma unroll
+                        for (int j = 0; j < NT; ++j)
+                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[j], 0, 0, 0);
+                    }
+                }
             }
         }
     }
+
+    // Epilogue through LDS, as in the kernel above.
+    float *stg = reinterpret_cast<float *>(lds);
+    __syncthreads();
+    if (wave < NCONS) {
+        const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wave * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
+                stg[row * LDT + j * 32 + frow] = acc[j][v];
+            }
+    }
+    __syncthreads();
+    finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, [&](int row) {
+        const int l = l0 + row;
+        const int rho = l / p.tw;
+        const int q = q0 + (l - rho * p.tw);
+        return (rho < NP && q < p.Q) ? rho * p.Q + q : -1;
+    });
 }
 
 // ---------------------------------------------------------------------------
@@ -678,6 +912,49 @@ hipError_t launch_tile(ConvParams p, bool vec, int split_k, hipStream_t stream) 
     return hipGetLastError();
 }
 
+// Column-block width for the patch kernel and whether every tile's patch fits PATCH_PMAX
+// positions.  Small images use the whole row (tiles then cross rows and images), wide ones
+// 16-pixel blocks (tiles are 8 x 16 rectangles) or 14-pixel blocks when that divides the row.
+bool patch_geometry(const ConvParams &p, int *tw_out) {
+    int tw;
+    if (p.Q <= 16) tw = p.Q;
+    else if (p.Q % 16 == 0) tw = 16;
+    else if (p.Q % 14 == 0) tw = 14;
+    else tw = 16;
+    const int NP = p.N * p.P, Hp = p.H + 2 * p.pad;
+    const long long lin = 1LL * NP * tw;
+    int worst = 0;
+    for (long long l0 = 0; l0 < lin; l0 += PATCH_BM) {
+        const int r0 = static_cast<int>(l0 / tw);
+        const int r1 = static_cast<int>(std::min<long long>(NP - 1, (l0 + PATCH_BM - 1) / tw));
+        const int v0 = (r0 / p.P) * Hp + r0 % p.P, v1 = (r1 / p.P) * Hp + r1 % p.P + 2;
+        worst = std::max(worst, (v1 - v0 + 1) * (tw + 2));
+        if (worst > PATCH_PMAX) return false;
+    }
+    *tw_out = tw;
+    return true;
+}
+
+bool patch_eligible(const ConvParams &p, bool vec, int *tw_out) {
+    return vec && p.R == 3 && p.S == 3 && p.stride == 1 && p.pad == 1 && p.C % BK == 0 && p.P == p.H &&
+           p.Q == p.W && patch_geometry(p, tw_out);
+}
+
+template <int BN>
+hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream) {
+    p.tw = tw;
+    p.n_cb = (p.Q + tw - 1) / tw;
+    const long long lin = 1LL * p.N * p.P * tw;
+    const int tiles_m = static_cast<int>((lin + PATCH_BM - 1) / PATCH_BM) * p.n_cb;
+    p.tiles_n = (p.K + BN - 1) / BN;
+    p.n_tiles = tiles_m * p.tiles_n;
+    p.split_k = 1;
+    p.tiles_per_xcd = (p.n_tiles + 7) / 8;
+    hipLaunchKernelGGL((conv3x3_patch_kernel<BN, 4>), dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)),
+                       dim3(8 * 64), 0, stream, p);
+    return hipGetLastError();
+}
+
 // Off by default: the partial tiles cross dies through memory, which costs about 8 us per
 // launch on MI355X and only pays for layers with very few tiles and a very long depth.
 std::atomic<int> g_max_split_k{1};
@@ -735,6 +1012,7 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.sps = 0;
     p.part = ctx.scratch;
     p.cnt = ctx.counters;
+    p.tw = p.n_cb = 0;
 
     const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
@@ -753,7 +1031,7 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     int best = 0, best_split = 1;
     double best_cost = 0.0;
     const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
-    for (int o = 0; o < GPULET_CONV_TILES; ++o) {
+    for (int o = 0; o < static_cast<int>(sizeof(kOrder) / sizeof(kOrder[0])); ++o) {
         const int i = kOrder[o];
         const TileChoice &t = kTiles[i];
         const long long tiles = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
@@ -778,7 +1056,11 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
         best = forced;
         best_split = 1;
     }
+    int tw = 0;
+    const bool patch_ok = patch_eligible(p, vec, &tw);
+    if (best == 7 && !patch_ok) best = 1;  // the patch kernel does not apply: same tile shape, gathered
     switch (best) {
+        case 7: return launch_patch<64>(p, tw, stream);
         case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
         case 1: return launch_tile<128, 64, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
         case 2: return launch_tile<64, 128, 2, 4, 4, 3, 2, 2>(p, vec, best_split, stream);

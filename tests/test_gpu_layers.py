@@ -47,7 +47,7 @@ def test_conv_parity_every_tile(part, case):
     x, w, b = conv_tensors(11, N, C, H, W, K, R)
     ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
     first = None
-    for tile in range(-1, 7):
+    for tile in range(-1, 8):
         got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
         whole, per_img = oracle.rel_err(got, ref)
         assert max(whole, per_img) <= LAYER_TOL, (tile, whole, per_img)
@@ -57,6 +57,36 @@ def test_conv_parity_every_tile(part, case):
             first = raw.clone()
         else:  # without a split the accumulation order does not depend on the tile
             assert torch.equal(raw, first), tile
+
+
+# N, C, H, W, K: 3x3, stride 1, pad 1, C a multiple of 64 -> the kernel that keeps input patches in LDS
+PATCH_CASES = [
+    (3, 64, 14, 14, 64),       # whole rows per block; tiles cross rows and images (M = 588: ragged last tile)
+    (9, 128, 7, 7, 72),        # 7-pixel rows: a tile spans three images; K ragged
+    (2, 64, 56, 56, 64),       # 14-pixel column blocks, four per row
+    (1, 64, 32, 32, 32),       # 16-pixel column blocks: tiles are 8 x 16 rectangles
+    (2, 64, 20, 20, 40),       # 16-pixel blocks with a ragged second block (4 of 16 columns)
+    (2, 192, 9, 33, 136),      # odd sizes, three channel blocks, three channel tiles
+    (1, 64, 5, 3, 8),          # smaller than one tile
+    (2, 256, 16, 16, 64),      # block width = row width = 16, four channel blocks
+]
+
+
+@pytest.mark.parametrize("case", PATCH_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_patch_kernel_parity(part, case):
+    N, C, H, W, K = case
+    x, w, b = conv_tensors(17, N, C, H, W, K, 3)
+    res = inputs.tensor(17, "res_patch", (N, K, H, W), "normal")
+    ref = oracle.conv2d(x, w, b, 1, 1, True, residual=res)
+    got, raw = gpu_conv(part, x, w, b, 1, 1, True, residual=res, tile=7)
+    assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+    _, gathered = gpu_conv(part, x, w, b, 1, 1, True, residual=res, tile=1)
+    assert torch.equal(raw, gathered)          # same summation order as the gathering kernel
+    ct = K + 16
+    got, _ = gpu_conv(part, x, w, b, 1, 1, False, ch_total=ct, ch_offset=8, tile=7)
+    ref = oracle.conv2d(x, w, b, 1, 1, False)
+    assert oracle.rel_err(got[:, 8:8 + K], ref)[1] <= LAYER_TOL
+    assert np.all(got[:, :8] == -512.0) and np.all(got[:, 8 + K:] == -512.0)
 
 
 @pytest.mark.parametrize("case", [(32, 256, 14, 14, 256, 3, 1, 1), (2, 512, 7, 7, 512, 3, 1, 1),
@@ -111,7 +141,7 @@ def test_conv_delta_kernel_copies_input_exactly(part):
     assert np.array_equal(got, x.astype(np.float64))
 
 
-@pytest.mark.parametrize("tile", [-1, 0, 3, 4, 6])
+@pytest.mark.parametrize("tile", [-1, 0, 3, 4, 6, 7])
 def test_conv_residual_and_channel_slice(part, tile):
     N, C, H, W, K, R = 2, 32, 10, 10, 40, 3
     x, w, b = conv_tensors(15, N, C, H, W, K, R)
