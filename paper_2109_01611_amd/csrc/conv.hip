@@ -700,30 +700,40 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             const int rho = l / p.tw;
             if (rho < NP) base = (vrow(rho) - v0) * pwt + (l - rho * p.tw);
         }
+        // A ring step is 12 depth steps of 16 (three taps x four).  The fragments of depth
+        // step i+AHEAD are requested before the matrix instructions of step i are issued, so
+        // LDS reads and matrix instructions overlap inside the one wavefront a SIMD runs.
+        constexpr int KSTEPS = 3 * (BK / 16), AHEAD = 2;
+        struct Frags {
+            bf16x8 a, b[NT];
+        };
         for (int blk = 0; blk < nblk; ++blk) {
             const __bf16 *pa = patch + (blk & 1) * PATCH;
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
                 __syncthreads();
                 const __bf16 *wb = wring + r * BSTAGE;
-#pragma unroll
-                for (int s = 0; s < 3; ++s) {
+                auto load = [&](Frags &f, int i) {
+                    const int s = i / (BK / 16), ks = i % (BK / 16);
                     const int pos = base + r * pwt + s;
-                    const __bf16 *arow = pa + pos * BK;
-                    const int key = (pos >> 1) & 7;
+                    f.a = *reinterpret_cast<const bf16x8 *>(pa + pos * BK +
+                                                            (((ks * 2 + fhalf) ^ ((pos >> 1) & 7)) * CHUNK));
 #pragma unroll
-                    for (int ks = 0; ks < BK / 16; ++ks) {
-                        const bf16x8 fa =
-                            *reinterpret_cast<const bf16x8 *>(arow + (((ks * 2 + fhalf) ^ key) * CHUNK));
-                        bf16x8 fb[NT];
+                    for (int j = 0; j < NT; ++j)
+                        f.b[j] = *reinterpret_cast<const bf16x8 *>(
+                            &wb[s * BN * BK + lds_pos(j * 32 + frow, ks * 2 + fhalf)]);
+                };
+                Frags f[KSTEPS];
 #pragma unroll
-                        for (int j = 0; j < NT; ++j)
-                            fb[j] = *reinterpret_cast<const bf16x8 *>(
-                                &wb[s * BN * BK + lds_pos(j * 32 + frow, ks * 2 + fhalf)]);
+                for (int i = 0; i < AHEAD; ++i) load(f[i], i);
 #pragma unroll
-                        for (int j = 0; j < NT; ++j)
-                            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[j], 0, 0, 0);
-                    }
+                for (int i = 0; i < KSTEPS; ++i) {
+                    if (i + AHEAD < KSTEPS) load(f[i + AHEAD], i + AHEAD);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i].a, f[i].b[j], acc[j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
@@ -1059,6 +1069,22 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     int tw = 0;
     const bool patch_ok = patch_eligible(p, vec, &tw);
     if (best == 7 && !patch_ok) best = 1;  // the patch kernel does not apply: same tile shape, gathered
+    // The patch kernel runs one workgroup per CU.  Measured on MI355X it beats the gathering
+    // tiles when all of its workgroups are resident at once (a second round doubles its time)
+    // and the depth is long enough (four or more channel blocks) to amortise loading the
+    // first patch.
+    if (forced < 0 && patch_ok && p.C >= 4 * BK) {
+        const int n_cb = (p.Q + tw - 1) / tw;
+        const long long lin = 1LL * p.N * p.P * tw;
+        const long long tiles = ((lin + PATCH_BM - 1) / PATCH_BM) * n_cb * ((p.K + 63) / 64);
+        // Workgroups are dealt round-robin to 8 dies and, inside a die, to 4 shader engines; a
+        // CU holds one workgroup, so every shader engine must have a CU for each of its share.
+        const long long per_se = ((tiles + 7) / 8 + 3) / 4;
+        if (per_se <= n_cu / 32) {
+            best = 7;
+            best_split = 1;
+        }
+    }
     switch (best) {
         case 7: return launch_patch<64>(p, tw, stream);
         case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
