@@ -128,6 +128,34 @@ typedef struct gpulet_sched_entry {
 gpulet_status gpulet_elastic_partitioning(const gpulet_sched_problem *problem, gpulet_sched_entry *entries,
                                           int max_entries, int *n_entries, int *schedulable);
 
+/* ------------------------------------------------------------------------
+ * Interference model (Sec. 4.4):
+ *   factor = c1*l2_1 + c2*l2_2 + c3*mem_1 + c4*mem_2 + c5
+ * l2 / mem = L2 and memory-bandwidth utilisation of the victim (1) and the
+ * aggressor (2) in their solo runs; factor = the victim's co-run latency over
+ * its solo latency on the same gpu-let.  `features` is [n][4] row-major in
+ * the order (l2_1, l2_2, mem_1, mem_2); `coef` is c1..c5.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Ordinary least squares over n >= 5 samples (Householder QR).  GPULET_EINVAL
+ * when values are not finite or the samples do not determine five
+ * coefficients (a feature column that is constant or a combination of the
+ * others).
+ */
+gpulet_status gpulet_interference_fit(const double *features, const double *factor, int n, double *coef);
+
+/* factor[i] of the model for n feature rows. */
+gpulet_status gpulet_interference_predict(const double *coef, const double *features, int n, double *factor);
+
+/*
+ * Relative prediction error |model - measured| / measured over n samples
+ * (measured factors must be positive), reported at the percentiles q[0..n_q)
+ * (each in (0, 100], nearest rank) as in the error CDF of Fig. 9.
+ */
+gpulet_status gpulet_interference_error(const double *coef, const double *features, const double *factor, int n,
+                                        const double *q, int n_q, double *error_at_q);
+
 #ifdef __cplusplus
 }
 #endif

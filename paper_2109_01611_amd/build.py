@@ -12,11 +12,11 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpulet.so")
 
-SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "conv.hip", "pool.hip",
+SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "interference.cpp", "conv.hip", "pool.hip",
            "fc.hip", "probe.hip"]
 
 # The scheduler's fp64 decisions must not depend on fused multiply-adds.
-EXTRA = {"sched.cpp": ["-ffp-contract=off"]}
+EXTRA = {"sched.cpp": ["-ffp-contract=off"], "interference.cpp": ["-ffp-contract=off"]}
 
 # Packed-fp32 VALU forms are switched off for device code on purpose.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

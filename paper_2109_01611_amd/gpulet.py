@@ -112,6 +112,9 @@ def _load():
         "gpulet_max_efficient_partition": ([IP, DP, I, IP, DP], c_int32),
         "gpulet_min_required_partition": ([IP, DP, I, c_double, IP], c_int32),
         "gpulet_elastic_partitioning": ([POINTER(SchedProblem), POINTER(SchedEntry), I, IP, IP], c_int32),
+        "gpulet_interference_fit": ([DP, DP, I, DP], c_int32),
+        "gpulet_interference_predict": ([DP, DP, I, DP], c_int32),
+        "gpulet_interference_error": ([DP, DP, DP, I, DP, I, DP], c_int32),
     }
     for name, (argtypes, restype) in sig.items():
         fn = getattr(L, name)

@@ -79,5 +79,31 @@ def elastic_partitioning(sizes, batches, tables, rates, slos, n_gpu, slowdown=No
                             for e in entries[:n.value]]
 
 
+def interference_fit(features, factors):
+    """Least-squares c1..c5 of the interference model; ``features`` rows are
+    (l2_victim, l2_aggressor, mem_victim, mem_aggressor)."""
+    n = len(factors)
+    coef = (c_double * 5)()
+    _check(lib.gpulet_interference_fit(_flat(features), _doubles(factors), n, coef), "gpulet_interference_fit")
+    return list(coef)
+
+
+def interference_predict(coef, features):
+    n = len(features)
+    out = (c_double * n)()
+    _check(lib.gpulet_interference_predict(_doubles(coef), _flat(features), n, out), "gpulet_interference_predict")
+    return list(out)
+
+
+def interference_error(coef, features, factors, percentiles=(90.0, 95.0)):
+    """Relative prediction error at the given percentiles (nearest rank)."""
+    n = len(factors)
+    out = (c_double * len(percentiles))()
+    _check(lib.gpulet_interference_error(_doubles(coef), _flat(features), _doubles(factors), n,
+                                         _doubles(percentiles), len(percentiles), out),
+           "gpulet_interference_error")
+    return list(out)
+
+
 __all__ = ["affordable_rate", "rate_curve", "max_efficient_partition", "min_required_partition",
-           "elastic_partitioning", "gpulet"]
+           "elastic_partitioning", "interference_fit", "interference_predict", "interference_error", "gpulet"]
