@@ -154,41 +154,58 @@ __device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsig
 
 // Last step of the epilogue for a BM x BN fp32 tile parked in LDS (rows padded
 // to BN + 8 floats): every thread of the workgroup takes 8 consecutive channels
-// of one tile row, adds bias and residual, applies ReLU, rounds once to bf16
-// and stores 16 bytes.  `pixel_of(row)` gives the output pixel (n*P + p)*Q + q
-// of a tile row, or -1 for rows past the end.
+// of one tile row at a time, adds bias and residual, applies ReLU, rounds once
+// to bf16 and stores 16 bytes.  `pixel_of(row)` gives the output pixel
+// (n*P + p)*Q + q of a tile row, or -1 for rows past the end.  A thread keeps
+// its channel group for all of its rows, so the bias is loaded once, and the
+// residual loads of all its rows are issued before the first store: layers with
+// a short depth are bound by this loop, and one load-use-store chain per row
+// would leave it waiting for memory latency several times per tile.
 template <int BM, int BN, int NTHR, typename PixelOf>
 __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *stg, int n0, PixelOf pixel_of) {
     constexpr int LDT = BN + 8;
-    constexpr int VPR = BN / 8;  // 8-channel groups per tile row
-    const bool vec_ok = p.vec_store;
-    for (int it = threadIdx.x; it < BM * VPR; it += NTHR) {
-        const int row = it / VPR, cv = it - row * VPR;
-        const int m = pixel_of(row), k = n0 + cv * 8;
-        if (m < 0 || k >= p.K) continue;
-        const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
-        const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
-        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        if (vec_ok && k + 8 <= p.K) {
-            if (p.b) {
-                const float4 b0 = *reinterpret_cast<const float4 *>(p.b + k);
-                const float4 b1 = *reinterpret_cast<const float4 *>(p.b + k + 4);
-                v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-                v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-            }
-            if (p.res) {
-                const uint4 rr = *reinterpret_cast<const uint4 *>(p.res + (m * p.K + k));
-                const unsigned ru[4] = {rr.x, rr.y, rr.z, rr.w};
+    constexpr int VPR = BN / 8;            // 8-channel groups per tile row
+    constexpr int RSTEP = NTHR / VPR;      // tile rows between two items of a thread
+    constexpr int ITEMS = (BM + RSTEP - 1) / RSTEP;
+    static_assert(NTHR % VPR == 0, "a thread keeps its channel group");
+    const int cv = threadIdx.x % VPR, row0 = threadIdx.x / VPR;
+    const int k = n0 + cv * 8;
+    if (k >= p.K) return;
+    if (p.vec_store && k + 8 <= p.K) {
+        float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (p.b) {
+            const float4 b0 = *reinterpret_cast<const float4 *>(p.b + k);
+            const float4 b1 = *reinterpret_cast<const float4 *>(p.b + k + 4);
+            bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
+            bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
+        }
+        int m[ITEMS];
+        uint4 rr[ITEMS];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    v[2 * e] += __uint_as_float(ru[e] << 16);
-                    v[2 * e + 1] += __uint_as_float(ru[e] & 0xFFFF0000u);
-                }
-            }
+        for (int i = 0; i < ITEMS; ++i) {
+            const int row = row0 + i * RSTEP;
+            m[i] = row < BM ? pixel_of(row) : -1;
+            rr[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        if (p.res) {
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i)
+                if (m[i] >= 0) rr[i] = *reinterpret_cast<const uint4 *>(p.res + (m[i] * p.K + k));
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (m[i] < 0) continue;
+            const int row = row0 + i * RSTEP;
+            const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
+            const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
+            float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            const unsigned ru[4] = {rr[i].x, rr[i].y, rr[i].z, rr[i].w};
             unsigned pk[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float a = v[2 * e], b = v[2 * e + 1];
+                // a bf16 is the upper half of the fp32 with the same value; +0 where there is no residual
+                float a = v[2 * e] + bias[2 * e] + __uint_as_float(ru[e] << 16);
+                float b = v[2 * e + 1] + bias[2 * e + 1] + __uint_as_float(ru[e] & 0xFFFF0000u);
                 if (p.relu) {
                     a = a > 0.f ? a : 0.f;
                     b = b > 0.f ? b : 0.f;
@@ -197,10 +214,14 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
                 pk[e] = static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&ha)) |
                         (static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&hb)) << 16);
             }
-            *reinterpret_cast<uint4 *>(p.y + (m * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        } else {
+            *reinterpret_cast<uint4 *>(p.y + (m[i] * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        }
+    } else {
+        for (int row = row0; row < BM; row += RSTEP) {
+            const int m = pixel_of(row);
+            if (m < 0) continue;
             for (int e = 0; e < 8 && k + e < p.K; ++e) {
-                float a = v[e] + (p.b ? p.b[k + e] : 0.f);
+                float a = stg[row * LDT + cv * 8 + e] + (p.b ? p.b[k + e] : 0.f);
                 if (p.res) a += static_cast<float>(p.res[m * p.K + k + e]);
                 if (p.relu) a = a > 0.f ? a : 0.f;
                 p.y[m * p.ldy + p.y_off + k + e] = static_cast<__bf16>(a);
@@ -1054,7 +1075,12 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
             }
             const long long per_cu = (tiles * sk + n_cu - 1) / n_cu;
             const double share = 1.0 / sk + (sk > 1 ? 0.06 + 0.02 * sk : 0.0);
-            const double cost = static_cast<double>(per_cu) * t.bm * t.bn * share / t.eff;
+            double eff = t.eff;
+            // 128x128 runs two workgroups per CU when there are more tiles than CUs (see the
+            // launch below); the overlap of one's loads with the other's epilogue weighs more
+            // the shorter the depth (measured against 256x128 at 9 .. 72 slices).
+            if (i == 0 && sk == 1 && tiles > n_cu) eff = std::min(1.2, 0.90 + 3.0 / nk);
+            const double cost = static_cast<double>(per_cu) * t.bm * t.bn * share / eff;
             if ((o == 0 && sk == 1) || cost < best_cost) {
                 best = i;
                 best_split = sk;
@@ -1087,7 +1113,13 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     }
     switch (best) {
         case 7: return launch_patch<64>(p, tw, stream);
-        case 0: return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
+        case 0: {
+            // With more tiles than CUs, a two-stage ring (64 KB, two workgroups per CU, one's loads
+            // overlapping the other's epilogue) beats the deeper prefetch of three stages.
+            const long long tiles = 1LL * ((p.M + 127) / 128) * ((p.K + 127) / 128);
+            if (tiles > n_cu && best_split == 1) return launch_tile<128, 128, 4, 2, 4, 2, 2, 2>(p, vec, 1, stream);
+            return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
+        }
         case 1: return launch_tile<128, 64, 4, 2, 4, 3, 2, 2>(p, vec, best_split, stream);
         case 2: return launch_tile<64, 128, 2, 4, 4, 3, 2, 2>(p, vec, best_split, stream);
         case 3: return launch_tile<64, 64, 2, 2, 2, 3, 2, 2>(p, vec, best_split, stream);
