@@ -5,5 +5,5 @@ CPU-baseline leg may import this package; the product never does.
 """
 
 from .reference import (  # noqa: F401
-    avgpool, conv2d, fc, global_avgpool, maxpool, model_flops, model_params, num_threads,
+    avgpool, conv2d, depthwise_conv2d, fc, global_avgpool, maxpool, model_flops, model_params, num_threads,
     out_dim, rel_err, run_model)

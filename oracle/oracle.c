@@ -73,6 +73,43 @@ void oracle_conv2d(const double *x, const double *w, const double *b, const doub
 }
 
 /*
+ * Depthwise convolution (one filter per channel, as in the depthwise-separable
+ * blocks of MobileNet; the SSD-MobileNet of the paper's Table 4):
+ *   y[n,c,p,q] = b[c] + sum_{r,s} xz[n,c,p*stride-pad+r,q*stride-pad+s] * w[c,r,s]
+ * with the same zero extension, bias and ReLU rules as oracle_conv2d.
+ */
+void oracle_depthwise_conv2d(const double *x, const double *w, const double *b, double *y, int N, int C,
+                             int H, int W, int R, int S, int stride, int pad, int relu)
+{
+    const int P = oracle_out_dim(H, R, stride, pad);
+    const int Q = oracle_out_dim(W, S, stride, pad);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int c = 0; c < C; ++c) {
+            for (int p = 0; p < P; ++p) {
+                for (int q = 0; q < Q; ++q) {
+                    double acc = b ? b[c] : 0.0;
+                    for (int r = 0; r < R; ++r) {
+                        const int h = p * stride - pad + r;
+                        if (h < 0 || h >= H)
+                            continue;
+                        for (int s = 0; s < S; ++s) {
+                            const int v = q * stride - pad + s;
+                            if (v < 0 || v >= W)
+                                continue;
+                            acc += x[(((size_t)n * C + c) * H + h) * W + v] * w[((size_t)c * R + r) * S + s];
+                        }
+                    }
+                    if (relu && !(acc > 0.0))
+                        acc = 0.0;
+                    y[(((size_t)n * C + c) * P + p) * Q + q] = acc;
+                }
+            }
+        }
+    }
+}
+
+/*
  * Max pooling over a k x k window: only taps inside the image take part
  * (padding acts as minus infinity).  A window with no tap inside the image
  * cannot occur when pad < k.

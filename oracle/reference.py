@@ -31,6 +31,8 @@ def _load():
         lib.oracle_out_dim.restype = _I
         lib.oracle_conv2d.argtypes = [_DP, _DP, _DP, _DP, _DP] + [_I] * 10
         lib.oracle_conv2d.restype = None
+        lib.oracle_depthwise_conv2d.argtypes = [_DP, _DP, _DP, _DP] + [_I] * 9
+        lib.oracle_depthwise_conv2d.restype = None
         lib.oracle_maxpool.argtypes = [_DP, _DP] + [_I] * 7
         lib.oracle_maxpool.restype = None
         lib.oracle_avgpool.argtypes = [_DP, _DP] + [_I] * 7
@@ -126,6 +128,26 @@ def fc(x, w, b=None, relu=False):
     return y
 
 
+def depthwise_conv2d(x, w, b=None, stride=1, pad=0, relu=False):
+    """Depthwise convolution layer (MobileNet blocks of the paper's SSD-MobileNet,
+    Table 4).  x (N,C,H,W), w (C,1,R,S) as PyTorch stores a grouped filter, b (C,)."""
+    lib = _load()
+    x, w = _f64(x), _f64(w)
+    N, C, H, W = x.shape
+    if w.ndim != 4 or w.shape[0] != C or w.shape[1] != 1:
+        raise ValueError("depthwise filter must be (C, 1, R, S)")
+    R, S = w.shape[2], w.shape[3]
+    P, Q = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    if P <= 0 or Q <= 0:
+        raise ValueError("empty output")
+    b = _f64(b) if b is not None else None
+    if b is not None and b.shape != (C,):
+        raise ValueError("bias shape")
+    y = np.empty((N, C, P, Q), dtype=np.float64)
+    lib.oracle_depthwise_conv2d(_p(x), _p(w), _p(b), _p(y), N, C, H, W, R, S, stride, pad, int(bool(relu)))
+    return y
+
+
 def run_model(model, params, x, keep=False):
     """Forward pass of a ``workloads.Model`` on batch ``x`` (N,C,H,W) in fp64.
 
@@ -138,6 +160,9 @@ def run_model(model, params, x, keep=False):
             w, b = params[nd.name]
             res = t[a["residual"]] if a["residual"] else None
             t[nd.dst] = conv2d(t[nd.src], w, b, a["stride"], a["pad"], a["relu"], res)
+        elif nd.op == "dwconv":
+            w, b = params[nd.name]
+            t[nd.dst] = depthwise_conv2d(t[nd.src], w, b, a["stride"], a["pad"], a["relu"])
         elif nd.op == "maxpool":
             t[nd.dst] = maxpool(t[nd.src], a["k"], a["stride"], a["pad"])
         elif nd.op == "gavgpool":
@@ -169,6 +194,12 @@ def model_flops(model):
             shapes[nd.dst] = (a["K"], P, Q)
             if a["residual"]:
                 assert shapes[a["residual"]] == shapes[nd.dst], nd.name
+        elif nd.op == "dwconv":
+            C, H, W = shapes[nd.src]
+            assert C == a["C"], (nd.name, C, a["C"])
+            P, Q = out_dim(H, a["k"], a["stride"], a["pad"]), out_dim(W, a["k"], a["stride"], a["pad"])
+            conv += 2 * P * Q * C * a["k"] * a["k"]
+            shapes[nd.dst] = (C, P, Q)
         elif nd.op == "maxpool":
             C, H, W = shapes[nd.src]
             shapes[nd.dst] = (C, out_dim(H, a["k"], a["stride"], a["pad"]),
@@ -194,6 +225,9 @@ def model_params(model):
         if nd.op == "conv":
             a = nd.attr
             n += a["K"] * a["C"] * a["k"] * a["k"] + a["K"]
+        elif nd.op == "dwconv":
+            a = nd.attr
+            n += a["C"] * a["k"] * a["k"] + a["C"]
         elif nd.op == "fc":
             n += nd.attr["Out"] * nd.attr["In"] + nd.attr["Out"]
     return n

@@ -14,6 +14,7 @@ Node kinds (all convolutions and pools are square):
 
   conv     src -> dst   C, K, k, stride, pad, relu, optional residual tensor
                         that is added before the ReLU
+  dwconv   src -> dst   C, k, stride, pad, relu: one k x k filter per channel
   maxpool  src -> dst   k, stride, pad (padding never wins the max)
   gavgpool src -> dst   mean over the whole H x W plane
   fc       src -> dst   In, Out, relu; In is flattened from (C, H, W)
@@ -31,6 +32,10 @@ Model = namedtuple("Model", "name in_shape in_dist nodes out")
 def _conv(name, src, dst, C, K, k, stride=1, pad=0, relu=True, residual=None):
     return Node("conv", name, src, dst,
                 dict(C=C, K=K, k=k, stride=stride, pad=pad, relu=relu, residual=residual))
+
+
+def _dwconv(name, src, dst, C, k, stride=1, pad=0, relu=True):
+    return Node("dwconv", name, src, dst, dict(C=C, k=k, stride=stride, pad=pad, relu=relu))
 
 
 def _maxpool(name, src, dst, k, stride, pad=0):
@@ -180,6 +185,45 @@ def googlenet(width_div=1, in_hw=224, n_class=1000, n_blocks=9):
                  (3, in_hw, in_hw), "uniform", nodes, "y")
 
 
+def ssd_mobilenet(width_div=1, in_hw=300, n_class=91):
+    """SSD-MobileNet shape (Table 4: camera data, 3x300x300): a MobileNet-v1
+    backbone (3x3 stride-2 stem, 13 depthwise-separable blocks), four extra
+    1x1 + 3x3 stride-2 feature stages and, on each of six feature maps, a 1x1
+    box head (4 values per anchor) and a 1x1 class head (``n_class`` scores
+    per anchor; 3 anchors on the first map, 6 on the others), concatenated
+    per map.  ReLU stands in for ReLU6 and no box decoding follows: the
+    workload is the dense part of the network.  The model's output tensor is
+    the head of the last (smallest) map; the other heads are the named
+    tensors ``head1`` .. ``head5``.  ``width_div`` and ``in_hw`` shrink it for
+    CPU-sized tests."""
+    d = width_div
+    ch = lambda c: max(8, c // d)
+    nodes = [_conv("stem", "x", "s0", 3, ch(32), 3, 2, 1, True)]
+    src, C = "s0", ch(32)
+    blocks = [(64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2), (512, 1), (512, 1), (512, 1), (512, 1),
+              (512, 1), (1024, 2), (1024, 1)]
+    feats = []
+    for i, (K, stride) in enumerate(blocks, 1):
+        nodes.append(_dwconv("dw%d" % i, src, "d%d" % i, C, 3, stride, 1, True))
+        nodes.append(_conv("pw%d" % i, "d%d" % i, "b%d" % i, C, ch(K), 1, 1, 0, True))
+        src, C = "b%d" % i, ch(K)
+        if i in (11, 13):
+            feats.append((src, C))
+    for j, (mid, K) in enumerate([(256, 512), (128, 256), (128, 256), (64, 128)], 1):
+        nodes.append(_conv("extra%d_a" % j, src, "e%da" % j, C, ch(mid), 1, 1, 0, True))
+        nodes.append(_conv("extra%d_b" % j, "e%da" % j, "e%db" % j, ch(mid), ch(K), 3, 2, 1, True))
+        src, C = "e%db" % j, ch(K)
+        feats.append((src, C))
+    for m, (f, fc) in enumerate(feats, 1):
+        anchors = 3 if m == 1 else 6
+        nodes.append(_conv("box%d" % m, f, "box%d" % m, fc, 4 * anchors, 1, 1, 0, False))
+        nodes.append(_conv("cls%d" % m, f, "cls%d" % m, fc, n_class * anchors, 1, 1, 0, False))
+        nodes.append(_concat("head%d" % m, ["box%d" % m, "cls%d" % m], "y" if m == len(feats) else "head%d" % m))
+    full = width_div == 1 and in_hw == 300 and n_class == 91
+    return Model("ssd_mobilenet" if full else "ssd_mobilenet_w%d_%d_%d" % (width_div, in_hw, n_class),
+                 (3, in_hw, in_hw), "uniform", nodes, "y")
+
+
 def parameters(model, seed=0):
     """Seeded weights and biases of ``model``: ``{node name: (w, b)}`` with
     ``w`` in the canonical (K, C, R, S) / (Out, In) order, bfloat16-exact
@@ -189,6 +233,9 @@ def parameters(model, seed=0):
         if nd.op == "conv":
             a = nd.attr
             shape = (a["K"], a["C"], a["k"], a["k"])
+        elif nd.op == "dwconv":
+            a = nd.attr
+            shape = (a["C"], 1, a["k"], a["k"])
         elif nd.op == "fc":
             shape = (nd.attr["Out"], nd.attr["In"])
         else:

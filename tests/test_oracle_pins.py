@@ -389,3 +389,93 @@ def test_lenet_and_vgg_wiring_against_handwritten_torch():
     want = F.linear(t, *tp["fc8"]).numpy()
     got = oracle.run_model(m, P, x)
     assert np.max(np.abs(got - want)) < 1e-11 * max(1.0, np.abs(want).max())
+
+
+# ---------------------------------------------------------------- depthwise convolution (SSD-MobileNet shape)
+
+@pytest.mark.parametrize("R,stride,pad", [(3, 1, 1), (3, 2, 1), (3, 1, 0), (5, 2, 2), (1, 1, 0)])
+def test_depthwise_brute_force_and_block_diagonal_full_conv(R, stride, pad):
+    N, C, H, W = 2, 5, 7, 6
+    x = RNG.standard_normal((N, C, H, W))
+    w = RNG.standard_normal((C, 1, R, R))
+    b = RNG.standard_normal(C)
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    for relu in (False, True):
+        got = oracle.depthwise_conv2d(x, w, b, stride, pad, relu)
+        want = np.zeros((N, C, P, Q))
+        for n, c, p, q in itertools.product(range(N), range(C), range(P), range(Q)):
+            acc = float(b[c])
+            for r, s in itertools.product(range(R), range(R)):
+                h, v = p * stride + r - pad, q * stride + s - pad
+                if 0 <= h < H and 0 <= v < W:
+                    acc += float(x[n, c, h, v]) * float(w[c, 0, r, s])
+            want[n, c, p, q] = max(acc, 0.0) if relu else acc
+        assert np.max(np.abs(got - want)) < 1e-12
+        # a depthwise convolution is a full convolution whose filter bank is diagonal in (k, c)
+        full = np.zeros((C, C, R, R))
+        for c in range(C):
+            full[c, c] = w[c, 0]
+        assert np.max(np.abs(got - oracle.conv2d(x, full, b, stride, pad, relu))) < 1e-12
+        t = F.conv2d(torch.from_numpy(x), torch.from_numpy(w), torch.from_numpy(b), stride, pad, groups=C)
+        t = F.relu(t) if relu else t
+        assert np.max(np.abs(got - t.numpy())) < 1e-12
+
+
+def test_depthwise_channels_do_not_mix_and_taps_are_not_transposed():
+    x = RNG.standard_normal((1, 3, 6, 6))
+    w = np.zeros((3, 1, 3, 3))
+    w[0, 0, 1, 1] = 1.0          # channel 0: identity
+    w[1, 0, 0, 1] = 1.0          # channel 1: reads the pixel above
+    w[2, 0, 1, 2] = 2.0          # channel 2: twice the pixel to the right
+    y = oracle.depthwise_conv2d(x, w, None, 1, 1)
+    assert np.array_equal(y[0, 0], x[0, 0])
+    assert np.array_equal(y[0, 1, 1:], x[0, 1, :-1]) and np.all(y[0, 1, 0] == 0)
+    assert np.array_equal(y[0, 2, :, :-1], 2 * x[0, 2, :, 1:]) and np.all(y[0, 2, :, -1] == 0)
+
+
+def test_ssd_mobilenet_totals_match_published_counts():
+    # MobileNets paper (Howard et al. 2017), COCO detection table: SSD 300 with MobileNet,
+    # 1.2 billion mult-adds and 6.8 million parameters.
+    m = workloads.ssd_mobilenet()
+    conv, fcf = oracle.model_flops(m)
+    assert fcf == 0
+    assert abs(conv / 2 / 1e9 - 1.2) < 0.05
+    assert abs(oracle.model_params(m) / 1e6 - 6.8) < 0.05
+    assert sum(1 for nd in m.nodes if nd.op == "dwconv") == 13
+    # the backbone at 224x224 is MobileNet-v1 without its classifier: that paper gives 569 M mult-adds and
+    # 4.2 M parameters including the 1024 -> 1000 fully connected layer
+    m224 = workloads.ssd_mobilenet(in_hw=224)
+    back = [nd for nd in m224.nodes if nd.name == "stem" or nd.name.startswith(("dw", "pw"))]
+    sub = workloads.Model("b", m224.in_shape, m224.in_dist, back, back[-1].dst)
+    assert abs((oracle.model_flops(sub)[0] / 2 + 1024 * 1000) / 1e6 - 569) < 1.0
+    assert abs((oracle.model_params(sub) + 1024 * 1000 + 1000) / 1e6 - 4.2) < 0.05
+
+
+def test_ssd_wiring_against_handwritten_torch():
+    m = workloads.ssd_mobilenet(width_div=8, in_hw=64, n_class=3)
+    P = workloads.parameters(m, seed=5)
+    x = workloads.batch_input(m, 2, seed=5)
+    T = oracle.run_model(m, P, x, keep=True)
+
+    def cv(t, name, stride=1, pad=0, groups=1):
+        w, b = P[name]
+        return F.conv2d(t, torch.from_numpy(w).double(), torch.from_numpy(b).double(), stride, pad, groups=groups)
+    t = F.relu(cv(torch.from_numpy(x).double(), "stem", 2, 1))
+    strides = [1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1]
+    feats = []
+    for i, st in enumerate(strides, 1):
+        t = F.relu(cv(t, "dw%d" % i, st, 1, groups=t.shape[1]))
+        t = F.relu(cv(t, "pw%d" % i))
+        if i in (11, 13):
+            feats.append(t)
+    for j in range(1, 5):
+        t = F.relu(cv(t, "extra%d_a" % j))
+        t = F.relu(cv(t, "extra%d_b" % j, 2, 1))
+        feats.append(t)
+    assert len(feats) == 6
+    for k, f in enumerate(feats, 1):
+        head = torch.cat([cv(f, "box%d" % k), cv(f, "cls%d" % k)], dim=1).numpy()
+        name = "y" if k == 6 else "head%d" % k
+        assert head.shape == T[name].shape
+        assert head.shape[1] == (3 if k == 1 else 6) * (4 + 3)
+        assert np.max(np.abs(head - T[name])) < 1e-9 * max(1.0, np.abs(head).max())
