@@ -189,6 +189,20 @@ gpulet_status gpulet_set_conv_tile(int tile);
  */
 gpulet_status gpulet_set_conv_split_k(int max_split);
 
+/*
+ * Depthwise convolution (one R x S filter per channel; the depthwise-separable
+ * blocks of the SSD-MobileNet of Table 4), fused bias and ReLU:
+ *   y[n,p,q,c] = act(b[c] + sum_{r,s} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[r,s,c])
+ * x: N*H*W*C bf16 NHWC, w: R*S*C bf16 (channel fastest), b: C fp32 or NULL,
+ * y: N*P*Q*C bf16.  fp32 accumulation in (r, s) order, one rounding to bf16.
+ * Bound by memory traffic (one multiply-add per input element), so it runs on
+ * the vector units.  GPULET_EINVAL for NULL x/w/y, non-positive sizes, an
+ * empty output or tensors of 2^30 elements or more.
+ */
+gpulet_status gpulet_depthwise_conv2d_fwd(const void *x, const void *w, const float *b, void *y, int N, int C,
+                                          int H, int W, int R, int S, int stride, int pad, int relu,
+                                          void *stream);
+
 enum { GPULET_POOL_MAX = 0, GPULET_POOL_AVG = 1, GPULET_POOL_GLOBAL_AVG = 2 };
 
 /*
@@ -214,7 +228,7 @@ gpulet_status gpulet_fc(const void *x, const void *w, const float *b, void *y, i
  * Whole model on a gpu-let (Sec. 5 "Backend inference executor").
  * ------------------------------------------------------------------------ */
 
-enum { GPULET_OP_CONV = 0, GPULET_OP_POOL = 1, GPULET_OP_FC = 2 };
+enum { GPULET_OP_CONV = 0, GPULET_OP_POOL = 1, GPULET_OP_FC = 2, GPULET_OP_DWCONV = 3 };
 
 /*
  * One layer.  Activations live in numbered buffers; a layer reads in_buf and
@@ -226,20 +240,20 @@ typedef struct gpulet_layer {
     int32_t in_buf;        /* buffer read */
     int32_t out_buf;       /* buffer written */
     int32_t res_buf;       /* CONV: buffer added before the ReLU, or -1 */
-    int32_t C;             /* CONV/POOL: input channels; FC: In (= C*H*W of in_buf) */
+    int32_t C;             /* CONV/DWCONV/POOL: input channels; FC: In (= C*H*W of in_buf) */
     int32_t K;             /* CONV: output channels; FC: Out */
-    int32_t R;             /* CONV: kernel height; POOL: window k */
-    int32_t S;             /* CONV: kernel width */
+    int32_t R;             /* CONV/DWCONV: kernel height; POOL: window k */
+    int32_t S;             /* CONV/DWCONV: kernel width */
     int32_t stride;
     int32_t pad;
-    int32_t relu;          /* CONV/FC */
+    int32_t relu;          /* CONV/DWCONV/FC */
     int32_t mode;          /* POOL: GPULET_POOL_* */
     int32_t out_ch_total;  /* CONV: channels of out_buf when this layer writes a slice of
                               a concatenated tensor; 0 means K */
     int32_t out_ch_offset; /* CONV: first channel written */
     int32_t out_fp32;      /* FC: store fp32 instead of bf16 */
     int32_t reserved;
-    const void *w;         /* device: CONV KRSC bf16, FC [Out][In] bf16 */
+    const void *w;         /* device: CONV KRSC bf16, DWCONV RSC bf16, FC [Out][In] bf16 */
     const float *b;        /* device: fp32 bias or NULL */
 } gpulet_layer;
 

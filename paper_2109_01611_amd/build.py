@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpulet.so")
 
-SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "interference.cpp", "conv.hip", "pool.hip",
+SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "interference.cpp", "conv.hip", "dwconv.hip", "pool.hip",
            "fc.hip", "probe.hip"]
 
 # The scheduler's fp64 decisions must not depend on fused multiply-adds.

@@ -67,7 +67,7 @@ struct LaunchCtx {
 LaunchCtx stream_ctx(hipStream_t stream);
 LaunchCtx partition_ctx(const gpulet_partition *p);
 
-// Kernel launchers (conv.hip, pool.hip, fc.hip).  Arguments are validated by the callers.
+// Kernel launchers (conv.hip, dwconv.hip, pool.hip, fc.hip).  Arguments are validated by the callers.
 struct ConvArgs {
     const void *x, *w;
     const float *b;
@@ -82,6 +82,8 @@ hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P
                        int k, int stride, int pad, hipStream_t stream);
 hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
                      int relu, int out_fp32, hipStream_t stream);
+hipError_t launch_dwconv(const void *x, const void *w, const float *b, void *y, int N, int C, int H, int W,
+                         int R, int S, int stride, int pad, int relu, int P, int Q, hipStream_t stream);
 hipError_t launch_probe(uint32_t *out, int n_blocks, hipStream_t stream);
 
 // Argument checks shared by the single-layer entry points and the model runner.
@@ -89,5 +91,6 @@ gpulet_status check_conv(const ConvArgs &a);
 gpulet_status check_pool(int N, int C, int H, int W, int mode, int k, int stride, int pad, int *P,
                          int *Q);
 gpulet_status check_fc(int N, int In, int Out);
+gpulet_status check_dwconv(int N, int C, int H, int W, int R, int S, int stride, int pad, int *P, int *Q);
 
 }  // namespace gpulet

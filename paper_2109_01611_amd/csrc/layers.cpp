@@ -55,6 +55,18 @@ extern "C" gpulet_status gpulet_set_conv_split_k(int max_split) {
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_depthwise_conv2d_fwd(const void *x, const void *w, const float *b, void *y,
+                                                     int N, int C, int H, int W, int R, int S, int stride,
+                                                     int pad, int relu, void *stream) {
+    if (!x || !w || !y) return GPULET_EINVAL;
+    int P = 0, Q = 0;
+    gpulet_status st = check_dwconv(N, C, H, W, R, S, stride, pad, &P, &Q);
+    if (st != GPULET_OK) return st;
+    GPULET_HIP(launch_dwconv(x, w, b, y, N, C, H, W, R, S, stride, pad, relu ? 1 : 0, P, Q,
+                             static_cast<hipStream_t>(stream)));
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_pool(const void *x, void *y, int N, int C, int H, int W, int mode,
                                      int k, int stride, int pad, void *stream) {
     if (!x || !y) return GPULET_EINVAL;

@@ -28,8 +28,8 @@ struct Step {
     int op;
     int in_buf, out_buf, res_buf;
     ConvArgs conv;  // CONV
-    int N, C, H, W, P, Q, mode, k, stride, pad;  // POOL
-    int In, Out, relu, out_fp32;                 // FC
+    int N, C, H, W, P, Q, mode, k, k2, stride, pad;  // POOL (k); DWCONV (k x k2, relu)
+    int In, Out, relu, out_fp32;                     // FC
     const void *w;
     const float *b;
 };
@@ -109,6 +109,14 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
             s.N = batch; s.C = src.C; s.H = src.H; s.W = src.W; s.P = P; s.Q = Q;
             s.mode = L.mode; s.k = L.R; s.stride = L.stride; s.pad = L.pad;
             oc = src.C; oh = P; ow = Q;
+        } else if (L.op == GPULET_OP_DWCONV) {
+            if (L.C != src.C || !L.w) return GPULET_EINVAL;
+            int P = 0, Q = 0;
+            gpulet_status st = check_dwconv(batch, src.C, src.H, src.W, L.R, L.S, L.stride, L.pad, &P, &Q);
+            if (st != GPULET_OK) return st;
+            s.N = batch; s.C = src.C; s.H = src.H; s.W = src.W; s.P = P; s.Q = Q;
+            s.k = L.R; s.k2 = L.S; s.stride = L.stride; s.pad = L.pad; s.relu = L.relu ? 1 : 0;
+            oc = src.C; oh = P; ow = Q;
         } else if (L.op == GPULET_OP_FC) {
             if (!L.w || 1LL * src.C * src.H * src.W != L.C) return GPULET_EINVAL;
             gpulet_status st = check_fc(batch, L.C, L.K);
@@ -160,6 +168,9 @@ hipError_t enqueue(const Bound &bd, const LaunchCtx &ctx, hipStream_t stream) {
         } else if (s.op == GPULET_OP_POOL) {
             e = launch_pool(bd.ptr(s.in_buf), bd.ptr(s.out_buf), s.N, s.C, s.H, s.W, s.P, s.Q, s.mode, s.k,
                             s.stride, s.pad, stream);
+        } else if (s.op == GPULET_OP_DWCONV) {
+            e = launch_dwconv(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.C, s.H, s.W, s.k, s.k2,
+                              s.stride, s.pad, s.relu, s.P, s.Q, stream);
         } else {
             e = launch_fc(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.In, s.Out, s.relu, s.out_fp32,
                           stream);

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(_HERE, "libgpulet.so")
 
 OK, EINVAL, EOVERSUB, EHIP, ENOMEM = 0, -1, -2, -3, -4
 POOL_MAX, POOL_AVG, POOL_GLOBAL_AVG = 0, 1, 2
-OP_CONV, OP_POOL, OP_FC = 0, 1, 2
+OP_CONV, OP_POOL, OP_FC, OP_DWCONV = 0, 1, 2, 3
 
 
 class GpuletError(RuntimeError):
@@ -95,6 +95,7 @@ def _load():
         "gpulet_conv2d_fwd_ex": ([P, P, P, P] + [I] * 10 + [P, I, I, P], c_int32),
         "gpulet_set_conv_tile": ([I], c_int32),
         "gpulet_set_conv_split_k": ([I], c_int32),
+        "gpulet_depthwise_conv2d_fwd": ([P, P, P, P] + [I] * 9 + [P], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
         "gpulet_model_workspace_bytes": ([POINTER(ModelDesc), I, POINTER(c_size_t)], c_int32),
@@ -218,6 +219,11 @@ def set_conv_tile(tile):
 
 def set_conv_split_k(max_split):
     _check(lib.gpulet_set_conv_split_k(max_split), "gpulet_set_conv_split_k")
+
+
+def depthwise_conv2d_fwd(x, w, b, y, N, C, H, W, R, S, stride, pad, relu, stream=None):
+    _check(lib.gpulet_depthwise_conv2d_fwd(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, R, S, stride, pad,
+                                           int(relu), stream), "gpulet_depthwise_conv2d_fwd")
 
 
 def pool(x, y, N, C, H, W, mode, k=1, stride=1, pad=0, stream=None):

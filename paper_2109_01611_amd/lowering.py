@@ -67,7 +67,7 @@ class DeviceModel:
         for nd in nodes:
             if nd.op == "conv":
                 chans[nd.dst] = nd.attr["K"]
-            elif nd.op in ("maxpool", "gavgpool"):
+            elif nd.op in ("maxpool", "gavgpool", "dwconv"):
                 chans[nd.dst] = chans[nd.src]
             elif nd.op == "fc":
                 chans[nd.dst] = nd.attr["Out"]
@@ -132,6 +132,14 @@ class DeviceModel:
                 if nd.dst in alias:
                     _, off, total = alias[nd.dst]
                     L.out_ch_total, L.out_ch_offset = total, off
+                L.w, L.b = wd.data_ptr(), bd.data_ptr()
+            elif nd.op == "dwconv":
+                w, b = params[nd.name]
+                wd = to_device_bf16(np.transpose(np.asarray(w)[:, 0], (1, 2, 0)), self.device)   # (C,1,R,S) -> RSC
+                bd = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(self.device)
+                self._keep += [wd, bd]
+                L.op, L.C, L.R, L.S = gpulet.OP_DWCONV, a["C"], a["k"], a["k"]
+                L.stride, L.pad, L.relu = a["stride"], a["pad"], int(a["relu"])
                 L.w, L.b = wd.data_ptr(), bd.data_ptr()
             elif nd.op == "maxpool":
                 L.op, L.C, L.R, L.stride, L.pad = gpulet.OP_POOL, chans[nd.src], a["k"], a["stride"], a["pad"]

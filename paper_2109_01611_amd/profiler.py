@@ -38,6 +38,11 @@ def model_flops(model):
             P, Q = _extent(H, a["k"], a["stride"], a["pad"]), _extent(W, a["k"], a["stride"], a["pad"])
             conv += 2 * P * Q * a["K"] * C * a["k"] * a["k"]
             shape[nd.dst] = (a["K"], P, Q)
+        elif nd.op == "dwconv":
+            C, H, W = shape[nd.src]
+            P, Q = _extent(H, a["k"], a["stride"], a["pad"]), _extent(W, a["k"], a["stride"], a["pad"])
+            conv += 2 * P * Q * C * a["k"] * a["k"]
+            shape[nd.dst] = (C, P, Q)
         elif nd.op == "maxpool":
             C, H, W = shape[nd.src]
             shape[nd.dst] = (C, _extent(H, a["k"], a["stride"], a["pad"]), _extent(W, a["k"], a["stride"], a["pad"]))
@@ -241,10 +246,11 @@ CONFIGS = {
     "resnet50": (workloads.resnet50, [1, 8, 32], [25, 50, 100]),
     "vgg16": (workloads.vgg16, [16], [50, 100]),
     "googlenet": (workloads.googlenet, [32], [50, 100]),
+    "ssd_mobilenet": (workloads.ssd_mobilenet, [32], [50, 100]),
 }
 
 # The scheduler's input: every model over the whole profiled grid (Fig. 3).
-GRID_MODELS = ("lenet5", "googlenet", "resnet50", "vgg16")
+GRID_MODELS = ("lenet5", "googlenet", "resnet50", "ssd_mobilenet", "vgg16")
 
 
 def main(argv=None):

@@ -155,6 +155,54 @@ def test_conv_residual_and_channel_slice(part, tile):
     assert np.all(got[:, :24] == -512.0) and np.all(got[:, 64:] == -512.0)
 
 
+# N, C, H, W, k, stride, pad
+DW_CASES = [
+    (2, 32, 19, 19, 3, 1, 1),       # Q = 19: ragged group of four pixels per thread
+    (2, 64, 20, 20, 3, 2, 1),       # MobileNet's stride-2 blocks
+    (1, 8, 5, 7, 3, 1, 1),
+    (3, 24, 9, 9, 3, 2, 0),
+    (1, 16, 11, 11, 5, 1, 2),
+    (2, 40, 6, 6, 5, 2, 2),
+    (2, 12, 7, 7, 3, 1, 1),         # C not a multiple of 8: scalar path
+    (1, 3, 10, 10, 3, 2, 1),
+    (1, 512, 10, 10, 3, 1, 1),
+    (2, 16, 4, 4, 1, 1, 0),         # 1x1 depthwise = per-channel scale
+]
+
+
+@pytest.mark.parametrize("case", DW_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_depthwise_conv_parity(part, case):
+    N, C, H, W, k, stride, pad = case
+    x = inputs.tensor(21, "dw/x", (N, C, H, W), "normal")
+    w = inputs.he_normal(21, "dw/w", (C, 1, k, k))
+    b = inputs.bias(21, "dw/b", C)
+    P, Q = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    xd = lowering.nchw_to_nhwc(x, DEV)
+    wd = lowering.to_device_bf16(np.transpose(w[:, 0], (1, 2, 0)), DEV)
+    bd = torch.from_numpy(b).to(DEV)
+    for relu, bias in ((True, bd), (False, None)):
+        yd = torch.full((N, P, Q, C), -512.0, dtype=torch.bfloat16, device=DEV)
+        torch.cuda.synchronize()
+        gpulet.depthwise_conv2d_fwd(xd, wd, bias, yd, N, C, H, W, k, k, stride, pad, relu, part.stream)
+        part.sync()
+        got = lowering.nhwc_to_nchw(yd)
+        ref = oracle.depthwise_conv2d(x, w, b if bias is not None else None, stride, pad, relu)
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+        assert not np.any(got == -512.0)
+
+
+def test_depthwise_argument_errors(part):
+    t = torch.zeros(64, dtype=torch.bfloat16, device=DEV)
+    for bad in [dict(N=0), dict(C=0), dict(k=0), dict(stride=0), dict(pad=-1), dict(H=2, k=5)]:
+        a = dict(N=1, C=8, H=4, W=4, k=3, stride=1, pad=1)
+        a.update(bad)
+        with pytest.raises(gpulet.GpuletError):
+            gpulet.depthwise_conv2d_fwd(t, t, None, t, a["N"], a["C"], a["H"], a["W"], a["k"], a["k"], a["stride"],
+                                        a["pad"], True, part.stream)
+    with pytest.raises(gpulet.GpuletError):
+        gpulet.depthwise_conv2d_fwd(None, t, None, t, 1, 8, 4, 4, 3, 3, 1, 1, True, part.stream)
+
+
 # N, C, H, W, mode, k, stride, pad
 POOL_CASES = [
     (2, 6, 28, 28, gpulet.POOL_MAX, 2, 2, 0), (2, 16, 10, 10, gpulet.POOL_MAX, 2, 2, 0),

@@ -52,6 +52,7 @@ def test_lenet5_on_small_gpulets(pct, which):
     workloads.resnet50(width_div=4, in_hw=64, n_class=20, blocks=(2, 2, 2, 2)),
     workloads.googlenet(width_div=2, in_hw=64, n_class=20),
     workloads.vgg16(width_div=8, in_hw=64, n_class=20),
+    workloads.ssd_mobilenet(width_div=4, in_hw=96, n_class=5),
 ], ids=lambda m: m.name)
 def test_small_variants(model):
     got, ref, _, _, _, _ = _run(model, 3, seed=5)
@@ -84,6 +85,54 @@ def test_per_layer_parity_on_actual_inputs():
         t[nd.dst] = got  # the next layer's oracle input is what the device really produced
 
 
+def test_ssd_mobilenet_every_head_and_depthwise_layer():
+    # the model's output is only the last head: read every named tensor back and check each
+    # layer against the oracle on the layer's actual (bf16) device input
+    model = workloads.ssd_mobilenet(width_div=4, in_hw=128, n_class=7)
+    batch = 2
+    _, _, _, dm, params, x = _run(model, batch, seed=9, reuse=False)
+    t = {"x": x.astype(np.float64)}
+    seen = set()
+    for nd in model.nodes:
+        a = nd.attr
+        if nd.op == "concat":
+            if nd.dst == model.out:
+                continue             # caller-owned, checked by the whole-model tests
+            dev = dm.read_tensor(nd.dst, batch).to(torch.float32).cpu().numpy().astype(np.float64).transpose(0, 3, 1, 2)
+            ref = np.concatenate([t[s] for s in nd.src], axis=1)
+            assert np.array_equal(dev, ref), nd.name        # slices written in place: exact
+            seen.add(nd.dst)
+            continue
+        src = t[nd.src]
+        w, b = params[nd.name]
+        if nd.op == "dwconv":
+            ref = oracle.depthwise_conv2d(src, w, b, a["stride"], a["pad"], a["relu"])
+        else:
+            ref = oracle.conv2d(src, w, b, a["stride"], a["pad"], a["relu"])
+        if nd.dst.startswith(("box", "cls")):
+            # written as a channel slice of its head: read the head and cut the slice out
+            k = nd.dst[3:]
+            head = "y" if k == "6" else "head" + k
+            if head == "y":
+                t[nd.dst] = ref
+                continue
+            full = dm.read_tensor(head, batch).to(torch.float32).cpu().numpy().astype(np.float64).transpose(0, 3, 1, 2)
+            n_box = 4 * (3 if k == "1" else 6)
+            got = full[:, :n_box] if nd.dst.startswith("box") else full[:, n_box:]
+        else:
+            got = dm.read_tensor(nd.dst, batch).to(torch.float32).cpu().numpy().astype(np.float64).transpose(0, 3, 1, 2)
+        assert got.shape == ref.shape, nd.name
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL, nd.name
+        t[nd.dst] = got
+    assert seen == {"head1", "head2", "head3", "head4", "head5"}
+
+
+def test_ssd_mobilenet_full_shape_batch2():
+    got, ref, _, _, _, _ = _run(workloads.ssd_mobilenet(), 2, 60, 0)
+    assert got.shape == (2, 6 * (4 + 91))
+    _assert_close(got, ref)
+
+
 def test_resnet50_full_shape_batch2():
     got, ref, _, _, _, _ = _run(workloads.resnet50(), 2)
     assert got.shape == (2, 1000)
@@ -101,7 +150,8 @@ def test_vgg16_full_shape_batch1():
 
 
 @pytest.mark.parametrize("name,batch,pct,which", [("resnet50", 32, 100, 0), ("resnet50", 8, 25, 0),
-                                                  ("googlenet", 32, 50, 1), ("vgg16", 16, 50, 0)])
+                                                  ("googlenet", 32, 50, 1), ("vgg16", 16, 50, 0),
+                                                  ("ssd_mobilenet", 32, 80, 0)])
 def test_serving_batch_sizes_on_sampled_images(name, batch, pct, which):
     model = getattr(workloads, name)()
     images = [0, batch - 1]
