@@ -36,7 +36,7 @@ import sys
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
-MODELS = ("lenet5", "googlenet", "resnet50", "vgg16")
+MODELS = ("lenet5", "googlenet", "resnet50", "ssd_mobilenet", "vgg16")
 BATCHES = (2, 4, 8, 16, 32)
 SPLITS = (20, 40, 50, 60, 80)       # size of the first gpu-let; the second takes the rest
 COPY_BYTES = 64 << 20
