@@ -49,6 +49,29 @@ constexpr int NTHREADS = 256;  // scalar-gather variant: four wavefronts
 constexpr unsigned OOB = 0x80000000u;      // byte offset past every buffer: the load returns zeros
 constexpr int RSRC_FLAGS = 0x00020000;     // raw buffer descriptor, 32-bit data format
 
+// Division of a non-negative int below 2^30 by a fixed positive divisor through one 64-bit
+// multiply: q = (n * mul) >> shift with shift = 30 + ceil(log2 d), mul = floor(2^shift / d) + 1.
+// Exact because n * (mul * d - 2^shift) <= n * d < 2^shift.  The tile setup of these kernels is
+// full of divisions by layer constants; the compiler's general sequence costs about 25
+// instructions each, on the critical path before the first load can be issued.
+struct FastDiv {
+    unsigned mul;
+    int shift;
+};
+
+inline FastDiv make_fastdiv(int d) {
+    int lg = 0;
+    while ((1LL << lg) < d) ++lg;
+    FastDiv f;
+    f.shift = 30 + lg;
+    f.mul = static_cast<unsigned>((1ULL << f.shift) / static_cast<unsigned long long>(d) + 1ULL);
+    return f;
+}
+
+__device__ __forceinline__ int fdiv(int n, const FastDiv f) {
+    return static_cast<int>((static_cast<unsigned long long>(static_cast<unsigned>(n)) * f.mul) >> f.shift);
+}
+
 struct ConvParams {
     const __bf16 *x, *w;
     const float *b;
@@ -67,6 +90,8 @@ struct ConvParams {
     unsigned *cnt;      // split-K scratch: arrival counter per tile (zero between launches)
     // Patch kernel only: output pixels are grouped in column blocks of `tw` pixels.
     int tw, n_cb;       // block width, blocks per output row
+    FastDiv d_pq, d_q, d_p, d_tiles_n, d_split_k, d_c, d_s;   // by P*Q, Q, P, tiles_n, split_k, C, S
+    FastDiv d_tw, d_ncb, d_pwt, d_hp;                         // patch kernel: by tw, n_cb, tw + 2, H + 2*pad
 };
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
@@ -257,8 +282,8 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     // contiguous range of depth slices.
     const int item = tile_of_block(p);
     if (item >= p.n_tiles * p.split_k) return;
-    const int tile = item / p.split_k, ks = item - tile * p.split_k;
-    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int tile = fdiv(item, p.d_split_k), ks = item - tile * p.split_k;
+    const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int lane = threadIdx.x & 63;
@@ -288,9 +313,9 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         for (int i = 0; i < AINS; ++i) {
             const int m = m0 + lrow + PROWS * i;
             if (m < p.M) {
-                const int n = m / (p.P * p.Q);
+                const int n = fdiv(m, p.d_pq);
                 const int pq = m - n * (p.P * p.Q);
-                const int pp = pq / p.Q, qq = pq - pp * p.Q;
+                const int pp = fdiv(pq, p.d_q), qq = pq - pp * p.Q;
                 a_h0[i] = pp * p.stride - p.pad;
                 a_w0[i] = qq * p.stride - p.pad;
                 a_off[i] = (((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C) * 2;
@@ -323,7 +348,7 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         if (!POINTWISE && p.tap_inner) {
             const int rs = p.R * p.S;
             const int cb = k_first / rs, t = k_first - cb * rs;
-            r = t / p.S;
+            r = fdiv(t, p.d_s);
             s = t - r * p.S;
             cblk = cb * BK;
             c = cblk + cc * CHUNK;
@@ -331,9 +356,9 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
             tap = ((r * p.W + s) * p.C + c) * 2;
         } else {
             g = k_first * BK + cc * CHUNK;
-            const int t = g / p.C;
+            const int t = fdiv(g, p.d_c);
             c = g - t * p.C;
-            r = t / p.S;
+            r = fdiv(t, p.d_s);
             s = t - r * p.S;
             tap = ((r * p.W + s) * p.C + c) * 2;
         }
@@ -608,8 +633,8 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
-    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
-    const int tl = tm / p.n_cb, cb = tm - tl * p.n_cb;
+    const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
+    const int tl = fdiv(tm, p.d_ncb), cb = tm - tl * p.n_cb;
     const int l0 = tl * BM, n0 = tn * BN, q0 = cb * p.tw;
     const int NP = p.N * p.P;
     const int Hp = p.H + 2 * p.pad;       // virtual rows per image
@@ -618,11 +643,11 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 
     // Virtual row of output row rho at tap row 0.
     auto vrow = [&](int rho) {
-        const int n = rho / p.P;
+        const int n = fdiv(rho, p.d_p);
         return n * Hp + (rho - n * p.P);
     };
-    const int rho_first = l0 / p.tw;
-    const int rho_last = min(NP - 1, (l0 + BM - 1) / p.tw);
+    const int rho_first = fdiv(l0, p.d_tw);
+    const int rho_last = min(NP - 1, fdiv(l0 + BM - 1, p.d_tw));
     const int v0 = vrow(rho_first);
     const int npos = (vrow(rho_last) + 2 - v0 + 1) * pwt;  // positions this tile needs (<= PMAX)
 
@@ -646,9 +671,9 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             const int cc = (lane & 7) ^ ((pos >> 1) & 7);
             a_off[j] = OOB;
             if (pos < npos) {
-                const int vr = pos / pwt, u = pos - vr * pwt;
+                const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
                 const int v = v0 + vr;
-                const int n = v / Hp;
+                const int n = fdiv(v, p.d_hp);
                 const int h = v - n * Hp - p.pad, w = q0 + u - p.pad;
                 if (n < p.N && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
                     a_off[j] = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C + cc * CHUNK) * 2);
@@ -718,7 +743,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
         int base = 0;
         {
             const int l = l0 + wave * 32 + frow;
-            const int rho = l / p.tw;
+            const int rho = fdiv(l, p.d_tw);
             if (rho < NP) base = (vrow(rho) - v0) * pwt + (l - rho * p.tw);
         }
         // A ring step is 12 depth steps of 16 (three taps x four).  The fragments of depth
@@ -776,7 +801,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     __syncthreads();
     finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, [&](int row) {
         const int l = l0 + row;
-        const int rho = l / p.tw;
+        const int rho = fdiv(l, p.d_tw);
         const int q = q0 + (l - rho * p.tw);
         return (rho < NP && q < p.Q) ? rho * p.Q + q : -1;
     });
@@ -929,6 +954,8 @@ hipError_t launch_tile(ConvParams p, bool vec, int split_k, hipStream_t stream) 
     p.n_tiles = tiles_m * p.tiles_n;
     const int nk = (p.Kg + BK - 1) / BK;
     p.split_k = vec ? split_k : 1;
+    p.d_tiles_n = make_fastdiv(p.tiles_n);
+    p.d_split_k = make_fastdiv(p.split_k);
     p.sps = (nk + p.split_k - 1) / p.split_k;
     p.tiles_per_xcd = (p.n_tiles * p.split_k + 7) / 8;  // work items per die
     const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8));
@@ -981,6 +1008,11 @@ hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream) {
     p.n_tiles = tiles_m * p.tiles_n;
     p.split_k = 1;
     p.tiles_per_xcd = (p.n_tiles + 7) / 8;
+    p.d_tiles_n = make_fastdiv(p.tiles_n);
+    p.d_tw = make_fastdiv(tw);
+    p.d_ncb = make_fastdiv(p.n_cb);
+    p.d_pwt = make_fastdiv(tw + 2);
+    p.d_hp = make_fastdiv(p.H + 2 * p.pad);
     hipLaunchKernelGGL((conv3x3_patch_kernel<BN, 4>), dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)),
                        dim3(8 * 64), 0, stream, p);
     return hipGetLastError();
@@ -1044,6 +1076,12 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.part = ctx.scratch;
     p.cnt = ctx.counters;
     p.tw = p.n_cb = 0;
+    p.d_pq = make_fastdiv(a.P * a.Q);
+    p.d_q = make_fastdiv(a.Q);
+    p.d_p = make_fastdiv(a.P);
+    p.d_c = make_fastdiv(a.C);
+    p.d_s = make_fastdiv(a.S);
+    p.d_tiles_n = p.d_split_k = p.d_tw = p.d_ncb = p.d_pwt = p.d_hp = make_fastdiv(1);
 
     const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
