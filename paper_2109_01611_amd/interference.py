@@ -1,7 +1,7 @@
 """Interference between two gpu-lets sharing a GPU (paper Sec. 3.2 / Fig. 6) and
 the linear model that predicts it (Sec. 4.4 / Fig. 9), measured on one MI355X.
 
-Three measurement steps and one analysis step; all arithmetic of the model
+Three measurement steps and two analysis steps; all arithmetic of the model
 (fit, prediction, error percentiles) runs in ``libgpulet.so``:
 
 1. ``solo`` (run under the profiler, once per counter set): every model at every
@@ -19,6 +19,12 @@ Three measurement steps and one analysis step; all arithmetic of the model
 3. ``sweep samples.json``: for every pair of different models, every pair of
    batch sizes and every split of the GPU, the latency of both alone on their
    masks and while running concurrently.
+
+5. ``study grid.csv features.json report.json out.json`` (no GPU needed): turns
+   the fitted model into the scheduler's slowdown matrix - for every ordered
+   pair of models the largest predicted factor over the profiled batch sizes
+   and splits, minus one - and counts schedulable scenarios with and without
+   it on the measured L(b, p) grid (the paper's gpulet+int against gpulet).
 
 4. ``fit features.json samples.json report.json``: utilisations = counter totals
    over the solo latency, relative to the whole GPU's L2 request rate and HBM
@@ -206,6 +212,53 @@ def fit(features_path, samples_path, report_path, seed=0):
     print(json.dumps(report, indent=1))
 
 
+def slowdown_matrix(feat, coef, latency_ms, names):
+    """F[victim][aggressor]: worst predicted co-run factor minus one over the
+    profiled batch sizes and splits; ``latency_ms[(model, batch, pct)]`` is the
+    solo latency the utilisations are taken over."""
+    from paper_2109_01611_amd import sched
+    F = []
+    for v in names:
+        row = []
+        for a in names:
+            rows = []
+            for pct in SPLITS:
+                for bv in BATCHES:
+                    for ba in BATCHES:
+                        sv = {"model": v, "batch": bv, "pct": pct, "alone_ms": latency_ms[(v, bv, pct)]}
+                        sa = {"model": a, "batch": ba, "pct": 100 - pct, "alone_ms": latency_ms[(a, ba, 100 - pct)]}
+                        l2v, memv = utilisation(feat, sv)
+                        l2a, mema = utilisation(feat, sa)
+                        rows.append([l2v, l2a, memv, mema])
+            row.append(max(0.0, max(sched.interference_predict(coef, rows)) - 1.0))
+        F.append(row)
+    return F
+
+
+def study(grid_csv, features_path, report_path, out_path):
+    from paper_2109_01611_amd import profiler, scenarios
+    rows = []
+    for r in csv.DictReader(open(grid_csv)):
+        rows.append({"model": r["model"], "batch": int(r["batch"]), "pct": int(r["pct"]), "mean_ms": float(r["mean_ms"])})
+    names = [profiler.CONFIGS[n][0]().name for n in profiler.GRID_MODELS]
+    short = dict(zip(names, profiler.GRID_MODELS))
+    feat = json.load(open(features_path))
+    coef = json.load(open(report_path))["coefficients_c1_c5"]
+    lat = {(short[r["model"]], r["batch"], r["pct"]): r["mean_ms"] for r in rows}
+    F = slowdown_matrix(feat, coef, lat, [short[n] for n in names])
+    out = profiler.scheduling_study(rows, names, list(scenarios.SIZES), list(scenarios.BATCHES), slowdown=F)
+    out["slowdown_matrix_victim_by_aggressor"] = {"models": names, "F": F}
+    with open(out_path, "w") as fh:
+        json.dump(out, fh, indent=1)
+    print("slowdown matrix (victim rows, aggressor columns), models %s" % names)
+    for n, row in zip(names, F):
+        print("  %-14s %s" % (n, " ".join("%.3f" % v for v in row)))
+    for g, res in out["grids"].items():
+        print("%s: %s" % (g, "  ".join("%s %d/%d (%.2f GPUs)" % (k, v["schedulable"], v["scenarios"],
+                                                                 v["mean_gpus_used"] or 0.0)
+                                       for k, v in res.items())))
+
+
 def main(argv):
     if len(argv) == 3 and argv[1] == "solo":
         solo(argv[2])
@@ -215,6 +268,8 @@ def main(argv):
         sweep(argv[2])
     elif len(argv) == 5 and argv[1] == "fit":
         fit(argv[2], argv[3], argv[4])
+    elif len(argv) == 6 and argv[1] == "study":
+        study(argv[2], argv[3], argv[4], argv[5])
     else:
         raise SystemExit(__doc__)
 

@@ -130,23 +130,26 @@ def knee_report(table, sizes, batches):
     return {"slo_ms": slo, "sizes": list(sizes), "rate": curve, "batch": best, "curvature": curv, "p_eff": p_eff}
 
 
-def schedulability(tables, slos, n_gpu, rate_sets, sizes, batches, merge=True):
+def schedulability(tables, slos, n_gpu, rate_sets, sizes, batches, merge=True, slowdown=None):
     """Number of rate sets Algorithm 1 can place on ``n_gpu`` GPUs, and the
     mean number of GPUs the schedulable ones occupy."""
     n_ok, gpus = 0, 0
     for rates in rate_sets:
-        ok, entries = sched.elastic_partitioning(sizes, batches, tables, rates, slos, n_gpu, merge=merge)
+        ok, entries = sched.elastic_partitioning(sizes, batches, tables, rates, slos, n_gpu, slowdown=slowdown,
+                                                 merge=merge)
         if ok:
             n_ok += 1
             gpus += len(set(e[0] for e in entries))
     return {"scenarios": len(rate_sets), "schedulable": n_ok, "mean_gpus_used": gpus / n_ok if n_ok else None}
 
 
-def scheduling_study(rows, names, sizes, batches, n_gpus=(1, 2, 4)):
+def scheduling_study(rows, names, sizes, batches, n_gpus=(1, 2, 4), slowdown=None):
     """Feeds the measured tables to the scheduler: knees per model, then the
     scenario grid of Sec. 3.1 at the paper's absolute rates and at rates scaled
     to each model's whole-GPU capacity, with and without spatial partitioning
-    (the latter: the 100% column only, temporal sharing still allowed)."""
+    (the latter: the 100% column only, temporal sharing still allowed).  With a
+    ``slowdown`` matrix [victim][aggressor] the interference-aware variant of
+    the scheduler (the paper's gpulet+int) is counted too."""
     tables = [latency_table(rows, n, sizes, batches) for n in names]
     knees = {n: knee_report(t, sizes, batches) for n, t in zip(names, tables)}
     slos = [knees[n]["slo_ms"] for n in names]
@@ -166,6 +169,9 @@ def scheduling_study(rows, names, sizes, batches, n_gpus=(1, 2, 4)):
                                                    False),
                 "whole_gpus_only": schedulability(whole, slos, n_gpu, rate_sets, [100], list(batches)),
             }
+            if slowdown is not None:
+                out["grids"]["%s/%d_gpu" % (gname, n_gpu)]["gpulets_with_interference"] = schedulability(
+                    tables, slos, n_gpu, rate_sets, list(sizes), list(batches), True, slowdown)
     return out
 
 
