@@ -186,8 +186,29 @@ __device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsig
 // residual loads of all its rows are issued before the first store: layers with
 // a short depth are bound by this loop, and one load-use-store chain per row
 // would leave it waiting for memory latency several times per tile.
+// The bias of the 8 channels a thread handles in finish_tile.  Called at the very start of a
+// kernel, so that the load's latency is hidden behind the whole main loop instead of sitting
+// between the last barrier and the first store.
+struct BiasRegs {
+    float4 lo, hi;
+};
+
+template <int BN, int NTHR>
+__device__ __forceinline__ BiasRegs load_bias(const ConvParams &p, int n0) {
+    constexpr int VPR = BN / 8;
+    const int k = n0 + (threadIdx.x % VPR) * 8;
+    BiasRegs r;
+    r.lo = r.hi = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p.b && p.vec_store && k + 8 <= p.K) {
+        r.lo = *reinterpret_cast<const float4 *>(p.b + k);
+        r.hi = *reinterpret_cast<const float4 *>(p.b + k + 4);
+    }
+    return r;
+}
+
 template <int BM, int BN, int NTHR, typename PixelOf>
-__device__ __forceinline__ void finish_tile(const ConvParams &p, const float *stg, int n0, PixelOf pixel_of) {
+__device__ __forceinline__ void finish_tile(const ConvParams &p, const float *stg, int n0, const BiasRegs &br,
+                                            PixelOf pixel_of) {
     constexpr int LDT = BN + 8;
     constexpr int VPR = BN / 8;            // 8-channel groups per tile row
     constexpr int RSTEP = NTHR / VPR;      // tile rows between two items of a thread
@@ -197,13 +218,7 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
     const int k = n0 + cv * 8;
     if (k >= p.K) return;
     if (p.vec_store && k + 8 <= p.K) {
-        float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (p.b) {
-            const float4 b0 = *reinterpret_cast<const float4 *>(p.b + k);
-            const float4 b1 = *reinterpret_cast<const float4 *>(p.b + k + 4);
-            bias[0] = b0.x; bias[1] = b0.y; bias[2] = b0.z; bias[3] = b0.w;
-            bias[4] = b1.x; bias[5] = b1.y; bias[6] = b1.z; bias[7] = b1.w;
-        }
+        const float bias[8] = {br.lo.x, br.lo.y, br.lo.z, br.lo.w, br.hi.x, br.hi.y, br.hi.z, br.hi.w};
         int m[ITEMS];
         uint4 rr[ITEMS];
 #pragma unroll
@@ -285,6 +300,7 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     const int tile = fdiv(item, p.d_split_k), ks = item - tile * p.split_k;
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
+    const BiasRegs bias_regs = load_bias<BN, (CWM * CWN + NPROD) * 64>(p, n0);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -575,7 +591,7 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         }
         // each thread re-reads only what it wrote itself, in the same iteration order
     }
-    finish_tile<BM, BN, NTHR>(p, stg, n0, [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
+    finish_tile<BM, BN, NTHR>(p, stg, n0, bias_regs, [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
 }
 
 // ---------------------------------------------------------------------------
@@ -636,6 +652,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int tl = fdiv(tm, p.d_ncb), cb = tm - tl * p.n_cb;
     const int l0 = tl * BM, n0 = tn * BN, q0 = cb * p.tw;
+    const BiasRegs bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);
     const int NP = p.N * p.P;
     const int Hp = p.H + 2 * p.pad;       // virtual rows per image
     const int pwt = p.tw + 2;             // patch width: block columns plus the two halo columns
@@ -799,7 +816,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             }
     }
     __syncthreads();
-    finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, [&](int row) {
+    finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, [&](int row) {
         const int l = l0 + row;
         const int rho = fdiv(l, p.d_tw);
         const int q = q0 + (l - rho * p.tw);
