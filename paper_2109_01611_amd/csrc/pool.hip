@@ -46,8 +46,13 @@ __device__ __forceinline__ uint4 pack8(const float f[8]) {
 }
 
 // Window pooling, 8 channels per thread.  AVG = false: max over in-image taps.
-// AVG = true: sum of in-image taps / (k*k).
-template <bool AVG>
+// AVG = true: sum of in-image taps / (k*k).  K > 0 fixes the window size at
+// compile time: all K*K loads are then issued before the first one is used
+// (taps outside the image load a clamped address and are masked afterwards), so
+// a thread pays the memory latency once instead of once per tap; these kernels
+// are small enough for that latency to be most of their run time.  K = 0 is the
+// general loop.
+template <bool AVG, int K>
 __global__ __launch_bounds__(256) void pool_window_vec8(const PoolParams p) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= p.total) return;
@@ -62,17 +67,43 @@ __global__ __launch_bounds__(256) void pool_window_vec8(const PoolParams p) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = AVG ? 0.f : -INFINITY;
     const int h0 = pp * p.stride - p.pad, w0 = q * p.stride - p.pad;
-    for (int r = 0; r < p.k; ++r) {
-        const int h = h0 + r;
-        if ((unsigned)h >= (unsigned)p.H) continue;
-        for (int s = 0; s < p.k; ++s) {
-            const int w = w0 + s;
-            if ((unsigned)w >= (unsigned)p.W) continue;
-            const uint4 v = *reinterpret_cast<const uint4 *>(p.x + (((n * p.H + h) * p.W + w) * p.C + c8 * 8));
-            float f[8];
-            unpack8(v, f);
+    if (K > 0) {
+        uint4 v[K > 0 ? K * K : 1];
+        bool ok[K > 0 ? K * K : 1];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = AVG ? acc[i] + f[i] : fmaxf(acc[i], f[i]);
+        for (int r = 0; r < K; ++r)
+#pragma unroll
+            for (int s = 0; s < K; ++s) {
+                const int h = h0 + r, w = w0 + s;
+                ok[r * K + s] = ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
+                const int hc = min(max(h, 0), p.H - 1), wc = min(max(w, 0), p.W - 1);
+                v[r * K + s] = *reinterpret_cast<const uint4 *>(p.x + (((n * p.H + hc) * p.W + wc) * p.C + c8 * 8));
+            }
+#pragma unroll
+        for (int j = 0; j < K * K; ++j) {
+            float f[8];
+            unpack8(v[j], f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (AVG)
+                    acc[i] += ok[j] ? f[i] : 0.f;
+                else
+                    acc[i] = ok[j] ? fmaxf(acc[i], f[i]) : acc[i];
+            }
+        }
+    } else {
+        for (int r = 0; r < p.k; ++r) {
+            const int h = h0 + r;
+            if ((unsigned)h >= (unsigned)p.H) continue;
+            for (int s = 0; s < p.k; ++s) {
+                const int w = w0 + s;
+                if ((unsigned)w >= (unsigned)p.W) continue;
+                const uint4 v = *reinterpret_cast<const uint4 *>(p.x + (((n * p.H + h) * p.W + w) * p.C + c8 * 8));
+                float f[8];
+                unpack8(v, f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = AVG ? acc[i] + f[i] : fmaxf(acc[i], f[i]);
+            }
         }
     }
     if (AVG) {
@@ -206,10 +237,15 @@ hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P
     const unsigned blocks = static_cast<unsigned>((p.total + 255) / 256);
     const bool avg = mode == GPULET_POOL_AVG;
     if (vec) {
-        if (avg)
-            hipLaunchKernelGGL(pool_window_vec8<true>, dim3(blocks), dim3(256), 0, stream, p);
-        else
-            hipLaunchKernelGGL(pool_window_vec8<false>, dim3(blocks), dim3(256), 0, stream, p);
+#define GPULET_POOL_LAUNCH(K) \
+    do { \
+        if (avg) hipLaunchKernelGGL((pool_window_vec8<true, K>), dim3(blocks), dim3(256), 0, stream, p); \
+        else hipLaunchKernelGGL((pool_window_vec8<false, K>), dim3(blocks), dim3(256), 0, stream, p); \
+    } while (0)
+        if (k == 3) GPULET_POOL_LAUNCH(3);
+        else if (k == 2) GPULET_POOL_LAUNCH(2);
+        else GPULET_POOL_LAUNCH(0);
+#undef GPULET_POOL_LAUNCH
     } else {
         if (avg)
             hipLaunchKernelGGL(pool_window_scalar<true>, dim3(blocks), dim3(256), 0, stream, p);
