@@ -275,6 +275,27 @@ typedef struct gpulet_model_desc {
     const gpulet_layer *layers;
 } gpulet_model_desc;
 
+/*
+ * Number of streams ("lanes", all with the gpu-let's CU mask) the model runner
+ * spreads independent layers over (inception branches, a projection shortcut
+ * next to the main path, detection heads).  Only 1 is accepted at present:
+ * every layer runs on the gpu-let's stream in table order.  A second lane is
+ * implemented (dependencies through buffers, reused ones included, become
+ * event waits; see gpulet_model_schedule) but switched off; GPULET_EINVAL for
+ * any other value.
+ */
+gpulet_status gpulet_set_model_lanes(int lanes);
+
+/*
+ * How the model runner would spread `m` over `lanes` lanes (1..2; host only,
+ * nothing is launched): lane[i] for each of the n_layers layers, and the
+ * cross-lane waits as pairs (wait_from[k] must complete before wait_to[k]
+ * starts).  Layers of one lane run in table order.  GPULET_ENOMEM if there are
+ * more than max_waits pairs (*n_waits then holds the number).
+ */
+gpulet_status gpulet_model_schedule(const gpulet_model_desc *m, int batch, int lanes, int *lane,
+                                    int *wait_from, int *wait_to, int max_waits, int *n_waits);
+
 /* Bytes of workspace gpulet_run_model needs for `batch` images (a multiple of
  * 256).  GPULET_EINVAL if the description is inconsistent (channel or feature
  * counts that do not match the inferred shapes, bad buffer indices, a buffer

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cstddef>
 #include <cstdint>
+#include <vector>
 
 #include "gpulet.h"
 
@@ -21,6 +22,10 @@ gpulet_status hip_fail(hipError_t e);
     } while (0)
 
 constexpr int kMaxMaskWords = 8;
+// Streams of one gpu-let, all with its CU mask.  Independent layers of a model (inception
+// branches, a projection shortcut next to the main path, detection heads) may run on different
+// lanes at once.  Two gpu-lets of two lanes fill the four hardware queues of a process.
+constexpr int kMaxLanes = 2;
 
 }  // namespace gpulet
 
@@ -33,7 +38,9 @@ struct gpulet_partition {
     int n_cu_total;
     int n_words;
     uint32_t mask[gpulet::kMaxMaskWords];
-    hipStream_t stream;
+    hipStream_t stream;     // lane 0: what callers see, where batches are ordered and timed
+    hipStream_t lane[gpulet::kMaxLanes];  // lane[0] == stream
+    std::vector<hipEvent_t> events;       // ordering events between lanes, grown on demand by the model runner
     void *scratch;          // device memory for split-K partial tiles, owned by the gpu-let
     size_t scratch_bytes;
     unsigned *counters;     // device arrival counters for split-K, zero between launches

@@ -32,6 +32,10 @@ struct Step {
     int In, Out, relu, out_fp32;                     // FC
     const void *w;
     const float *b;
+    bool slice;             // CONV writing a channel slice of a wider (concatenated) tensor
+    int lane;               // stream of the gpu-let this layer runs on
+    std::vector<int> wait;  // earlier layers on other lanes this one must wait for
+    bool record;            // a later layer on another lane waits for this one
 };
 
 struct Plan {
@@ -41,6 +45,85 @@ struct Plan {
     size_t ws_bytes = 0;
     int in_buf = 0, out_buf = 0;
 };
+
+// One lane: see gpulet_set_model_lanes.
+std::atomic<int> g_model_lanes{1};
+
+// Data dependencies between layers and their spread over the gpu-let's lanes.
+//
+// Buffers are reused, so besides "reads what an earlier layer wrote" a layer must also wait
+// for every earlier reader and writer of the buffer it overwrites.  Layers that write
+// disjoint channel slices of one concatenated tensor do not depend on one another, but each
+// of them depends on whatever the first of them had to wait for (`guard`).
+//
+// A layer stays on the lane of its most recent dependency when it is the first to continue
+// that lane; otherwise it moves to the lane that has been idle longest.  Dependencies on the
+// same lane are implied by stream order; the others become event waits.
+void assign_lanes(Plan &plan, int n_bufs, int n_lanes) {
+    struct Hazard {
+        std::vector<int> writers, readers, guard;
+        bool sliced = false;
+    };
+    std::vector<Hazard> hz(static_cast<size_t>(n_bufs));
+    std::vector<int> tail(static_cast<size_t>(n_lanes), -1);  // last layer placed on each lane
+    const int n = static_cast<int>(plan.steps.size());
+    for (int i = 0; i < n; ++i) {
+        Step &s = plan.steps[static_cast<size_t>(i)];
+        std::vector<int> deps;
+        auto reads = [&](int buf) {
+            Hazard &h = hz[static_cast<size_t>(buf)];
+            deps.insert(deps.end(), h.writers.begin(), h.writers.end());
+        };
+        reads(s.in_buf);
+        if (s.res_buf >= 0) reads(s.res_buf);
+        Hazard &o = hz[static_cast<size_t>(s.out_buf)];
+        const bool joins = s.slice && o.sliced && o.readers.empty();  // another slice of the same tensor
+        if (joins) {
+            deps.insert(deps.end(), o.guard.begin(), o.guard.end());
+        } else {
+            o.guard = o.readers;
+            o.guard.insert(o.guard.end(), o.writers.begin(), o.writers.end());
+            deps.insert(deps.end(), o.guard.begin(), o.guard.end());
+            o.writers.clear();
+            o.readers.clear();
+            o.sliced = s.slice;
+        }
+        std::sort(deps.begin(), deps.end());
+        deps.erase(std::unique(deps.begin(), deps.end()), deps.end());
+
+        int lane = 0;
+        if (n_lanes > 1 && !deps.empty()) {
+            const int latest = deps.back();
+            const int ll = plan.steps[static_cast<size_t>(latest)].lane;
+            if (tail[static_cast<size_t>(ll)] == latest) {
+                lane = ll;
+            } else {
+                for (int l = 1; l < n_lanes; ++l)
+                    if (tail[static_cast<size_t>(l)] < tail[static_cast<size_t>(lane)]) lane = l;
+            }
+        }
+        s.lane = lane;
+        s.wait.clear();
+        for (int d : deps) {
+            Step &ds = plan.steps[static_cast<size_t>(d)];
+            // a same-lane dependency, and anything older than it on another lane's chain, is
+            // already ordered; keep only the newest dependency of every other lane
+            if (ds.lane == lane) continue;
+            bool newer = false;
+            for (int e : deps)
+                if (e > d && plan.steps[static_cast<size_t>(e)].lane == ds.lane) newer = true;
+            if (newer) continue;
+            s.wait.push_back(d);
+            ds.record = true;
+        }
+        tail[static_cast<size_t>(lane)] = i;
+
+        // this layer now reads and writes
+        hz[static_cast<size_t>(s.in_buf)].readers.push_back(i);
+        if (s.res_buf >= 0) hz[static_cast<size_t>(s.res_buf)].readers.push_back(i);
+        o.writers.push_back(i);
+    }
+}
 
 size_t round_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -76,6 +159,9 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         s.res_buf = -1;
         s.w = L.w;
         s.b = L.b;
+        s.slice = false;
+        s.lane = 0;
+        s.record = false;
         int oc = 0, oh = 0, ow = 0, oelem = 2;
         if (L.op == GPULET_OP_CONV) {
             if (L.C != src.C || !L.w) return GPULET_EINVAL;
@@ -88,6 +174,7 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
             a.Q = out_extent(src.W, L.S, L.stride, L.pad);
             a.y_ch_stride = L.out_ch_total > 0 ? L.out_ch_total : L.K;
             a.y_ch_offset = L.out_ch_total > 0 ? L.out_ch_offset : 0;
+            s.slice = L.out_ch_total > 0;
             // Pointers are filled in at run time; validate the rest with stand-ins.
             ConvArgs chk = a;
             chk.x = chk.w = chk.y = &chk;
@@ -131,6 +218,7 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         plan.steps.push_back(s);
     }
     if (!plan.bufs[static_cast<size_t>(m->out_buf)].written) return GPULET_EINVAL;
+    assign_lanes(plan, m->n_bufs, g_model_lanes.load());
 
     plan.offset.assign(static_cast<size_t>(m->n_bufs), static_cast<size_t>(-1));
     size_t off = 0;
@@ -155,10 +243,53 @@ struct Bound {
     }
 };
 
-// Enqueues every layer of one batch on `stream`; no host synchronisation.
-hipError_t enqueue(const Bound &bd, const LaunchCtx &ctx, hipStream_t stream) {
-    for (const Step &s : bd.plan->steps) {
-        hipError_t e;
+// Event number `idx` of the gpu-let's pool (created on first use, never timed).
+hipError_t pool_event(gpulet_partition *p, size_t idx, hipEvent_t *ev) {
+    while (p->events.size() <= idx) {
+        hipEvent_t e = nullptr;
+        hipError_t st = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+        if (st != hipSuccess) return st;
+        p->events.push_back(e);
+    }
+    *ev = p->events[idx];
+    return hipSuccess;
+}
+
+// Enqueues every layer of one batch on the gpu-let's lanes; no host synchronisation.  Lane 0
+// is the gpu-let's stream: the batch starts after everything enqueued there before and is
+// complete, for anything enqueued there afterwards, when this returns.
+hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
+    const std::vector<Step> &steps = bd.plan->steps;
+    bool lane_used[kMaxLanes] = {false};
+    for (const Step &s : steps) lane_used[s.lane] = true;
+    // events 0 .. kMaxLanes-1: fork and joins; kMaxLanes + i: layer i
+    hipEvent_t fork = nullptr;
+    hipError_t e = hipSuccess;
+    for (int l = 1; l < kMaxLanes; ++l) {
+        if (!lane_used[l]) continue;
+        if (!fork) {
+            e = pool_event(p, 0, &fork);
+            if (e == hipSuccess) e = hipEventRecord(fork, p->lane[0]);
+            if (e != hipSuccess) return e;
+        }
+        e = hipStreamWaitEvent(p->lane[l], fork, 0);
+        if (e != hipSuccess) return e;
+    }
+    LaunchCtx ctx0 = partition_ctx(p), ctx_other = ctx0;
+    ctx_other.scratch = nullptr;  // the split-K scratch is not shared between concurrent layers
+    ctx_other.scratch_bytes = 0;
+    ctx_other.counters = nullptr;
+    ctx_other.n_counters = 0;
+    for (size_t i = 0; i < steps.size(); ++i) {
+        const Step &s = steps[i];
+        hipStream_t stream = p->lane[s.lane];
+        const LaunchCtx &ctx = s.lane == 0 ? ctx0 : ctx_other;
+        for (int d : s.wait) {
+            hipEvent_t ev;
+            e = pool_event(p, kMaxLanes + static_cast<size_t>(d), &ev);
+            if (e == hipSuccess) e = hipStreamWaitEvent(stream, ev, 0);
+            if (e != hipSuccess) return e;
+        }
         if (s.op == GPULET_OP_CONV) {
             ConvArgs a = s.conv;
             a.x = bd.ptr(s.in_buf);
@@ -175,6 +306,20 @@ hipError_t enqueue(const Bound &bd, const LaunchCtx &ctx, hipStream_t stream) {
             e = launch_fc(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.In, s.Out, s.relu, s.out_fp32,
                           stream);
         }
+        if (e != hipSuccess) return e;
+        if (s.record) {
+            hipEvent_t ev;
+            e = pool_event(p, kMaxLanes + i, &ev);
+            if (e == hipSuccess) e = hipEventRecord(ev, stream);
+            if (e != hipSuccess) return e;
+        }
+    }
+    for (int l = 1; l < kMaxLanes; ++l) {
+        if (!lane_used[l]) continue;
+        hipEvent_t join;
+        e = pool_event(p, static_cast<size_t>(l), &join);
+        if (e == hipSuccess) e = hipEventRecord(join, p->lane[l]);
+        if (e == hipSuccess) e = hipStreamWaitEvent(p->lane[0], join, 0);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -211,7 +356,7 @@ struct EventPair {
 // One timed batch, waited for: returns its elapsed milliseconds.
 hipError_t timed_batch(const Bound &bd, gpulet_partition *p, int batch, EventPair &ev, float *ms) {
     hipError_t e = hipEventRecord(ev.a, p->stream);
-    if (e == hipSuccess) e = enqueue(bd, partition_ctx(p), p->stream);
+    if (e == hipSuccess) e = enqueue(bd, p);
     if (e == hipSuccess) e = hipEventRecord(ev.b, p->stream);
     if (e == hipSuccess) e = hipEventSynchronize(ev.b);
     if (e == hipSuccess) e = hipEventElapsedTime(ms, ev.a, ev.b);
@@ -223,6 +368,39 @@ hipError_t timed_batch(const Bound &bd, gpulet_partition *p, int batch, EventPai
 }
 
 }  // namespace
+
+extern "C" gpulet_status gpulet_set_model_lanes(int lanes) {
+    // Running layers on a second lane is switched off: a run that replayed a two-lane forward
+    // pass from a captured graph on a masked stream stopped making progress, and the cause has
+    // not been established.  The dependency analysis stays available through
+    // gpulet_model_schedule.
+    if (lanes != 1) return GPULET_EINVAL;
+    g_model_lanes.store(1);
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_model_schedule(const gpulet_model_desc *m, int batch, int lanes, int *lane,
+                                               int *wait_from, int *wait_to, int max_waits, int *n_waits) {
+    if (!lane || !n_waits || max_waits < 0 || (max_waits > 0 && (!wait_from || !wait_to))) return GPULET_EINVAL;
+    if (lanes < 1 || lanes > kMaxLanes) return GPULET_EINVAL;
+    Plan plan;
+    gpulet_status st = build_plan(m, batch, plan);
+    if (st != GPULET_OK) return st;
+    assign_lanes(plan, m->n_bufs, lanes);
+    int n = 0;
+    for (size_t i = 0; i < plan.steps.size(); ++i) {
+        lane[i] = plan.steps[i].lane;
+        for (int d : plan.steps[i].wait) {
+            if (n < max_waits) {
+                wait_from[n] = d;
+                wait_to[n] = static_cast<int>(i);
+            }
+            ++n;
+        }
+    }
+    *n_waits = n;
+    return n > max_waits ? GPULET_ENOMEM : GPULET_OK;
+}
 
 extern "C" gpulet_status gpulet_model_workspace_bytes(const gpulet_model_desc *m, int batch,
                                                       size_t *bytes) {
@@ -267,7 +445,7 @@ extern "C" gpulet_status gpulet_run_model(const gpulet_model_desc *m, int batch,
         GPULET_HIP(timed_batch(bd, p, batch, ev, latency_ms));
         return GPULET_OK;
     }
-    GPULET_HIP(enqueue(bd, partition_ctx(p), p->stream));
+    GPULET_HIP(enqueue(bd, p));
     p->batches_run.fetch_add(1);
     p->images_run.fetch_add(static_cast<uint64_t>(batch));
     return GPULET_OK;
@@ -287,7 +465,7 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
     const Bound bd{&plan, in, out, static_cast<char *>(workspace)};
 
     for (int i = 0; i < warmup; ++i) {
-        GPULET_HIP(enqueue(bd, partition_ctx(p), p->stream));
+        GPULET_HIP(enqueue(bd, p));
         p->batches_run.fetch_add(1);
         p->images_run.fetch_add(static_cast<uint64_t>(batch));
     }
@@ -298,7 +476,7 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
     for (int i = 0; i < iters; ++i) {
         EventPair &e = ev[static_cast<size_t>(i)];
         GPULET_HIP(hipEventRecord(e.a, p->stream));
-        GPULET_HIP(enqueue(bd, partition_ctx(p), p->stream));
+        GPULET_HIP(enqueue(bd, p));
         GPULET_HIP(hipEventRecord(e.b, p->stream));
         p->batches_run.fetch_add(1);
         p->images_run.fetch_add(static_cast<uint64_t>(batch));
@@ -361,7 +539,7 @@ extern "C" gpulet_status gpulet_model_graph_create(const gpulet_model_desc *m, i
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
     GPULET_HIP(hipStreamBeginCapture(p->stream, hipStreamCaptureModeThreadLocal));
-    hipError_t e = enqueue(bd, partition_ctx(p), p->stream);
+    hipError_t e = enqueue(bd, p);
     hipError_t e2 = hipStreamEndCapture(p->stream, &graph);  // always end the capture
     if (e == hipSuccess) e = e2;
     if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);

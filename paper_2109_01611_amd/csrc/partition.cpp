@@ -119,7 +119,12 @@ extern "C" gpulet_status gpulet_partition_create(int device, int pct, int which,
     GPULET_HIP(hipGetDevice(&prev));
     GPULET_HIP(hipSetDevice(device));
     hipStream_t stream = nullptr;
+    hipStream_t extra[kMaxLanes] = {nullptr};
     hipError_t e = hipExtStreamCreateWithCUMask(&stream, static_cast<uint32_t>(n_words), words);
+    // The second lane is switched off (gpulet_set_model_lanes), so its stream is not created.
+    constexpr bool kCreateLanes = false;
+    for (int l = 1; l < kMaxLanes && e == hipSuccess && kCreateLanes; ++l)
+        e = hipExtStreamCreateWithCUMask(&extra[l], static_cast<uint32_t>(n_words), words);
     // Split-K scratch of the gpu-let: partial tiles and zeroed arrival counters.
     constexpr size_t kScratchBytes = 64u << 20;
     constexpr int kCounters = 4096;
@@ -133,6 +138,8 @@ extern "C" gpulet_status gpulet_partition_create(int device, int pct, int which,
         if (scratch) (void)hipFree(scratch);
         if (counters) (void)hipFree(counters);
         if (stream) (void)hipStreamDestroy(stream);
+        for (int l = 1; l < kMaxLanes; ++l)
+            if (extra[l]) (void)hipStreamDestroy(extra[l]);
         (void)hipSetDevice(prev);
         return hip_fail(e);
     }
@@ -147,6 +154,8 @@ extern "C" gpulet_status gpulet_partition_create(int device, int pct, int which,
     p->n_words = n_words;
     std::memcpy(p->mask, words, sizeof words);
     p->stream = stream;
+    p->lane[0] = stream;
+    for (int l = 1; l < kMaxLanes; ++l) p->lane[l] = extra[l];
     p->scratch = scratch;
     p->scratch_bytes = kScratchBytes;
     p->counters = counters;
@@ -171,6 +180,13 @@ extern "C" gpulet_status gpulet_partition_destroy(gpulet_partition *p) {
         stream = p->stream;
     }
     hipError_t e1 = hipStreamSynchronize(stream);
+    for (int l = 1; l < kMaxLanes; ++l) {
+        if (!p->lane[l]) continue;
+        hipError_t el = hipStreamSynchronize(p->lane[l]);
+        if (e1 == hipSuccess) e1 = el;
+        (void)hipStreamDestroy(p->lane[l]);
+    }
+    for (hipEvent_t ev : p->events) (void)hipEventDestroy(ev);
     hipError_t e2 = hipStreamDestroy(stream);
     (void)hipFree(p->scratch);
     (void)hipFree(p->counters);

@@ -98,6 +98,8 @@ def _load():
         "gpulet_depthwise_conv2d_fwd": ([P, P, P, P] + [I] * 9 + [P], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
+        "gpulet_set_model_lanes": ([I], c_int32),
+        "gpulet_model_schedule": ([POINTER(ModelDesc), I, I, IP, IP, IP, I, IP], c_int32),
         "gpulet_model_workspace_bytes": ([POINTER(ModelDesc), I, POINTER(c_size_t)], c_int32),
         "gpulet_model_buffer_info": ([POINTER(ModelDesc), I, I, POINTER(I), POINTER(I), POINTER(I),
                                       POINTER(I), POINTER(c_size_t)], c_int32),
@@ -243,6 +245,20 @@ def time_conv2d(x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual=Non
                                   int(relu), ptr(residual), y_ch_stride, y_ch_offset, stream, warmup,
                                   iters, byref(ms)), "gpulet_time_conv2d")
     return ms.value
+
+
+def set_model_lanes(lanes):
+    _check(lib.gpulet_set_model_lanes(lanes), "gpulet_set_model_lanes")
+
+
+def model_schedule(desc, batch, lanes=2):
+    """-> (lane per layer, [(from, to)] cross-lane waits) for ``lanes`` lanes (host-only analysis)."""
+    n = desc.n_layers
+    lane = (c_int * n)()
+    cap = 4 * n + 8
+    wf, wt, nw = (c_int * cap)(), (c_int * cap)(), c_int()
+    _check(lib.gpulet_model_schedule(byref(desc), batch, lanes, lane, wf, wt, cap, byref(nw)), "gpulet_model_schedule")
+    return list(lane), [(wf[i], wt[i]) for i in range(nw.value)]
 
 
 def model_workspace_bytes(desc, batch):

@@ -176,6 +176,52 @@ def test_batch_size_does_not_change_an_images_result():
     assert oracle.rel_err(c[:2], a[:2])[1] <= MODEL_TOL
 
 
+@pytest.mark.parametrize("model", [
+    workloads.googlenet(width_div=2, in_hw=96, n_class=20),
+    workloads.ssd_mobilenet(width_div=4, in_hw=128, n_class=5),
+    workloads.resnet50(width_div=4, in_hw=64, n_class=20, blocks=(2, 2, 2, 2)),
+], ids=lambda m: m.name)
+@pytest.mark.skip(reason="two-lane execution is switched off in the library: this test stopped making progress once "
+                         "(eager batches, then a captured two-lane graph on a masked stream) and the cause is not "
+                         "established; gpulet_set_model_lanes rejects 2 until it is")
+def test_two_lanes_give_the_same_bits_as_one(model):
+    # independent layers on a second stream of the gpu-let: same results, batch after batch
+    # (buffers are reused, so a missing ordering edge shows as a changed output)
+    params = workloads.parameters(model, 3)
+    x = workloads.batch_input(model, 6, 3)
+    dm = lowering.DeviceModel(model, params, DEV)
+    xd = dm.input_to_device(x)
+    outs = {}
+    try:
+        for lanes in (1, 2):
+            gpulet.set_model_lanes(lanes)
+            lane, _ = gpulet.model_schedule(dm.desc, 6)
+            assert (1 in lane) == (lanes == 2)
+            with gpulet.Partition(0, 40, 0) as p:
+                runs = []
+                for _ in range(4):
+                    y, _ = dm.run(p, xd)
+                    runs.append(y.clone())
+                ws, n = dm.workspace(6)
+                y = dm.alloc_output(6)
+                lat, _ = gpulet.profile_model(dm.desc, 6, p, xd, y, ws, n, warmup=2, iters=20, sync_each=False)
+                p.sync()
+                runs.append(y.clone())
+                with gpulet.ModelGraph(dm.desc, 6, p, xd, y, ws, n) as g:
+                    for _ in range(3):
+                        y.zero_()
+                        g.launch()
+                        p.sync()
+                        runs.append(y.clone())
+            assert all(torch.equal(r, runs[0]) for r in runs)
+            outs[lanes] = runs[0]
+    finally:
+        gpulet.set_model_lanes(2)
+    assert torch.equal(outs[1], outs[2])
+    ref = oracle.run_model(model, params, x).reshape(6, -1)
+    _assert_close(outs[2].to(torch.float32).cpu().numpy().astype(np.float64).reshape(6, -1), ref)
+
+
 def test_corun_two_gpulets_gives_same_results_and_counts():
     ma, mb = workloads.resnet50(width_div=4, in_hw=64, n_class=20), workloads.googlenet(width_div=4, in_hw=64, n_class=20)
     pa_, pb_ = workloads.parameters(ma, 8), workloads.parameters(mb, 8)
