@@ -239,18 +239,25 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
             const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
             const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
             float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            const unsigned ru[4] = {rr[i].x, rr[i].y, rr[i].z, rr[i].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += bias[e];
+            if (p.res) {
+                // a bf16 is the upper half of the fp32 with the same value
+                const unsigned ru[4] = {rr[i].x, rr[i].y, rr[i].z, rr[i].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] += __uint_as_float(ru[e] << 16);
+                    v[2 * e + 1] += __uint_as_float(ru[e] & 0xFFFF0000u);
+                }
+            }
+            if (p.relu) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+            }
             unsigned pk[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                // a bf16 is the upper half of the fp32 with the same value; +0 where there is no residual
-                float a = v[2 * e] + bias[2 * e] + __uint_as_float(ru[e] << 16);
-                float b = v[2 * e + 1] + bias[2 * e + 1] + __uint_as_float(ru[e] & 0xFFFF0000u);
-                if (p.relu) {
-                    a = a > 0.f ? a : 0.f;
-                    b = b > 0.f ? b : 0.f;
-                }
-                const __bf16 ha = static_cast<__bf16>(a), hb = static_cast<__bf16>(b);
+                const __bf16 ha = static_cast<__bf16>(v[2 * e]), hb = static_cast<__bf16>(v[2 * e + 1]);
                 pk[e] = static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&ha)) |
                         (static_cast<unsigned>(*reinterpret_cast<const unsigned short *>(&hb)) << 16);
             }
