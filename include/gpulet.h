@@ -168,12 +168,15 @@ gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b,
  * process onto one workgroup tile (pixels x channels):
  *   0: 128x128  1: 128x64  2: 64x128  3: 64x64  4: 128x32  5: 32x128  6: 256x128
  *   7: 128x64 with the input patch of a tile resident in LDS (3x3 filters,
- *      stride 1, pad 1, C a multiple of 64; other shapes run tile 1 instead),
+ *      stride 1, pad 1, C a multiple of 64; other shapes run tile 1 instead)
+ *   8: 64x128 walked by workgroups that keep their weights in LDS and stream
+ *      over many pixel tiles (1x1 filters, C of 64 or 128; other shapes run
+ *      tile 2 instead),
  * or -1 to return to automatic selection, which picks the tile whose busiest
  * CU has the least work for the launch's shape and the stream's CU count.
- * Results do not depend on the tile.  GPULET_EINVAL outside -1..7.
+ * Results do not depend on the tile.  GPULET_EINVAL outside -1..8.
  */
-enum { GPULET_CONV_TILES = 8 };
+enum { GPULET_CONV_TILES = 9 };
 gpulet_status gpulet_set_conv_tile(int tile);
 
 /*

@@ -21,3 +21,15 @@ def test_benchmark_layer_full_size_on_gpulets(pct, which):
         got, _ = gpu_conv(p, x, w, b, 1, 1, True)
     whole, per_img = oracle.rel_err(got, ref)
     assert max(whole, per_img) <= LAYER_TOL, (whole, per_img)
+
+
+@pytest.mark.parametrize("pct,which", [(20, 0), (60, 1)])
+def test_streaming_1x1_kernel_on_small_gpulets(pct, which):
+    # few CUs: every workgroup of the streaming kernel walks over many pixel tiles
+    x, w, b = conv_tensors(19, 6, 64, 40, 40, 128, 1)
+    ref = oracle.conv2d(x, w, b, 1, 0, True)
+    with gpulet.Partition(0, pct, which) as small:
+        got, _ = gpu_conv(small, x, w, b, 1, 0, True)
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+        got, _ = gpu_conv(small, x, w, b, 1, 0, True, tile=8)
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL

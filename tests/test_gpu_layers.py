@@ -47,7 +47,7 @@ def test_conv_parity_every_tile(part, case):
     x, w, b = conv_tensors(11, N, C, H, W, K, R)
     ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
     first = None
-    for tile in range(-1, 8):
+    for tile in range(-1, 9):
         got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
         whole, per_img = oracle.rel_err(got, ref)
         assert max(whole, per_img) <= LAYER_TOL, (tile, whole, per_img)
@@ -87,6 +87,36 @@ def test_conv_patch_kernel_parity(part, case):
     ref = oracle.conv2d(x, w, b, 1, 1, False)
     assert oracle.rel_err(got[:, 8:8 + K], ref)[1] <= LAYER_TOL
     assert np.all(got[:, :8] == -512.0) and np.all(got[:, 8 + K:] == -512.0)
+
+
+# N, C, H, W, K, stride: 1x1 filters with 64 or 128 input channels -> the streaming kernel (tile 8)
+STREAM_CASES = [
+    (1, 64, 5, 5, 24, 1),          # a single ragged tile
+    (2, 64, 19, 17, 136, 1),       # M = 646: eleven tiles, last one ragged; two channel tiles, second ragged
+    (3, 128, 16, 16, 64, 1),       # two depth slices
+    (2, 128, 21, 21, 264, 2),      # strided 1x1 (projection shortcut), three channel tiles
+    (8, 64, 56, 56, 256, 1),       # many tiles per workgroup
+    (4, 128, 28, 28, 512, 1),
+]
+
+
+@pytest.mark.parametrize("case", STREAM_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_streaming_1x1_kernel_parity(part, case):
+    N, C, H, W, K, stride = case
+    x, w, b = conv_tensors(18, N, C, H, W, K, 1)
+    P, Q = (H - 1) // stride + 1, (W - 1) // stride + 1
+    res = inputs.tensor(18, "res_stream", (N, K, P, Q), "normal")
+    ref = oracle.conv2d(x, w, b, stride, 0, True, residual=res)
+    got, raw = gpu_conv(part, x, w, b, stride, 0, True, residual=res, tile=8)
+    assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+    _, one_tile_each = gpu_conv(part, x, w, b, stride, 0, True, residual=res, tile=2)
+    assert torch.equal(raw, one_tile_each)      # same depth order as the other kernels
+    _, again = gpu_conv(part, x, w, b, stride, 0, True, residual=res, tile=8)
+    assert torch.equal(raw, again)
+    got, _ = gpu_conv(part, x, w, None, stride, 0, False, ch_total=K + 24, ch_offset=16, tile=8)
+    ref = oracle.conv2d(x, w, None, stride, 0, False)
+    assert oracle.rel_err(got[:, 16:16 + K], ref)[1] <= LAYER_TOL
+    assert np.all(got[:, :16] == -512.0) and np.all(got[:, 16 + K:] == -512.0)
 
 
 @pytest.mark.parametrize("case", [(32, 256, 14, 14, 256, 3, 1, 1), (2, 512, 7, 7, 512, 3, 1, 1),
