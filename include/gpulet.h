@@ -59,10 +59,17 @@ int gpulet_last_hip_error(void);
  * units in n_xcd equal dies.  Pure integer host code, no GPU needed.
  *
  * The paper gives sizes in percent; a CU mask needs a whole number of CUs.
- * The share is rounded per die so that every die contributes the same count:
- *   share(pct) = (pct * cus_per_xcd + 50) / 100   (integer division),
- * clamped to 1 .. cus_per_xcd - 1 for pct < 100 (share(100) = cus_per_xcd), so
- * a Split always leaves the partner at least one CU per die.  which = 0 takes
+ * Every die contributes the same count (workgroups are dealt round-robin to
+ * the dies), and that count is a multiple of the 4 shader engines of a die
+ * (workgroups are dealt round-robin to those as well, so the engine with the
+ * fewest CUs in the mask sets the pace; CU c of a die is in engine c % 4):
+ *   share(pct) = 4 * ((pct * cus_per_xcd + 200) / 400)   (integer division),
+ * clamped to 4 .. cus_per_xcd - 4 for pct < 100 (share(100) = cus_per_xcd), so
+ * a Split always leaves the partner a balanced share.  On 32 CUs per die the
+ * paper's sizes 20/40/50/60/80 become 8/12/16/20/24 CUs per die (25, 37.5,
+ * 50, 62.5, 75 % of the device).  Dies whose CU count is not a multiple of 4,
+ * or below 8, round to whole CUs instead: (pct * cus_per_xcd + 50) / 100,
+ * clamped to 1 .. cus_per_xcd - 1.  which = 0 takes
  * the first share(pct) CUs of every die; which = 1 is the partner produced by
  * Split: it takes what a which = 0 gpu-let of (100 - pct) leaves, i.e.
  * cus_per_xcd - share(100 - pct) CUs per die, so the two are disjoint and

@@ -5,12 +5,27 @@
 
 namespace {
 
-// CUs per die of a which = 0 gpu-let of `pct` percent: round half up, but a
-// gpu-let smaller than the whole GPU never takes a die's last CU and never
-// gets none, so its Split partner always exists.
+// Shader engines per die.  CU c of a die sits in shader engine c % kEngines, and the hardware
+// deals workgroups round-robin to the engines of a die whatever the mask, so the engine with the
+// fewest CUs inside the mask sets the pace: a share that is not a multiple of kEngines runs no
+// faster than the next lower multiple (measured on MI355X: 26 CUs per die slower than 24, 13
+// slower than 12, 6 as fast as 4).
+constexpr int kEngines = 4;
+
+// CUs per die of a which = 0 gpu-let of `pct` percent: the nearest multiple of kEngines (half
+// rounds up), kept inside kEngines .. cpx - kEngines for a gpu-let smaller than the whole GPU so
+// that its Split partner always exists and is balanced too.  Dies whose CU count is not a
+// multiple of kEngines (or too small to split that way) fall back to rounding to whole CUs,
+// 1 .. cpx - 1.
 int share0(int pct, int cpx) {
     if (pct >= 100) return cpx;
     if (pct <= 0) return 0;
+    if (cpx % kEngines == 0 && cpx >= 2 * kEngines) {
+        int n = kEngines * ((pct * cpx + 50 * kEngines) / (100 * kEngines));
+        if (n > cpx - kEngines) n = cpx - kEngines;
+        if (n < kEngines) n = kEngines;
+        return n;
+    }
     int n = (pct * cpx + 50) / 100;
     if (n > cpx - 1) n = cpx - 1;
     if (n < 1) n = 1;

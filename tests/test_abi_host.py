@@ -40,8 +40,8 @@ def _popcount(words):
     return sum(bin(w).count("1") for w in words)
 
 
-@pytest.mark.parametrize("pct,n_cu", [(20, 48), (25, 64), (40, 104), (50, 128), (60, 152), (80, 208),
-                                      (100, 256), (1, 8), (99, 248)])
+@pytest.mark.parametrize("pct,n_cu", [(20, 64), (25, 64), (40, 96), (50, 128), (60, 160), (80, 192),
+                                      (100, 256), (1, 32), (99, 224), (12, 32), (13, 32), (19, 64)])
 def test_mask_sizes_on_256_cus(pct, n_cu):
     words, n = gpulet.mask_for_pct(256, 8, pct, 0)
     assert len(words) == 8 and n == n_cu and _popcount(words) == n_cu
@@ -61,6 +61,9 @@ def test_split_gives_disjoint_cover(pct):
     bits = [i for i in range(256) if (a[i // 32] >> (i % 32)) & 1]
     per_die = [sum(1 for i in bits if i % 8 == d) for d in range(8)]
     assert len(set(per_die)) == 1
+    # ... and CU c of a die is in shader engine c % 4: every engine contributes the same count
+    per_engine = [sum(1 for i in bits if i % 8 == 0 and (i // 8) % 4 == e) for e in range(4)]
+    assert len(set(per_engine)) == 1 and per_engine[0] >= 1
 
 
 def test_two_partitions_never_overlap_when_sizes_fit():
@@ -76,6 +79,11 @@ def test_mask_other_geometries_and_errors():
     assert n == 16 and words == [0xFFFF, 0]
     words, n = gpulet.mask_for_pct(64, 1, 75, 1)
     assert n == 48 and words == [0xFFFF0000, 0xFFFFFFFF]
+    # dies that cannot be split by shader engine round to whole CUs, at least one on each side
+    assert gpulet.mask_for_pct(6, 1, 50, 0) == ([0b000111], 3)
+    assert gpulet.mask_for_pct(6, 1, 1, 0) == ([0b000001], 1)
+    assert gpulet.mask_for_pct(6, 1, 1, 1) == ([0b000001 << 5], 1)
+    assert gpulet.mask_for_pct(30, 3, 40, 0)[1] == 12
     for args in [(256, 8, 0, 0), (256, 8, 101, 0), (256, 8, 50, 2), (255, 8, 50, 0), (0, 8, 50, 0), (256, 0, 50, 0)]:
         with pytest.raises(gpulet.GpuletError) as e:
             gpulet.mask_for_pct(*args)

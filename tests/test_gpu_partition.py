@@ -44,10 +44,13 @@ def test_split_partners_run_on_disjoint_cus(pct):
             per_die = collections.Counter(x for x, _ in pl)
             assert sorted(per_die) == list(range(8))
             assert set(per_die.values()) == {part.n_cu // 8}
+            # ... and the same number in every shader engine of every die
+            per_engine = collections.Counter((x, ph >> 5) for x, ph in pl)
+            assert len(per_engine) == 32 and set(per_engine.values()) == {part.n_cu // 32}
 
 
 def test_sizes_and_full_gpu():
-    want = {20: 48, 25: 64, 40: 104, 50: 128, 60: 152, 80: 208, 100: 256}
+    want = {20: 64, 25: 64, 40: 96, 50: 128, 60: 160, 80: 192, 100: 256}
     for pct, n_cu in want.items():
         with gpulet.Partition(0, pct, 0) as p:
             assert (p.pct, p.which, p.n_cu, p.device) == (pct, 0, n_cu, 0)
