@@ -178,12 +178,19 @@ gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b,
  *      stride 1, pad 1, C a multiple of 64; other shapes run tile 1 instead)
  *   8: 64x128 walked by workgroups that keep their weights in LDS and stream
  *      over many pixel tiles (1x1 filters, C of 64 or 128; other shapes run
- *      tile 2 instead),
+ *      tile 2 instead)
+ *   9: 4 rows x 32 columns of one image by 32 or 64 channels, for inputs of at
+ *      most 4 channels (image stems): the tile's input patch sits in LDS as
+ *      4-channel pixels and filter rows are padded to 16 or 32 elements
+ *      (filters of 3, 5 or 7 rows and at most 8 columns; other shapes run
+ *      tile 1 instead),
  * or -1 to return to automatic selection, which picks the tile whose busiest
- * CU has the least work for the launch's shape and the stream's CU count.
- * Results do not depend on the tile.  GPULET_EINVAL outside -1..8.
+ * CU has the least work for the launch's shape and the stream's CU count, and
+ * tile 9 wherever it applies.  Tiles 0..8 give bit-identical results; tile 9
+ * groups the same ascending sum differently (zero padding inside the depth),
+ * so it agrees with them to rounding.  GPULET_EINVAL outside -1..9.
  */
-enum { GPULET_CONV_TILES = 9 };
+enum { GPULET_CONV_TILES = 10 };
 gpulet_status gpulet_set_conv_tile(int tile);
 
 /*
