@@ -45,13 +45,17 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
-// ReLU switch without a branch and without the NaN-quieting pass of fmaxf: as signed integers
-// every negative float (and -0) is below zero, so max(bits, 0) is max(x, +0); with the limit at
-// INT_MIN the operation is the identity.
-__device__ __forceinline__ int relu_limit(int relu) { return relu ? 0 : static_cast<int>(0x80000000u); }
-__device__ __forceinline__ float relu_or_pass(float x, int limit) {
-    const int b = __float_as_int(x);
-    return __int_as_float(b > limit ? b : limit);
+typedef __attribute__((ext_vector_type(2))) short s16x2;
+
+// ReLU on a pair of bf16 in one dword, switched without a branch: as signed 16-bit integers
+// every negative bf16 (and -0) is below zero, so max(bits, 0) is max(x, +0); with the limit at
+// 0x8000 the operation is the identity.  Rounding to bf16 keeps the sign, so clamping after the
+// rounding gives the same bits as clamping the fp32 value before it.
+__device__ __forceinline__ unsigned relu_limit(int relu) { return relu ? 0u : 0x80008000u; }
+__device__ __forceinline__ unsigned relu_or_pass(unsigned pair, unsigned limit) {
+    const s16x2 r = __builtin_elementwise_max(*reinterpret_cast<const s16x2 *>(&pair),
+                                              *reinterpret_cast<const s16x2 *>(&limit));
+    return *reinterpret_cast<const unsigned *>(&r);
 }
 // Two floats -> two bf16 (round to nearest even) in one dword, the first in the low half.
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
@@ -236,7 +240,7 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
     if (k >= p.K) return;
     if (p.vec_store && k + 8 <= p.K) {
         const float bias[8] = {br.lo.x, br.lo.y, br.lo.z, br.lo.w, br.hi.x, br.hi.y, br.hi.z, br.hi.w};
-        const int limit = relu_limit(p.relu);
+        const unsigned limit = relu_limit(p.relu);
         int m[ITEMS];
         uint4 rr[ITEMS];
 #pragma unroll
@@ -271,7 +275,7 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
             unsigned pk[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                pk[e] = pack_bf16(relu_or_pass(v[2 * e], limit), relu_or_pass(v[2 * e + 1], limit));
+                pk[e] = relu_or_pass(pack_bf16(v[2 * e], v[2 * e + 1]), limit);
             *reinterpret_cast<uint4 *>(p.y + (m[i] * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
     } else {
@@ -997,10 +1001,11 @@ __global__ __launch_bounds__(12 * 64) void conv1x1_stream_kernel(const ConvParam
 //  * the patch is double buffered and requested two tiles ahead into
 //    registers, so a tile has one workgroup barrier and never waits for memory;
 //  * the product is taken as filters x pixels, which leaves every lane with
-//    groups of 4 consecutive channels of one pixel; one 32-lane swap per
-//    register pair turns them into groups of 8, and the lane stores 16 bytes
-//    straight from registers (no LDS round trip).  The accumulators start
-//    from the bias (read from LDS) instead of zero.
+//    groups of 4 consecutive channels of one pixel; rounded to bf16 they cross
+//    a piece of LDS private to the wavefront (no barrier) and return as 16
+//    bytes per lane with eight consecutive lanes covering one pixel, so the
+//    stores write whole 128-byte lines.  The accumulators start from the bias
+//    (read from LDS) instead of zero.
 // Needs a destination that allows aligned 16-byte stores, K % 8 == 0 and no
 // residual operand; other layers stay with the gathering kernel.
 // The depth is summed in ascending (r, s, c) order like every other kernel,
@@ -1019,7 +1024,9 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(const ConvParams p, cons
                                                         const int tiles_q, const int tiles_pq) {
     constexpr int BN = NT * 32, KS = KROW / 16;
     constexpr int WELEMS = BN * R * KROW;  // padded weights, staged once on their way to registers
-    __shared__ __attribute__((aligned(16))) unsigned char stg_raw[WELEMS * 2];
+    constexpr int TROW = BN * 2 + 16;      // bytes per pixel row of the epilogue's transposition (padded)
+    constexpr int STG_BYTES = WELEMS * 2 > 4 * 32 * TROW ? WELEMS * 2 : 4 * 32 * TROW;
+    __shared__ __attribute__((aligned(16))) unsigned char stg_raw[STG_BYTES];
     __shared__ __attribute__((aligned(16))) uint2 patch[2][STEM_PX];
     __shared__ __attribute__((aligned(16))) float lbias[BN];
 
@@ -1128,36 +1135,41 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(const ConvParams p, cons
     };
 
     // Registers -> memory for one wavefront's 32 pixels x BN filters.  Accumulator register v of
-    // a lane belongs to filter 8*(v/4) + 4*(lane/32) + v%4 of its 32 and to pixel lane%32.
-    auto store_direct = [&](const Tile &tl, const f32x16 (&acc)[NT]) {
-        const int pp = tl.p0 + wave, qq = tl.q0 + frow;
-        const bool valid = pp < p.P && qq < p.Q;
-        const int m = (tl.n * p.P + pp) * p.Q + qq;
-        const int limit = relu_limit(p.relu);
+    // a lane belongs to filter 8*(v/4) + 4*(lane/32) + v%4 of its 32 and to pixel lane%32, so a
+    // lane holds 8-byte pieces of one pixel.  They pass through a region of LDS private to the
+    // wavefront (rows of TROW bytes per pixel; no workgroup barrier) and come back with eight
+    // consecutive lanes holding the eight 16-byte groups of one pixel: every store instruction
+    // then writes whole 128-byte lines.
+    auto store_rows = [&](const Tile &tl, const f32x16 (&acc)[NT]) {
+        unsigned char *tr = stg_raw + wave * (32 * TROW);
+        const unsigned limit = relu_limit(p.relu);
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int kb = n0 + t * 32;
-            unsigned d[8];
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                d[e] = pack_bf16(relu_or_pass(acc[t][2 * e], limit), relu_or_pass(acc[t][2 * e + 1], limit));
-            // d[2g], d[2g+1] = filters 8g + 4*(lane/32) .. +4.  Swapping the upper 32 lanes of group
-            // 2q with the lower 32 lanes of group 2q+1 leaves a lower lane with filters 16q .. 16q+8
-            // and its partner 32 lanes up with 16q+8 .. 16q+16, eight consecutive ones each.
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<uint2 *>(tr + frow * TROW + t * 64 + g * 16 + fhalf * 8) =
+                    make_uint2(relu_or_pass(pack_bf16(acc[t][4 * g], acc[t][4 * g + 1]), limit),
+                               relu_or_pass(pack_bf16(acc[t][4 * g + 2], acc[t][4 * g + 3]), limit));
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        constexpr int GPP = BN / 8;        // 16-byte groups per pixel
+        constexpr int PPI = 64 / GPP;      // pixels per store instruction
+        const int grp = lane % GPP, px0 = lane / GPP;
+        const int pp = tl.p0 + wave;
+        const int k = n0 + grp * 8;
+        const int mrow = (tl.n * p.P + pp) * p.Q;
+        uint4 out[32 / PPI];
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
+        for (int i = 0; i < 32 / PPI; ++i)
+            out[i] = *reinterpret_cast<const uint4 *>(tr + (px0 + i * PPI) * TROW + grp * 16);
 #pragma unroll
-                for (int w = 0; w < 2; ++w) {
-                    const auto sw = __builtin_amdgcn_permlane32_swap(d[4 * q + w], d[4 * q + 2 + w], false, false);
-                    d[4 * q + w] = sw[0];
-                    d[4 * q + 2 + w] = sw[1];
-                }
-                const int k = kb + 16 * q + 8 * fhalf;
-                if (valid && k < p.K)
-                    *reinterpret_cast<uint4 *>(p.y + (m * p.ldy + p.y_off + k)) =
-                        make_uint4(d[4 * q], d[4 * q + 1], d[4 * q + 2], d[4 * q + 3]);
-            }
+        for (int i = 0; i < 32 / PPI; ++i) {
+            const int qq = tl.q0 + px0 + i * PPI;
+            if (pp < p.P && qq < p.Q && k < p.K)
+                *reinterpret_cast<uint4 *>(p.y + ((mrow + qq) * p.ldy + p.y_off + k)) = out[i];
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     };
 
     // The patch of tile t+1 is written to LDS during tile t and was requested during tile t-1:
@@ -1165,7 +1177,7 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(const ConvParams p, cons
     uint2 nxt[STEM_PXT], nxt2[STEM_PXT];
     Tile cur = tile_at(0), nx = cur;
     fetch(cur, nxt);
-    stash(0, nxt);
+    stash(0, nxt);  // (the first barrier of the tile loop also frees the weights' staging area)
     if (T > 1) {
         nx = tile_at(1);
         fetch(nx, nxt);
@@ -1213,7 +1225,7 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(const ConvParams p, cons
                     acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[r][j][n], a.h, acc[n], 0, 0, 0);
             }
         if (t + 1 < T) stash((t + 1) & 1, have);
-        store_direct(cur, acc);
+        store_rows(cur, acc);
         cur = nx;
         nx = nx2;
     };
