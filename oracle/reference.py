@@ -148,29 +148,34 @@ def depthwise_conv2d(x, w, b=None, stride=1, pad=0, relu=False):
     return y
 
 
-def run_model(model, params, x, keep=False):
+def run_model(model, params, x, keep=False, storage=None):
     """Forward pass of a ``workloads.Model`` on batch ``x`` (N,C,H,W) in fp64.
 
     Returns the output tensor, or with ``keep`` the dict of every named
-    tensor (for per-layer comparisons)."""
+    tensor (for per-layer comparisons).  ``storage``, if given, is applied to
+    the output of every layer that computes (not to pooling by maximum or
+    concatenation, which only move values): a test passes the rounding of an
+    implementation's tensor format there to tell the error of the format from
+    the error of the arithmetic.  The arithmetic of every layer stays fp64."""
+    keep_as = storage if storage is not None else (lambda a: a)
     t = {"x": _f64(x)}
     for nd in model.nodes:
         a = nd.attr
         if nd.op == "conv":
             w, b = params[nd.name]
             res = t[a["residual"]] if a["residual"] else None
-            t[nd.dst] = conv2d(t[nd.src], w, b, a["stride"], a["pad"], a["relu"], res)
+            t[nd.dst] = keep_as(conv2d(t[nd.src], w, b, a["stride"], a["pad"], a["relu"], res))
         elif nd.op == "dwconv":
             w, b = params[nd.name]
-            t[nd.dst] = depthwise_conv2d(t[nd.src], w, b, a["stride"], a["pad"], a["relu"])
+            t[nd.dst] = keep_as(depthwise_conv2d(t[nd.src], w, b, a["stride"], a["pad"], a["relu"]))
         elif nd.op == "maxpool":
             t[nd.dst] = maxpool(t[nd.src], a["k"], a["stride"], a["pad"])
         elif nd.op == "gavgpool":
-            t[nd.dst] = global_avgpool(t[nd.src])
+            t[nd.dst] = keep_as(global_avgpool(t[nd.src]))
         elif nd.op == "fc":
             w, b = params[nd.name]
             src = t[nd.src]
-            t[nd.dst] = fc(src.reshape(src.shape[0], -1), w, b, a["relu"])
+            t[nd.dst] = keep_as(fc(src.reshape(src.shape[0], -1), w, b, a["relu"]))
         elif nd.op == "concat":
             t[nd.dst] = np.concatenate([t[s] for s in nd.src], axis=1)
         else:

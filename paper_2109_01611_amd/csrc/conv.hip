@@ -1119,6 +1119,11 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(const ConvParams p, cons
             const bool ok = static_cast<unsigned>(h0 + prow[i]) < static_cast<unsigned>(p.H) &&
                             static_cast<unsigned>(w0 + pcol[i]) < static_cast<unsigned>(p.W);
             const unsigned off = ok ? static_cast<unsigned>(base + poff[i]) : OOB;
+            if (p.C == 4) {  // pixels are 8 bytes already (an 8-byte aligned tensor is checked on the host)
+                const auto two = __builtin_amdgcn_raw_buffer_load_b64(rx, off, 0, 0);
+                v[i] = make_uint2(two[0], two[1]);
+                continue;
+            }
             unsigned e[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -1481,6 +1486,7 @@ hipError_t launch_stream(ConvParams p, int n_cu, hipStream_t stream) {
 bool stem_applicable(const ConvParams &p) {
     if (p.C > 4 || p.S > 8 || !(p.R == 3 || p.R == 5 || p.R == 7)) return false;
     if (!p.vec_store || p.K % 8 != 0 || p.res) return false;
+    if (p.C == 4 && reinterpret_cast<uintptr_t>(p.x) % 8 != 0) return false;  // 8-byte pixel loads
     const int krow = p.S <= 4 ? 16 : 32;
     const int nrows = (STEM_TP - 1) * p.stride + p.R, ncols = (STEM_TQ - 1) * p.stride + krow / 4;
     return nrows * ncols <= STEM_PX;

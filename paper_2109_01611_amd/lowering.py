@@ -11,10 +11,12 @@ Layout conversions
   * FC weights whose input is a (C, H, W) feature map: columns go from the
     channel-major flatten order to the NHWC one.
 
-The model input is stored with its channel count padded up to a multiple of 8
-(zeros), and the first convolution's weights are padded to match, so image
-stems (C = 3) and LeNet (C = 1) use the same 16-byte gathers as every other
-layer; the extra channels contribute exact zeros.
+The model input is stored with its channel count padded with zeros, and the
+first convolution's weights are padded to match; the extra channels contribute
+exact zeros.  RGB stems (C = 3, a filter of 3, 5 or 7 rows, a multiple of 8
+filters) are padded to 4 channels, the 8-byte pixels the library's stem kernel
+stages; everything else (LeNet's C = 1 with 6 filters) to a multiple of 8, so
+that it uses the same 16-byte gathers as every other layer.
 
 Buffers are reused once their last reader has run, which keeps the working
 set small enough to stay in the last-level cache between layers.  A concat
@@ -59,7 +61,13 @@ class DeviceModel:
         nodes = [nd for nd in model.nodes]
         # channel padding of the model input (only convolutions may read it then)
         c_in = model.in_shape[0]
-        self.in_pad = (-c_in) % 8 if all(nd.op == "conv" for nd in nodes if nd.src == "x") else 0
+        readers = [nd for nd in nodes if nd.src == "x"]
+        if not all(nd.op == "conv" for nd in readers):
+            self.in_pad = 0
+        elif c_in <= 4 and all(nd.attr["k"] in (3, 5, 7) and nd.attr["K"] % 8 == 0 for nd in readers):
+            self.in_pad = 4 - c_in
+        else:
+            self.in_pad = (-c_in) % 8
 
         # channels of every named tensor, straight from the table
         chans = {"x": model.in_shape[0]}

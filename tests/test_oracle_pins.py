@@ -479,3 +479,26 @@ def test_ssd_wiring_against_handwritten_torch():
         assert head.shape == T[name].shape
         assert head.shape[1] == (3 if k == 1 else 6) * (4 + 3)
         assert np.max(np.abs(head - T[name])) < 1e-9 * max(1.0, np.abs(head).max())
+
+
+def test_run_model_storage_hook_sees_every_computing_layer_once():
+    # The hook models an implementation's tensor format; the layers' arithmetic must not change.
+    m = workloads.resnet50(width_div=8, in_hw=32, n_class=10, blocks=(1, 2))
+    P = workloads.parameters(m, seed=3)
+    x = workloads.batch_input(m, 2, seed=3)
+    plain = oracle.run_model(m, P, x)
+    seen = []
+
+    def ident(a):
+        seen.append(a.shape)
+        return a
+
+    assert np.array_equal(oracle.run_model(m, P, x, storage=ident), plain)
+    assert len(seen) == sum(nd.op in ("conv", "dwconv", "fc", "gavgpool") for nd in m.nodes)
+    # a hook that halves every stored tensor scales a bias-free ReLU chain by 2^-depth: checked on
+    # the stem alone (one conv, then max-pool, which stores nothing new)
+    T = oracle.run_model(m, P, x, keep=True, storage=lambda a: 0.5 * a)
+    T0 = oracle.run_model(m, P, x, keep=True)
+    first = m.nodes[0]
+    assert first.op == "conv"
+    assert np.array_equal(T[first.dst], 0.5 * T0[first.dst])
