@@ -183,14 +183,17 @@ gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b,
  *      most 4 channels (image stems): the tile's input patch sits in LDS as
  *      4-channel pixels and filter rows are padded to 16 or 32 elements
  *      (filters of 3, 5 or 7 rows and at most 8 columns; other shapes run
- *      tile 1 instead),
+ *      tile 1 instead)
+ *  10: 128x64 walked by workgroups that keep their 64 filters' weights in
+ *      registers (3x3 filters, stride 1, pad 1, exactly 64 input channels, no
+ *      residual operand; other shapes run tile 1 instead),
  * or -1 to return to automatic selection, which picks the tile whose busiest
  * CU has the least work for the launch's shape and the stream's CU count, and
- * tile 9 wherever it applies.  Tiles 0..8 give bit-identical results; tile 9
+ * tile 9 wherever it applies.  Tiles 0..8 and 10 give bit-identical results; tile 9
  * groups the same ascending sum differently (zero padding inside the depth),
- * so it agrees with them to rounding.  GPULET_EINVAL outside -1..9.
+ * so it agrees with them to rounding.  GPULET_EINVAL outside -1..10.
  */
-enum { GPULET_CONV_TILES = 10 };
+enum { GPULET_CONV_TILES = 11 };
 gpulet_status gpulet_set_conv_tile(int tile);
 
 /*

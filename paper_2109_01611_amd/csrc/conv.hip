@@ -847,6 +847,232 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 }
 
 // ---------------------------------------------------------------------------
+// 3x3 filters, stride 1, pad 1, exactly 64 input channels (the first stages of
+// VGG-16 and ResNet-50): the weights stay in registers.
+//
+// With one block of 64 channels the patch kernel above would fetch all of a
+// filter tile's weights (72 KB) for every 128 output pixels, more than the
+// pixels themselves.  Here a workgroup owns one tile of 64 filters for its whole
+// life and walks over many pixel tiles.  Its four consumer wavefronts are 2
+// pixel halves x 2 filter halves (64 pixels x 32 filters each), and a consumer
+// keeps the 36 fragments of its 32 filters (9 taps x 4 depth steps) in 144
+// registers: in the main loop LDS serves only the input patch, two fragment
+// reads for two matrix instructions.  Four producer wavefronts keep the patches
+// of the next tiles in flight (two LDS buffers of 32 KB, DMA loads; a third buffer changed nothing).
+//
+// Per tile every wavefront executes two barriers:
+//   B1(t): the patch of tile t has landed (each producer waited for its own
+//          transfers; those of later tiles may still be in flight);
+//   B2(t): the consumers have read the patch of tile t for the last time; the
+//          producers refill that buffer with tile t+2.
+// The product is taken as filters x pixels, so a lane ends up with groups of 4
+// consecutive filters of one pixel; bias, ReLU and the rounding to bf16 happen
+// in registers, and a piece of LDS private to the wavefront turns the groups
+// into 16 bytes per lane with four consecutive lanes covering a pixel's 32
+// filters (no workgroup barrier, 64-byte store segments).
+// Taps and channels are summed in the order of the patch kernel and the bias
+// is added last, so results are bit-identical to the other tiles.  No residual
+// operand; K % 8 == 0 and a destination that allows aligned 16-byte stores.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, const int wgs_per_col, const int tiles_m,
+                                                          const int die_aware) {
+    constexpr int BM = PATCH_BM, BN = 64, NPROD = 4, PMAX = PATCH_PMAX, NB = 2;  // NB patch buffers
+    constexpr int PATCH = PMAX * BK;           // elements per patch buffer
+    constexpr int POPS = PMAX / 8 / NPROD;     // patch transfers per producer lane and tile
+    constexpr int TROW = 32 * 2 + 16;          // bytes per pixel row of a consumer's transposition area (padded)
+    static_assert(NB * POPS <= 63, "6-bit transfer counter");
+    __shared__ __attribute__((aligned(1024))) __bf16 patch[NB * PATCH];
+    __shared__ __attribute__((aligned(16))) unsigned char trs[4 * 64 * TROW];
+    __shared__ __attribute__((aligned(16))) float lbias[BN];
+
+    // Which pixel tiles this workgroup walks: first, stride, count (uniform over the workgroup).
+    // Workgroups are dealt round-robin to the eight dies.  When the grid allows it every die
+    // gets one contiguous eighth of the pixel tiles, which its workgroups (all filter tiles
+    // included) sweep side by side: the halo rows and columns that neighbouring tiles share, and
+    // the second read of a patch by the next filter tile, then hit that die's L2 instead of
+    // crossing the fabric again.
+    int col, first, step, T;
+    if (die_aware) {
+        const int die = blockIdx.x & 7, r = blockIdx.x >> 3;
+        col = r % p.tiles_n;
+        const int slot = r / p.tiles_n;
+        const int per_die = (tiles_m + 7) >> 3;
+        const int begin = die * per_die;
+        const int count = min(per_die, tiles_m - begin);
+        step = wgs_per_col >> 3;
+        first = begin + slot;
+        T = slot < count ? (count - slot + step - 1) / step : 0;
+    } else {
+        col = blockIdx.x % p.tiles_n;
+        first = blockIdx.x / p.tiles_n;
+        step = wgs_per_col;
+        T = first < tiles_m ? (tiles_m - first + step - 1) / step : 0;
+    }
+    if (T <= 0) return;
+    const int n0 = col * BN;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NP = p.N * p.P;
+    const int Hp = p.H + 2 * p.pad;       // virtual rows per image
+    const int pwt = p.tw + 2;             // patch width: block columns plus the two halo columns
+    if (threadIdx.x < BN) lbias[threadIdx.x] = (p.b && n0 + threadIdx.x < p.K) ? p.b[n0 + threadIdx.x] : 0.f;
+
+    auto vrow = [&](int rho) {
+        const int n = fdiv(rho, p.d_p);
+        return n * Hp + (rho - n * p.P);
+    };
+    // Pixel tile t of this workgroup: first linear pixel, first column, first virtual row.
+    struct Tile {
+        int l0, q0, v0, npos;
+    };
+    auto tile_at = [&](int t) {
+        const int tm = first + t * step;
+        const int tl = fdiv(tm, p.d_ncb), cb = tm - tl * p.n_cb;
+        Tile r;
+        r.l0 = tl * BM;
+        r.q0 = cb * p.tw;
+        const int rho_first = fdiv(r.l0, p.d_tw);
+        const int rho_last = min(NP - 1, fdiv(r.l0 + BM - 1, p.d_tw));
+        r.v0 = vrow(rho_first);
+        r.npos = (vrow(rho_last) + 2 - r.v0 + 1) * pwt;  // positions this tile needs (<= PMAX)
+        return r;
+    };
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------ producer
+        const int pw = wave - 4;
+        const i32x4 rx = make_rsrc(p.x, p.x_bytes);
+        // Transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8; this lane fills
+        // physical chunk lane&7 of one of them.
+        auto issue_patch = [&](int t) {
+            const unsigned base = lds_addr(patch + (t % NB) * PATCH) + pw * 1024;
+            Tile tl = tile_at(t < T ? t : 0);
+            if (t >= T) tl.npos = 0;  // past the end: the transfers still run (fixed count) and write zeros
+#pragma unroll
+            for (int j = 0; j < POPS; ++j) {
+                const int pos = (j * NPROD + pw) * 8 + (lane >> 3);
+                const int cc = (lane & 7) ^ ((pos >> 1) & 7);
+                unsigned off = OOB;
+                if (pos < tl.npos) {
+                    const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
+                    const int v = tl.v0 + vr;
+                    const int n = fdiv(v, p.d_hp);
+                    const int h = v - n * Hp - p.pad, w = tl.q0 + u - p.pad;
+                    if (n < p.N && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+                        off = static_cast<unsigned>((((n * p.H + h) * p.W + w) * BK + cc * CHUNK) * 2);
+                }
+                dma16(rx, base + j * NPROD * 1024, off);
+            }
+        };
+#pragma unroll
+        for (int t = 0; t < NB; ++t) issue_patch(t);
+        for (int t = 0; t < T; ++t) {
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((NB - 1) * POPS));  // all but the transfers of later tiles have landed
+            __syncthreads();                                         // B1
+            __syncthreads();                                         // B2
+            issue_patch(t + NB);
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    } else {
+        // ------------------------------------------------------------ consumer
+        const int frow = lane & 31, fhalf = lane >> 5;
+        const int wy = wave >> 1, wx = wave & 1;   // pixel half, filter half
+        // The fragments of this wavefront's 32 filters: tap-major, four depth steps of 16 each.
+        bf16x8 wf[36];
+        {
+            const __amdgpu_buffer_rsrc_t rw =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16 *>(p.w), 0, p.w_bytes, RSRC_FLAGS);
+            const int k = n0 + wx * 32 + frow;
+#pragma unroll
+            for (int i = 0; i < 36; ++i) {
+                const int tap = i >> 2, ks = i & 3;
+                const unsigned off = k < p.K ? static_cast<unsigned>(((k * 9 + tap) * BK + (ks * 2 + fhalf) * CHUNK) * 2) : OOB;
+                const u32x4 raw = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
+                wf[i] = __builtin_bit_cast(bf16x8, raw);
+            }
+        }
+        unsigned char *tr = trs + wave * (64 * TROW);
+        const unsigned limit = relu_limit(p.relu);
+        const int kst = n0 + wx * 32 + (lane & 3) * 8;   // first of the 8 filters this lane stores
+
+        for (int t = 0; t < T; ++t) {
+            const Tile tl = tile_at(t);
+            // Patch positions of this lane's two pixels at tap (0, 0).
+            int base[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int l = tl.l0 + wy * 64 + i * 32 + frow;
+                const int rho = fdiv(l, p.d_tw);
+                base[i] = rho < NP ? (vrow(rho) - tl.v0) * pwt + (l - rho * p.tw) : 0;
+            }
+            f32x16 acc[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+            __syncthreads();  // B1
+            const __bf16 *pa = patch + (t % NB) * PATCH;
+            // The fragments of depth step i+AHEAD are requested before the matrix instructions of
+            // step i are issued, so LDS reads and matrix instructions overlap inside the wavefront.
+            constexpr int AHEAD = 2;
+            struct Frags {
+                bf16x8 a[2];
+            };
+            auto load = [&](Frags &f, int i) {
+                const int tap = i >> 2, ks = i & 3;
+                const int r = tap / 3, sx = tap - r * 3;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int pos = base[h] + r * pwt + sx;
+                    f.a[h] = *reinterpret_cast<const bf16x8 *>(pa + pos * BK + (((ks * 2 + fhalf) ^ ((pos >> 1) & 7)) * CHUNK));
+                }
+            };
+            Frags f[36];
+#pragma unroll
+            for (int i = 0; i < AHEAD; ++i) load(f[i], i);
+#pragma unroll
+            for (int i = 0; i < 36; ++i) {
+                if (i + AHEAD < 36) load(f[i + AHEAD], i + AHEAD);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    acc[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], f[i].a[h], acc[h], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();  // B2
+
+            // Register v of a lane: filter 8*(v/4) + 4*(lane/32) + v%4 of the 32, pixel lane%32 (+32 h).
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 b4 = *reinterpret_cast<const float4 *>(&lbias[wx * 32 + 8 * g + 4 * fhalf]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    *reinterpret_cast<uint2 *>(tr + (h * 32 + frow) * TROW + g * 16 + fhalf * 8) = make_uint2(
+                        relu_or_pass(pack_bf16(acc[h][4 * g] + b4.x, acc[h][4 * g + 1] + b4.y), limit),
+                        relu_or_pass(pack_bf16(acc[h][4 * g + 2] + b4.z, acc[h][4 * g + 3] + b4.w), limit));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            uint4 out[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                out[i] = *reinterpret_cast<const uint4 *>(tr + ((lane >> 2) + i * 16) * TROW + (lane & 3) * 16);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int l = tl.l0 + wy * 64 + (lane >> 2) + i * 16;
+                const int rho = fdiv(l, p.d_tw);
+                const int q = tl.q0 + (l - rho * p.tw);
+                if (rho < NP && q < p.Q && kst < p.K)
+                    *reinterpret_cast<uint4 *>(p.y + ((rho * p.Q + q) * p.ldy + p.y_off + kst)) = out[i];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // 1x1 filters over 64 or 128 input channels with many output tiles: a streaming
 // kernel.
 //
@@ -1451,6 +1677,34 @@ hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// The 3x3 kernel with register-resident weights: what the patch kernel needs, exactly 64 input
+// channels, no residual operand, aligned 16-byte stores.
+bool c64_applicable(const ConvParams &p, bool vec, int *tw_out) {
+    return patch_eligible(p, vec, tw_out) && p.C == BK && !p.res && p.vec_store && p.K % 8 == 0;
+}
+
+hipError_t launch_c64(ConvParams p, int tw, int n_cu, hipStream_t stream) {
+    p.tw = tw;
+    p.n_cb = (p.Q + tw - 1) / tw;
+    const long long lin = 1LL * p.N * p.P * tw;
+    const int tiles_m = static_cast<int>((lin + PATCH_BM - 1) / PATCH_BM) * p.n_cb;
+    p.tiles_n = (p.K + 63) / 64;
+    p.n_tiles = tiles_m * p.tiles_n;
+    p.split_k = 1;
+    p.d_tw = make_fastdiv(tw);
+    p.d_ncb = make_fastdiv(p.n_cb);
+    p.d_pwt = make_fastdiv(tw + 2);
+    p.d_hp = make_fastdiv(p.H + 2 * p.pad);
+    // one workgroup per CU (registers), all resident at once; a multiple of 8 per filter tile
+    // where possible, so that every die can own a contiguous eighth of the pixel tiles
+    int wgs_per_col = std::max(1, std::min(tiles_m, n_cu / p.tiles_n));
+    const int die_aware = wgs_per_col >= 8 ? 1 : 0;
+    if (die_aware) wgs_per_col &= ~7;
+    hipLaunchKernelGGL(conv3x3_c64_kernel, dim3(static_cast<unsigned>(wgs_per_col * p.tiles_n)), dim3(512), 0, stream, p,
+                       wgs_per_col, tiles_m, die_aware);
+    return hipGetLastError();
+}
+
 // The streaming 1x1 kernel: C of 64 or 128, unit filter, enough pixel tiles that every
 // workgroup walks over several of them.
 bool stream_applicable(const ConvParams &p, bool vec) {
@@ -1670,9 +1924,23 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     }
     if (best == 8 && !stream_applicable(p, vec)) best = 2;  // same tile shape, one tile per workgroup
     if (forced < 0 && stream_eligible(p, vec, n_cu)) best = 8;
+    int tw64 = 0;
+    const bool c64_ok = c64_applicable(p, vec, &tw64);
+    if (best == 10 && !c64_ok) best = 1;
+    // Loading 144 registers of weights per consumer pays from about eight pixel tiles per
+    // workgroup on (measured: 3x3 64->64 on 224x224 at batch 32 209 -> 150-160 us, 64->192 on
+    // 56x56 36.6 -> 31.7 us; with three tiles per workgroup, 64->64 on 56x56, it is 9 % slower).
+    if (forced < 0 && c64_ok) {
+        const int n_cb = (p.Q + tw64 - 1) / tw64;
+        const long long tiles_m = ((1LL * p.N * p.P * tw64 + PATCH_BM - 1) / PATCH_BM) * n_cb;
+        const int tiles_n = (p.K + 63) / 64;
+        const int wgs_per_col = std::max(1, n_cu / tiles_n);
+        if (tiles_m >= 8LL * wgs_per_col) best = 10;
+    }
     if (best == 9 && !stem_applicable(p)) best = 1;
     if (forced < 0 && stem_applicable(p)) best = 9;  // by shape alone: the same bits in every batch and gpu-let
     switch (best) {
+        case 10: return launch_c64(p, tw64, n_cu, stream);
         case 9: return launch_stem(p, n_cu, stream);
         case 8: return launch_stream(p, n_cu, stream);
         case 7: return launch_patch<64>(p, tw, stream);

@@ -47,7 +47,7 @@ def test_conv_parity_every_tile(part, case):
     x, w, b = conv_tensors(11, N, C, H, W, K, R)
     ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
     first = None
-    for tile in range(-1, 10):
+    for tile in range(-1, 11):
         got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
         whole, per_img = oracle.rel_err(got, ref)
         assert max(whole, per_img) <= LAYER_TOL, (tile, whole, per_img)
@@ -87,6 +87,36 @@ def test_conv_patch_kernel_parity(part, case):
     ref = oracle.conv2d(x, w, b, 1, 1, False)
     assert oracle.rel_err(got[:, 8:8 + K], ref)[1] <= LAYER_TOL
     assert np.all(got[:, :8] == -512.0) and np.all(got[:, 8 + K:] == -512.0)
+
+
+# N, H, W, K: 3x3, stride 1, pad 1, exactly 64 input channels -> weights resident in registers (tile 10)
+C64_CASES = [
+    (3, 14, 14, 64),        # whole rows per block; M = 588: ragged last tile, fewer tiles than workgroups
+    (2, 56, 56, 64),        # 14-pixel column blocks
+    (1, 32, 32, 32),        # 16-pixel blocks; one filter half empty
+    (2, 20, 20, 40),        # ragged second column block, ragged filter tile
+    (2, 9, 33, 136),        # odd sizes, three filter tiles (last one 8 wide)
+    (1, 5, 3, 8),           # smaller than one tile
+    (16, 56, 56, 128),      # several tiles per workgroup, two filter tiles
+    (9, 7, 7, 72),          # a tile spans three images
+]
+
+
+@pytest.mark.parametrize("case", C64_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_3x3_c64_resident_weights_kernel_parity(part, case):
+    N, H, W, K = case
+    x, w, b = conv_tensors(21, N, 64, H, W, K, 3)
+    ref = oracle.conv2d(x, w, b, 1, 1, True)
+    got, raw = gpu_conv(part, x, w, b, 1, 1, True, tile=10)
+    assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+    _, gathered = gpu_conv(part, x, w, b, 1, 1, True, tile=1)
+    assert torch.equal(raw, gathered)          # same summation order as the gathering kernel
+    _, again = gpu_conv(part, x, w, b, 1, 1, True, tile=10)
+    assert torch.equal(raw, again)
+    got, _ = gpu_conv(part, x, w, None, 1, 1, False, ch_total=K + 24, ch_offset=16, tile=10)
+    ref = oracle.conv2d(x, w, None, 1, 1, False)
+    assert oracle.rel_err(got[:, 16:16 + K], ref)[1] <= LAYER_TOL
+    assert np.all(got[:, :16] == -512.0) and np.all(got[:, 16 + K:] == -512.0)
 
 
 # N, C, H, W, K, stride: 1x1 filters with 64 or 128 input channels -> the streaming kernel (tile 8)
