@@ -285,6 +285,10 @@ DW_CASES = [
     (1, 3, 10, 10, 3, 2, 1),
     (1, 512, 10, 10, 3, 1, 1),
     (2, 16, 4, 4, 1, 1, 0),         # 1x1 depthwise = per-channel scale
+    (2, 64, 21, 23, 3, 2, 1),       # stride 2, odd sizes: Q = 12, P = 11
+    (3, 24, 9, 10, 3, 2, 1),        # stride 2, Q = 5: ragged pair of pixels per thread
+    (1, 128, 38, 38, 3, 1, 1),
+    (2, 8, 3, 3, 3, 1, 1),          # every window touches the padding
 ]
 
 
