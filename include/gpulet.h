@@ -171,6 +171,20 @@ gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b,
                                    int y_ch_offset, void *stream);
 
 /*
+ * Pooling branch of an inception block (GoogLeNet of Table 4) in one kernel:
+ *   y = act(b + conv1x1(maxpool(x, window 3x3, stride 1, pad 1), w))
+ * with the pool's maximum taken over in-image taps only, as in gpulet_pool.
+ * The pooled tensor is never written; the result has the bits of gpulet_pool
+ * followed by gpulet_conv2d_fwd_ex.  x: N*H*W*C bf16, w: K*C bf16, b: K fp32
+ * or NULL, y and the channel-slice arguments as in gpulet_conv2d_fwd_ex.
+ * Errors: those of gpulet_conv2d_fwd_ex, and GPULET_EINVAL unless C is a
+ * multiple of 8 and x and w are 16-byte aligned.
+ */
+gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const float *b, void *y, int N,
+                                          int C, int H, int W, int K, int relu, int y_ch_stride,
+                                          int y_ch_offset, void *stream);
+
+/*
  * Tuning and testing knob: force every later convolution launch of the
  * process onto one workgroup tile (pixels x channels):
  *   0: 128x128  1: 128x64  2: 64x128  3: 64x64  4: 128x32  5: 32x128  6: 256x128
@@ -272,7 +286,8 @@ typedef struct gpulet_layer {
                               a concatenated tensor; 0 means K */
     int32_t out_ch_offset; /* CONV: first channel written */
     int32_t out_fp32;      /* FC: store fp32 instead of bf16 */
-    int32_t reserved;
+    int32_t pre_pool;      /* CONV: 0, or 3 = a 3x3 / stride 1 / pad 1 max pool of in_buf comes first
+                              (gpulet_maxpool3_conv1x1_fwd; 1x1 filters, stride 1, pad 0, C % 8 == 0) */
     const void *w;         /* device: CONV KRSC bf16, DWCONV RSC bf16, FC [Out][In] bf16 */
     const float *b;        /* device: fp32 bias or NULL */
 } gpulet_layer;

@@ -81,6 +81,7 @@ struct ConvArgs {
     void *y;
     const void *residual;
     int N, C, H, W, K, R, S, stride, pad, relu, P, Q, y_ch_stride, y_ch_offset;
+    int pre_pool = 0;  // 3: a 3x3 / stride 1 / pad 1 max pool is applied to x first (1x1 filters only)
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 void set_conv_tile(int tile);

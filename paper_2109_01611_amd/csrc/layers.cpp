@@ -1,6 +1,8 @@
 // Single-layer entry points of the C ABI: argument checks, then a launch on
 // the caller's stream (paper Sec. 5: the executor runs the model's layers on
 // its gpu-let).
+#include <cstdint>
+
 #include "gpulet_internal.h"
 
 using namespace gpulet;
@@ -31,6 +33,20 @@ extern "C" gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, cons
     gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual,
                                       y_ch_stride, y_ch_offset);
     if (st != GPULET_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv(a, stream_ctx(s), s));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const float *b, void *y, int N,
+                                                     int C, int H, int W, int K, int relu, int y_ch_stride,
+                                                     int y_ch_offset, void *stream) {
+    ConvArgs a;
+    a.pre_pool = 3;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, 1, 1, 1, 0, relu, nullptr, y_ch_stride,
+                                      y_ch_offset);
+    if (st != GPULET_OK) return st;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0) return GPULET_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     GPULET_HIP(launch_conv(a, stream_ctx(s), s));
     return GPULET_OK;

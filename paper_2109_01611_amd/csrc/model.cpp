@@ -172,6 +172,7 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
             a.stride = L.stride; a.pad = L.pad; a.relu = L.relu ? 1 : 0;
             a.P = out_extent(src.H, L.R, L.stride, L.pad);
             a.Q = out_extent(src.W, L.S, L.stride, L.pad);
+            a.pre_pool = L.pre_pool;
             a.y_ch_stride = L.out_ch_total > 0 ? L.out_ch_total : L.K;
             a.y_ch_offset = L.out_ch_total > 0 ? L.out_ch_offset : 0;
             s.slice = L.out_ch_total > 0;

@@ -39,7 +39,7 @@ class Layer(ctypes.Structure):
     """Mirror of ``gpulet_layer``."""
     _fields_ = [(n, c_int32) for n in (
         "op", "in_buf", "out_buf", "res_buf", "C", "K", "R", "S", "stride", "pad", "relu", "mode",
-        "out_ch_total", "out_ch_offset", "out_fp32", "reserved")] + [("w", c_void_p), ("b", c_void_p)]
+        "out_ch_total", "out_ch_offset", "out_fp32", "pre_pool")] + [("w", c_void_p), ("b", c_void_p)]
 
 
 class SchedModel(ctypes.Structure):
@@ -96,6 +96,7 @@ def _load():
         "gpulet_set_conv_tile": ([I], c_int32),
         "gpulet_set_conv_split_k": ([I], c_int32),
         "gpulet_depthwise_conv2d_fwd": ([P, P, P, P] + [I] * 9 + [P], c_int32),
+        "gpulet_maxpool3_conv1x1_fwd": ([P, P, P, P] + [I] * 8 + [P], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
         "gpulet_set_model_lanes": ([I], c_int32),
@@ -226,6 +227,11 @@ def set_conv_split_k(max_split):
 def depthwise_conv2d_fwd(x, w, b, y, N, C, H, W, R, S, stride, pad, relu, stream=None):
     _check(lib.gpulet_depthwise_conv2d_fwd(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, R, S, stride, pad,
                                            int(relu), stream), "gpulet_depthwise_conv2d_fwd")
+
+
+def maxpool3_conv1x1_fwd(x, w, b, y, N, C, H, W, K, relu, ch_total=0, ch_offset=0, stream=None):
+    _check(lib.gpulet_maxpool3_conv1x1_fwd(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, K, int(relu), ch_total,
+                                           ch_offset, stream), "gpulet_maxpool3_conv1x1_fwd")
 
 
 def pool(x, y, N, C, H, W, mode, k=1, stride=1, pad=0, stream=None):

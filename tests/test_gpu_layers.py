@@ -89,6 +89,56 @@ def test_conv_patch_kernel_parity(part, case):
     assert np.all(got[:, :8] == -512.0) and np.all(got[:, 8 + K:] == -512.0)
 
 
+# N, C, H, W, K: max pool 3x3 / stride 1 / pad 1 fused into a 1x1 convolution (inception pooling branch)
+POOLED_CASES = [
+    (2, 192, 28, 28, 32),      # inception 3a
+    (3, 480, 14, 14, 64),      # 4a: M = 588, ragged last pixel tile; 7.5 depth slices
+    (2, 832, 7, 7, 128),       # 5a: two filter tiles
+    (1, 8, 5, 3, 8),           # smaller than a tile, one chunk of depth
+    (2, 72, 9, 11, 40),        # ragged depth slice and filter tile
+    (1, 64, 1, 1, 16),         # a single pixel: every tap is the pixel itself
+    (2, 256, 1, 9, 24),        # one row: vertical taps all clamp
+]
+
+
+@pytest.mark.parametrize("case", POOLED_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_maxpool_fused_into_1x1_conv_parity(part, case):
+    N, C, H, W, K = case
+    x = inputs.tensor(22, "pc/x%d_%d_%d_%d" % (N, C, H, W), (N, C, H, W), "normal")     # negative values too
+    w = inputs.he_normal(22, "pc/w%d_%d" % (K, C), (K, C, 1, 1))
+    b = inputs.bias(22, "pc/b%d" % K, K)
+    xd = lowering.nchw_to_nhwc(x, DEV)
+    wd = lowering.kcrs_to_krsc(w, DEV)
+    bd = torch.from_numpy(b).to(DEV)
+    ct, off = K + 24, 16
+    yd = torch.full((N, H, W, ct), -512.0, dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    gpulet.maxpool3_conv1x1_fwd(xd, wd, bd, yd, N, C, H, W, K, True, ct, off, part.stream)
+    part.sync()
+    got = lowering.nhwc_to_nchw(yd)
+    ref = oracle.conv2d(oracle.maxpool(x, 3, 1, 1), w, b, 1, 0, True)
+    assert oracle.rel_err(got[:, off:off + K], ref)[1] <= LAYER_TOL
+    assert np.all(got[:, :off] == -512.0) and np.all(got[:, off + K:] == -512.0)
+    # the same bits as the pool kernel followed by the convolution kernel
+    pooled = torch.empty((N, H, W, C), dtype=torch.bfloat16, device=DEV)
+    y2 = torch.full((N, H, W, ct), -512.0, dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    gpulet.pool(xd, pooled, N, C, H, W, gpulet.POOL_MAX, 3, 1, 1, part.stream)
+    gpulet.conv2d_fwd_ex(pooled, wd, bd, y2, N, C, H, W, K, 1, 1, 1, 0, True, None, ct, off, part.stream)
+    part.sync()
+    assert torch.equal(yd, y2)
+    assert np.array_equal(lowering.nhwc_to_nchw(pooled), oracle.maxpool(x, 3, 1, 1))   # max pooling is exact
+
+
+def test_maxpool_fused_conv_rejects_what_it_cannot_run(part):
+    x = torch.zeros((1, 4, 4, 12), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((8, 1, 1, 12), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros((1, 4, 4, 8), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(gpulet.GpuletError) as e:      # C not a multiple of 8
+        gpulet.maxpool3_conv1x1_fwd(x, w, None, y, 1, 12, 4, 4, 8, True, 0, 0, part.stream)
+    assert e.value.status == gpulet.EINVAL
+
+
 # N, H, W, K: 3x3, stride 1, pad 1, exactly 64 input channels -> weights resident in registers (tile 10)
 C64_CASES = [
     (3, 14, 14, 64),        # whole rows per block; M = 588: ragged last tile, fewer tiles than workgroups
@@ -333,6 +383,11 @@ POOL_CASES = [
     (2, 7, 9, 9, gpulet.POOL_AVG, 3, 2, 1), (4, 2048, 7, 7, gpulet.POOL_GLOBAL_AVG, 1, 1, 0),
     (3, 1000, 5, 3, gpulet.POOL_GLOBAL_AVG, 1, 1, 0), (2, 13, 6, 6, gpulet.POOL_GLOBAL_AVG, 1, 1, 0),
     (1, 8, 1, 1, gpulet.POOL_GLOBAL_AVG, 1, 1, 0), (1, 1024, 7, 7, gpulet.POOL_GLOBAL_AVG, 1, 1, 0),
+    (2, 8, 5, 7, gpulet.POOL_MAX, 3, 1, 1), (1, 64, 12, 12, gpulet.POOL_MAX, 3, 2, 1),
+    (2, 40, 7, 9, gpulet.POOL_MAX, 2, 2, 0), (1, 8, 3, 3, gpulet.POOL_MAX, 3, 2, 1),
+    (2, 16, 6, 6, gpulet.POOL_MAX, 3, 3, 1), (1, 8, 2, 2, gpulet.POOL_MAX, 3, 1, 2),
+    (1, 16, 1, 1, gpulet.POOL_MAX, 3, 1, 1), (2, 48, 9, 4, gpulet.POOL_MAX, 2, 1, 1),
+    (1, 16, 9, 9, gpulet.POOL_MAX, 5, 2, 2),
 ]
 
 

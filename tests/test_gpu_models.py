@@ -188,6 +188,22 @@ def test_serving_batch_sizes_on_sampled_images(name, batch, pct, which):
     assert len({got[i].tobytes() for i in range(batch)}) == batch
 
 
+def test_inception_pool_branches_run_inside_their_projection():
+    model = workloads.googlenet(width_div=2, in_hw=96, n_class=20)
+    params = workloads.parameters(model, 9)
+    x = workloads.batch_input(model, 3, 9)
+    fused = lowering.DeviceModel(model, params, DEV, fuse_pools=True)
+    plain = lowering.DeviceModel(model, params, DEV)
+    n_pools = sum(nd.op == "maxpool" and (nd.attr["k"], nd.attr["stride"]) == (3, 1) for nd in model.nodes)
+    assert n_pools == 9 and len(fused.fused_pools) == 9 and not plain.fused_pools
+    with gpulet.Partition(0, 100, 0) as p:
+        a, _ = fused.run(p, fused.input_to_device(x))
+        b, _ = plain.run(p, plain.input_to_device(x))
+    assert torch.equal(a, b)            # fusing does not change a bit
+    ref = oracle.run_model(model, params, x).reshape(3, -1)
+    _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(3, -1), ref)
+
+
 def test_batch_size_does_not_change_an_images_result():
     # default: no depth splitting, so an image's logits are independent of its batch and gpu-let
     model = workloads.resnet50(width_div=2, in_hw=96, n_class=50)
