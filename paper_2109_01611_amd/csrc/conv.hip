@@ -235,10 +235,30 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
     constexpr int RSTEP = NTHR / VPR;      // tile rows between two items of a thread
     constexpr int ITEMS = (BM + RSTEP - 1) / RSTEP;
     static_assert(NTHR % VPR == 0, "a thread keeps its channel group");
+    if (!(p.vec_store && p.K % 8 == 0)) {
+        // Destinations that do not allow aligned 16-byte stores (channel counts such as the 546
+        // of a detection head, odd channel offsets): one element per thread and pass, with the
+        // lanes of a wavefront on consecutive channels of one pixel, so that the 2-byte stores
+        // of an instruction fall into one or two 128-byte lines; the bias is loaded once.
+        static_assert(NTHR % BN == 0, "whole tile rows per pass");
+        constexpr int ROWS = NTHR / BN;
+        const int c = threadIdx.x % BN, kc = n0 + c;
+        if (kc >= p.K) return;
+        const float bias1 = p.b ? p.b[kc] : 0.f;
+        for (int row = threadIdx.x / BN; row < BM; row += ROWS) {
+            const int m = pixel_of(row);
+            if (m < 0) continue;
+            float a = stg[row * LDT + c] + bias1;
+            if (p.res) a += static_cast<float>(p.res[m * p.K + kc]);
+            if (p.relu) a = a > 0.f ? a : 0.f;
+            p.y[m * p.ldy + p.y_off + kc] = static_cast<__bf16>(a);
+        }
+        return;
+    }
     const int cv = threadIdx.x % VPR, row0 = threadIdx.x / VPR;
     const int k = n0 + cv * 8;
     if (k >= p.K) return;
-    if (p.vec_store && k + 8 <= p.K) {
+    {
         const float bias[8] = {br.lo.x, br.lo.y, br.lo.z, br.lo.w, br.hi.x, br.hi.y, br.hi.z, br.hi.w};
         const unsigned limit = relu_limit(p.relu);
         int m[ITEMS];
@@ -277,17 +297,6 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
             for (int e = 0; e < 4; ++e)
                 pk[e] = relu_or_pass(pack_bf16(v[2 * e], v[2 * e + 1]), limit);
             *reinterpret_cast<uint4 *>(p.y + (m[i] * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        }
-    } else {
-        for (int row = row0; row < BM; row += RSTEP) {
-            const int m = pixel_of(row);
-            if (m < 0) continue;
-            for (int e = 0; e < 8 && k + e < p.K; ++e) {
-                float a = stg[row * LDT + cv * 8 + e] + (p.b ? p.b[k + e] : 0.f);
-                if (p.res) a += static_cast<float>(p.res[m * p.K + k + e]);
-                if (p.relu) a = a > 0.f ? a : 0.f;
-                p.y[m * p.ldy + p.y_off + k + e] = static_cast<__bf16>(a);
-            }
         }
     }
 }
