@@ -89,7 +89,7 @@ void set_conv_split_k(int max_split);
 hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P, int Q, int mode,
                        int k, int stride, int pad, hipStream_t stream);
 hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
-                     int relu, int out_fp32, hipStream_t stream);
+                     int relu, int out_fp32, const LaunchCtx &ctx, hipStream_t stream);
 hipError_t launch_dwconv(const void *x, const void *w, const float *b, void *y, int N, int C, int H, int W,
                          int R, int S, int stride, int pad, int relu, int P, int Q, hipStream_t stream);
 hipError_t launch_probe(uint32_t *out, int n_blocks, hipStream_t stream);

@@ -98,8 +98,8 @@ extern "C" gpulet_status gpulet_fc(const void *x, const void *w, const float *b,
     if (!x || !w || !y) return GPULET_EINVAL;
     gpulet_status st = check_fc(N, In, Out);
     if (st != GPULET_OK) return st;
-    GPULET_HIP(launch_fc(x, w, b, y, N, In, Out, relu ? 1 : 0, out_fp32 ? 1 : 0,
-                         static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_fc(x, w, b, y, N, In, Out, relu ? 1 : 0, out_fp32 ? 1 : 0, stream_ctx(s), s));
     return GPULET_OK;
 }
 

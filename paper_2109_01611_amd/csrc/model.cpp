@@ -304,7 +304,7 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
             e = launch_dwconv(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.C, s.H, s.W, s.k, s.k2,
                               s.stride, s.pad, s.relu, s.P, s.Q, stream);
         } else {
-            e = launch_fc(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.In, s.Out, s.relu, s.out_fp32,
+            e = launch_fc(bd.ptr(s.in_buf), s.w, s.b, bd.ptr(s.out_buf), s.N, s.In, s.Out, s.relu, s.out_fp32, ctx,
                           stream);
         }
         if (e != hipSuccess) return e;

@@ -417,7 +417,9 @@ def test_pool_parity(part, case):
 
 # N, In, Out
 FC_CASES = [(32, 400, 120), (32, 120, 84), (32, 84, 10), (1, 2048, 1000), (8, 1024, 1000),
-            (33, 72, 17), (5, 8, 3), (40, 4096, 1000), (16, 25088, 64), (2, 100, 7)]
+            (33, 72, 17), (5, 8, 3), (40, 4096, 1000), (16, 25088, 64), (2, 100, 7),
+            # long rows: 64 outputs per workgroup, depth split over workgroups
+            (32, 25088, 136), (1, 25088, 256), (17, 8192, 4096), (3, 8195, 20), (40, 9000, 72)]
 
 
 @pytest.mark.parametrize("case", FC_CASES, ids=lambda c: "x".join(map(str, c)))
@@ -453,3 +455,23 @@ def test_full_size_vgg_fc6(part):
     gpulet.fc(xd, wd, bd, yd, N, In, Out, True, False, part.stream)
     part.sync()
     assert oracle.rel_err(yd.to(torch.float32).cpu().numpy(), ref)[1] <= LAYER_TOL
+
+
+def test_long_row_fc_is_reproducible_and_batch_independent(part):
+    # partial tiles of an output group meet in scratch and are added in split order by whichever
+    # workgroup arrives last: same bits every time, and the same bits for an image in any batch
+    N, In, Out = 32, 25088, 200
+    x = inputs.tensor(33, "fcsx", (N, In), "uniform")
+    w = inputs.he_normal(33, "fcsw", (Out, In))
+    b = inputs.bias(33, "fcsb", Out)
+    xd, wd, bd = lowering.to_device_bf16(x, DEV), lowering.to_device_bf16(w, DEV), torch.from_numpy(b).to(DEV)
+    runs = []
+    for n in (N, N, 16, 1):
+        yd = torch.full((n, Out), -512.0, dtype=torch.float32, device=DEV)
+        torch.cuda.synchronize()
+        gpulet.fc(xd, wd, bd, yd, n, In, Out, False, True, part.stream)
+        part.sync()
+        runs.append(yd.clone())
+    assert torch.equal(runs[0], runs[1])
+    assert torch.equal(runs[0][:16], runs[2]) and torch.equal(runs[0][:1], runs[3])
+    assert oracle.rel_err(runs[0].cpu().numpy().astype(np.float64), oracle.fc(x, w, b, False))[1] <= 1e-4
