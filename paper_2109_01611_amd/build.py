@@ -12,8 +12,9 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpulet.so")
 
-SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "interference.cpp", "conv.hip", "dwconv.hip", "pool.hip",
-           "fc.hip", "probe.hip"]
+SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "interference.cpp", "conv.hip",
+           "conv_igemm.hip", "conv_patch.hip", "conv_stream.hip", "conv_stem.hip", "conv_pooled.hip", "dwconv.hip",
+           "pool.hip", "fc.hip", "probe.hip"]
 
 # The scheduler's fp64 decisions must not depend on fused multiply-adds.
 EXTRA = {"sched.cpp": ["-ffp-contract=off"], "interference.cpp": ["-ffp-contract=off"]}

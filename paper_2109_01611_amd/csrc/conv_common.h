@@ -1,0 +1,274 @@
+// Shared by the convolution kernels of this library (conv_*.hip): layer
+// parameters as the kernels see them, the multiply-shift division, the LDS
+// swizzle, the DMA-to-LDS transfer, and the common epilogue that turns an fp32
+// tile parked in LDS into bf16 rows (bias, residual, ReLU, one rounding).
+// Device code; include from .hip files only.
+#ifndef GPULET_CONV_COMMON_H
+#define GPULET_CONV_COMMON_H
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "gpulet_internal.h"
+
+namespace gpulet {
+namespace conv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+typedef __attribute__((ext_vector_type(2))) short s16x2;
+
+// ReLU on a pair of bf16 in one dword, switched without a branch: as signed 16-bit integers
+// every negative bf16 (and -0) is below zero, so max(bits, 0) is max(x, +0); with the limit at
+// 0x8000 the operation is the identity.  Rounding to bf16 keeps the sign, so clamping after the
+// rounding gives the same bits as clamping the fp32 value before it.
+__device__ __forceinline__ unsigned relu_limit(int relu) { return relu ? 0u : 0x80008000u; }
+__device__ __forceinline__ unsigned relu_or_pass(unsigned pair, unsigned limit) {
+    const s16x2 r = __builtin_elementwise_max(*reinterpret_cast<const s16x2 *>(&pair),
+                                              *reinterpret_cast<const s16x2 *>(&limit));
+    return *reinterpret_cast<const unsigned *>(&r);
+}
+// Two floats -> two bf16 (round to nearest even) in one dword, the first in the low half.
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    return *reinterpret_cast<const unsigned *>(&h);
+}
+
+constexpr int BK = 64;         // depth slice per main-loop step (elements)
+constexpr int CHUNK = 8;       // elements per 16-byte chunk
+constexpr int NTHREADS = 256;  // scalar-gather variant: four wavefronts
+constexpr unsigned OOB = 0x80000000u;      // byte offset past every buffer: the load returns zeros
+constexpr int RSRC_FLAGS = 0x00020000;     // raw buffer descriptor, 32-bit data format
+
+// Division of a non-negative int below 2^30 by a fixed positive divisor through one 64-bit
+// multiply: q = (n * mul) >> shift with shift = 30 + ceil(log2 d), mul = floor(2^shift / d) + 1.
+// Exact because n * (mul * d - 2^shift) <= n * d < 2^shift.  The tile setup of these kernels is
+// full of divisions by layer constants; the compiler's general sequence costs about 25
+// instructions each, on the critical path before the first load can be issued.
+struct FastDiv {
+    unsigned mul;
+    int shift;
+};
+
+inline FastDiv make_fastdiv(int d) {
+    int lg = 0;
+    while ((1LL << lg) < d) ++lg;
+    FastDiv f;
+    f.shift = 30 + lg;
+    f.mul = static_cast<unsigned>((1ULL << f.shift) / static_cast<unsigned long long>(d) + 1ULL);
+    return f;
+}
+
+__device__ __forceinline__ int fdiv(int n, const FastDiv f) {
+    return static_cast<int>((static_cast<unsigned long long>(static_cast<unsigned>(n)) * f.mul) >> f.shift);
+}
+
+struct ConvParams {
+    const __bf16 *x, *w;
+    const float *b;
+    __bf16 *y;
+    const __bf16 *res;
+    int N, C, H, W, K, R, S, stride, pad, relu, P, Q;
+    int M, Kg;          // GEMM rows and depth
+    int ldy, y_off;     // channels per output pixel of the destination, first channel
+    int tiles_n, n_tiles, tiles_per_xcd;
+    unsigned x_bytes, w_bytes;
+    int tap_inner;      // depth order: 64-channel block outermost, filter taps inside it
+    int vec_store;      // output (and residual) rows allow aligned 16-byte accesses
+    int split_k;        // workgroups sharing one output tile, each taking a contiguous range of slices
+    int sps;            // slices per split
+    float *part;        // split-K scratch: [n_tiles * split_k][BM * BN] fp32 partial tiles
+    unsigned *cnt;      // split-K scratch: arrival counter per tile (zero between launches)
+    // Patch kernel only: output pixels are grouped in column blocks of `tw` pixels.
+    int tw, n_cb;       // block width, blocks per output row
+    FastDiv d_pq, d_q, d_p, d_tiles_n, d_split_k, d_c, d_s;   // by P*Q, Q, P, tiles_n, split_k, C, S
+    FastDiv d_tw, d_ncb, d_pwt, d_hp;                         // patch kernel: by tw, n_cb, tw + 2, H + 2*pad
+};
+
+// LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
+// Rows are 128 bytes; XOR-ing the chunk index with bits 1..3 of the row spreads
+// 16 consecutive rows at one logical chunk over all 64 banks.
+__device__ __forceinline__ int lds_pos(int row, int chunk) {
+    return row * BK + ((chunk ^ ((row >> 1) & 7)) * CHUNK);
+}
+
+// Workgroups are dealt round-robin to the eight dies, each with its own L2.
+// Give every die a contiguous run of tiles so that tiles sharing a pixel block
+// (all their channel tiles) hit the same L2.
+__device__ __forceinline__ int tile_of_block(const ConvParams &p) {
+    return (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+}
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are
+// outstanding and leaves the other counters alone (gfx9 encoding).
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+// Raw buffer descriptor over `bytes` bytes at `ptr`: offsets at or past `bytes` read as zero.
+__device__ __forceinline__ i32x4 make_rsrc(const void *ptr, unsigned bytes) {
+    const unsigned long long a = reinterpret_cast<unsigned long long>(ptr);
+    return i32x4{static_cast<int>(a), static_cast<int>((a >> 32) & 0xFFFF), static_cast<int>(bytes), RSRC_FLAGS};
+}
+
+// LDS byte address of a __shared__ object.
+__device__ __forceinline__ unsigned lds_addr(const void *p) {
+    return static_cast<unsigned>(reinterpret_cast<unsigned long long>(
+        (const __attribute__((address_space(3))) char *)p));
+}
+
+// One wavefront-wide transfer of 64 x 16 bytes from a buffer into LDS: lane i's
+// 16 bytes at byte offset `voff` land at LDS address `lds_base` + 16*i
+// (`lds_base` is the same for the whole wavefront and travels in M0).  Issued
+// as assembly so that waiting for it stays under this kernel's control: the
+// transfers of later ring stages must remain in flight across LDS reads.
+__device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsigned voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(rsrc)
+                 : "memory");
+}
+
+// Last step of the epilogue for a BM x BN fp32 tile parked in LDS (rows padded
+// to BN + 8 floats): every thread of the workgroup takes 8 consecutive channels
+// of one tile row at a time, adds bias and residual, applies ReLU, rounds once
+// to bf16 and stores 16 bytes.  `pixel_of(row)` gives the output pixel
+// (n*P + p)*Q + q of a tile row, or -1 for rows past the end.  A thread keeps
+// its channel group for all of its rows, so the bias is loaded once, and the
+// residual loads of all its rows are issued before the first store: layers with
+// a short depth are bound by this loop, and one load-use-store chain per row
+// would leave it waiting for memory latency several times per tile.
+// The bias of the 8 channels a thread handles in finish_tile.  Called at the very start of a
+// kernel, so that the load's latency is hidden behind the whole main loop instead of sitting
+// between the last barrier and the first store.
+struct BiasRegs {
+    float4 lo, hi;
+};
+
+template <int BN, int NTHR>
+__device__ __forceinline__ BiasRegs load_bias(const ConvParams &p, int n0) {
+    constexpr int VPR = BN / 8;
+    const int k = n0 + (threadIdx.x % VPR) * 8;
+    BiasRegs r;
+    r.lo = r.hi = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (p.b && p.vec_store && k + 8 <= p.K) {
+        r.lo = *reinterpret_cast<const float4 *>(p.b + k);
+        r.hi = *reinterpret_cast<const float4 *>(p.b + k + 4);
+    }
+    return r;
+}
+
+template <int BM, int BN, int NTHR, typename PixelOf>
+__device__ __forceinline__ void finish_tile(const ConvParams &p, const float *stg, int n0, const BiasRegs &br,
+                                            PixelOf pixel_of) {
+    constexpr int LDT = BN + 8;
+    constexpr int VPR = BN / 8;            // 8-channel groups per tile row
+    constexpr int RSTEP = NTHR / VPR;      // tile rows between two items of a thread
+    constexpr int ITEMS = (BM + RSTEP - 1) / RSTEP;
+    static_assert(NTHR % VPR == 0, "a thread keeps its channel group");
+    if (!(p.vec_store && p.K % 8 == 0)) {
+        // Destinations that do not allow aligned 16-byte stores (channel counts such as the 546
+        // of a detection head, odd channel offsets): one element per thread and pass, with the
+        // lanes of a wavefront on consecutive channels of one pixel, so that the 2-byte stores
+        // of an instruction fall into one or two 128-byte lines; the bias is loaded once.
+        static_assert(NTHR % BN == 0, "whole tile rows per pass");
+        constexpr int ROWS = NTHR / BN;
+        const int c = threadIdx.x % BN, kc = n0 + c;
+        if (kc >= p.K) return;
+        const float bias1 = p.b ? p.b[kc] : 0.f;
+        for (int row = threadIdx.x / BN; row < BM; row += ROWS) {
+            const int m = pixel_of(row);
+            if (m < 0) continue;
+            float a = stg[row * LDT + c] + bias1;
+            if (p.res) a += static_cast<float>(p.res[m * p.K + kc]);
+            if (p.relu) a = a > 0.f ? a : 0.f;
+            p.y[m * p.ldy + p.y_off + kc] = static_cast<__bf16>(a);
+        }
+        return;
+    }
+    const int cv = threadIdx.x % VPR, row0 = threadIdx.x / VPR;
+    const int k = n0 + cv * 8;
+    if (k >= p.K) return;
+    {
+        const float bias[8] = {br.lo.x, br.lo.y, br.lo.z, br.lo.w, br.hi.x, br.hi.y, br.hi.z, br.hi.w};
+        const unsigned limit = relu_limit(p.relu);
+        int m[ITEMS];
+        uint4 rr[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int row = row0 + i * RSTEP;
+            m[i] = row < BM ? pixel_of(row) : -1;
+            rr[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        if (p.res) {
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i)
+                if (m[i] >= 0) rr[i] = *reinterpret_cast<const uint4 *>(p.res + (m[i] * p.K + k));
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            if (m[i] < 0) continue;
+            const int row = row0 + i * RSTEP;
+            const float4 lo = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8]);
+            const float4 hi = *reinterpret_cast<const float4 *>(&stg[row * LDT + cv * 8 + 4]);
+            float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += bias[e];
+            if (p.res) {
+                // a bf16 is the upper half of the fp32 with the same value
+                const unsigned ru[4] = {rr[i].x, rr[i].y, rr[i].z, rr[i].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] += __uint_as_float(ru[e] << 16);
+                    v[2 * e + 1] += __uint_as_float(ru[e] & 0xFFFF0000u);
+                }
+            }
+            unsigned pk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                pk[e] = relu_or_pass(pack_bf16(v[2 * e], v[2 * e + 1]), limit);
+            *reinterpret_cast<uint4 *>(p.y + (m[i] * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        }
+    }
+}
+
+// Patch-based 3x3 kernels: pixels per tile and patch positions per LDS buffer (32 KB).
+constexpr int PATCH_BM = 128;
+constexpr int PATCH_PMAX = 256;
+
+// ---------------------------------------------------------------------------
+// Host side of each kernel family: whether it applies to a layer, and its launch.
+// `vec` = C % 8 == 0 with 16-byte aligned x and w.
+// ---------------------------------------------------------------------------
+
+// conv_igemm.hip: gathering tiles 0..6 of gpulet_set_conv_tile (scalar-gather variant when !vec).
+// `two_stage` selects the 64 KB ring of tile 0 (two workgroups per CU).
+hipError_t launch_igemm(const ConvParams &p, bool vec, int tile, int split_k, bool two_stage, hipStream_t stream);
+
+// conv_patch.hip: tile 7 (input patch in LDS) and tile 10 (64 input channels, weights in registers).
+bool patch_eligible(const ConvParams &p, bool vec, int *tw_out);
+hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream);
+bool c64_applicable(const ConvParams &p, bool vec, int *tw_out);
+hipError_t launch_c64(ConvParams p, int tw, int n_cu, hipStream_t stream);
+
+// conv_stream.hip: tile 8 (streaming 1x1).
+bool stream_applicable(const ConvParams &p, bool vec);
+bool stream_eligible(const ConvParams &p, bool vec, int n_cu);
+hipError_t launch_stream(ConvParams p, int n_cu, hipStream_t stream);
+
+// conv_stem.hip: tile 9 (at most four input channels).
+bool stem_applicable(const ConvParams &p);
+hipError_t launch_stem(ConvParams p, int n_cu, hipStream_t stream);
+
+// conv_pooled.hip: 3x3 / stride 1 / pad 1 max pool fused into a 1x1 convolution.
+hipError_t launch_pooled_conv(ConvParams p, hipStream_t stream);
+
+}  // namespace conv
+}  // namespace gpulet
+#endif  // GPULET_CONV_COMMON_H
