@@ -10,6 +10,7 @@
 
 #include <algorithm>
 
+#include "device_util.h"
 #include "gpulet_internal.h"
 
 namespace gpulet {
@@ -18,56 +19,11 @@ namespace conv {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-
-typedef __attribute__((ext_vector_type(2))) short s16x2;
-
-// ReLU on a pair of bf16 in one dword, switched without a branch: as signed 16-bit integers
-// every negative bf16 (and -0) is below zero, so max(bits, 0) is max(x, +0); with the limit at
-// 0x8000 the operation is the identity.  Rounding to bf16 keeps the sign, so clamping after the
-// rounding gives the same bits as clamping the fp32 value before it.
-__device__ __forceinline__ unsigned relu_limit(int relu) { return relu ? 0u : 0x80008000u; }
-__device__ __forceinline__ unsigned relu_or_pass(unsigned pair, unsigned limit) {
-    const s16x2 r = __builtin_elementwise_max(*reinterpret_cast<const s16x2 *>(&pair),
-                                              *reinterpret_cast<const s16x2 *>(&limit));
-    return *reinterpret_cast<const unsigned *>(&r);
-}
-// Two floats -> two bf16 (round to nearest even) in one dword, the first in the low half.
-__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-    const f32x2 v = {lo, hi};
-    const bf16x2 h = __builtin_convertvector(v, bf16x2);
-    return *reinterpret_cast<const unsigned *>(&h);
-}
-
 constexpr int BK = 64;         // depth slice per main-loop step (elements)
 constexpr int CHUNK = 8;       // elements per 16-byte chunk
 constexpr int NTHREADS = 256;  // scalar-gather variant: four wavefronts
 constexpr unsigned OOB = 0x80000000u;      // byte offset past every buffer: the load returns zeros
 constexpr int RSRC_FLAGS = 0x00020000;     // raw buffer descriptor, 32-bit data format
-
-// Division of a non-negative int below 2^30 by a fixed positive divisor through one 64-bit
-// multiply: q = (n * mul) >> shift with shift = 30 + ceil(log2 d), mul = floor(2^shift / d) + 1.
-// Exact because n * (mul * d - 2^shift) <= n * d < 2^shift.  The tile setup of these kernels is
-// full of divisions by layer constants; the compiler's general sequence costs about 25
-// instructions each, on the critical path before the first load can be issued.
-struct FastDiv {
-    unsigned mul;
-    int shift;
-};
-
-inline FastDiv make_fastdiv(int d) {
-    int lg = 0;
-    while ((1LL << lg) < d) ++lg;
-    FastDiv f;
-    f.shift = 30 + lg;
-    f.mul = static_cast<unsigned>((1ULL << f.shift) / static_cast<unsigned long long>(d) + 1ULL);
-    return f;
-}
-
-__device__ __forceinline__ int fdiv(int n, const FastDiv f) {
-    return static_cast<int>((static_cast<unsigned long long>(static_cast<unsigned>(n)) * f.mul) >> f.shift);
-}
 
 struct ConvParams {
     const __bf16 *x, *w;

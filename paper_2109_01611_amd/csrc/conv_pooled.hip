@@ -26,16 +26,6 @@ namespace {
 // ---------------------------------------------------------------------------
 constexpr int PC_BM = 32, PC_BN = 64;
 
-__device__ __forceinline__ unsigned bf16_pair_order_key(unsigned v) {
-    const s16x2 x = *reinterpret_cast<const s16x2 *>(&v);
-    const s16x2 k = x ^ ((x >> 15) & static_cast<short>(0x7fff));
-    return *reinterpret_cast<const unsigned *>(&k);
-}
-__device__ __forceinline__ unsigned max_keys(unsigned a, unsigned b) {
-    const s16x2 r = __builtin_elementwise_max(*reinterpret_cast<const s16x2 *>(&a), *reinterpret_cast<const s16x2 *>(&b));
-    return *reinterpret_cast<const unsigned *>(&r);
-}
-
 // These layers are small (a few hundred pixel tiles at most) and all latency: a tile is 32
 // pixels x 64 filters so that there are enough workgroups, every thread pools one chunk per
 // slice, and the raw loads of slices j+1 and j+2 are in flight while slice j is multiplied.

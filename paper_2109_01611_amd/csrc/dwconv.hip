@@ -12,6 +12,7 @@
 // caches.  Algorithmic bytes: 2*(N*H*W*C + N*P*Q*C + R*S*C) + 4*C.
 #include <hip/hip_runtime.h>
 
+#include "device_util.h"
 #include "gpulet_internal.h"
 
 namespace gpulet {
@@ -24,37 +25,8 @@ struct DwParams {
     int N, C, H, W, R, S, stride, pad, relu, P, Q;
     int qt;     // thread columns per output row = ceil(Q / TQ)
     int total;  // work items
-    unsigned cv_mul, qt_mul, p_mul;   // 3x3 kernel: multipliers for the divisions by C/8, qt and P
-    int cv_shift, qt_shift, p_shift;  // (q = (n * mul) >> shift, exact for n < 2^30)
+    FastDiv d_cv, d_qt, d_p;  // 3x3 kernel: divisions by C/8, qt and P
 };
-
-// Division of a non-negative int below 2^30 by a fixed positive divisor d through one 64-bit
-// multiply: shift = 30 + ceil(log2 d), mul = floor(2^shift / d) + 1.
-inline void fastdiv_for(int d, unsigned *mul, int *shift) {
-    int lg = 0;
-    while ((1LL << lg) < d) ++lg;
-    *shift = 30 + lg;
-    *mul = static_cast<unsigned>((1ULL << *shift) / static_cast<unsigned long long>(d) + 1ULL);
-}
-
-__device__ __forceinline__ int fdiv(int n, unsigned mul, int shift) {
-    return static_cast<int>((static_cast<unsigned long long>(static_cast<unsigned>(n)) * mul) >> shift);
-}
-
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(2))) short s16x2_t;
-
-// Two floats -> two bf16 (round to nearest even) in one dword, then ReLU as a 16-bit integer
-// max against `limit` (0, or 0x8000 per half for "no ReLU"): negative bf16 are negative int16,
-// and rounding keeps the sign, so the bits equal clamping before rounding.
-__device__ __forceinline__ unsigned pack_relu(float lo, float hi, unsigned limit) {
-    const f32x2_t v = {lo, hi};
-    const bf16x2_t h = __builtin_convertvector(v, bf16x2_t);
-    const s16x2_t r = __builtin_elementwise_max(*reinterpret_cast<const s16x2_t *>(&h),
-                                                *reinterpret_cast<const s16x2_t *>(&limit));
-    return *reinterpret_cast<const unsigned *>(&r);
-}
 
 __device__ __forceinline__ void unpack8(const uint4 &v, float f[8]) {
     const unsigned u[4] = {v.x, v.y, v.z, v.w};
@@ -156,11 +128,11 @@ __global__ __launch_bounds__(256) void dwconv3x3_vec8(const DwParams p, const un
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= p.total) return;
     const int cv = p.C >> 3;
-    int t = fdiv(idx, p.cv_mul, p.cv_shift);
+    int t = fdiv(idx, p.d_cv);
     const int c8 = idx - t * cv;
-    const int t1 = fdiv(t, p.qt_mul, p.qt_shift);
+    const int t1 = fdiv(t, p.d_qt);
     const int qg = t - t1 * p.qt;
-    const int n = fdiv(t1, p.p_mul, p.p_shift);
+    const int n = fdiv(t1, p.d_p);
     const int pp = t1 - n * p.P;
     const int q0 = qg * TQ;
     const int h0 = pp * STRIDE - p.pad, w_first = q0 * STRIDE - p.pad;
@@ -216,14 +188,14 @@ __global__ __launch_bounds__(256) void dwconv3x3_vec8(const DwParams p, const un
             }
         }
     }
-    const unsigned limit = p.relu ? 0u : 0x80008000u;
+    const unsigned limit = relu_limit(p.relu);
 #pragma unroll
     for (int j = 0; j < TQ; ++j) {
         const int q = q0 + j;
         if (q >= p.Q) break;
         unsigned o[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = pack_relu(acc[j][2 * i], acc[j][2 * i + 1], limit);
+        for (int i = 0; i < 4; ++i) o[i] = relu_or_pass(pack_bf16(acc[j][2 * i], acc[j][2 * i + 1]), limit);
         *reinterpret_cast<uint4 *>(p.y + (((n * p.P + pp) * p.Q + q) * p.C + c8 * 8)) =
             make_uint4(o[0], o[1], o[2], o[3]);
     }
@@ -280,9 +252,9 @@ hipError_t launch_dwconv(const void *x, const void *w, const float *b, void *y, 
                      reinterpret_cast<uintptr_t>(b) % 16 == 0;
     if (vec && R == 3 && S == 3 && (stride == 1 || stride == 2)) {
         const unsigned x_bytes = static_cast<unsigned>(2LL * N * H * W * C);
-        fastdiv_for(C / 8, &p.cv_mul, &p.cv_shift);
-        fastdiv_for(P, &p.p_mul, &p.p_shift);
-        fastdiv_for((Q + (stride == 1 ? 4 : 2) - 1) / (stride == 1 ? 4 : 2), &p.qt_mul, &p.qt_shift);
+        p.d_cv = make_fastdiv(C / 8);
+        p.d_p = make_fastdiv(P);
+        p.d_qt = make_fastdiv((Q + (stride == 1 ? 4 : 2) - 1) / (stride == 1 ? 4 : 2));
         if (stride == 1) {
             constexpr int TQ = 4;
             p.qt = (Q + TQ - 1) / TQ;

@@ -6,6 +6,7 @@
 // wavefront shuffle reduction.
 #include <hip/hip_runtime.h>
 
+#include "device_util.h"
 #include "gpulet_internal.h"
 
 namespace gpulet {
@@ -16,38 +17,8 @@ struct PoolParams {
     __bf16 *y;
     int N, C, H, W, P, Q, k, stride, pad;
     int total;  // work items
-    unsigned cv_mul, q_mul, p_mul;   // pool_max_vec8: multipliers for the divisions by C/8, Q and P
-    int cv_shift, q_shift, p_shift;  // (q = (n * mul) >> shift, exact for n < 2^30)
+    FastDiv d_cv, d_q, d_p;  // pool_max_vec8: divisions by C/8, Q and P
 };
-
-// Division of a non-negative int below 2^30 by a fixed positive divisor d through one 64-bit
-// multiply: shift = 30 + ceil(log2 d), mul = floor(2^shift / d) + 1.
-inline void fastdiv_for(int d, unsigned *mul, int *shift) {
-    int lg = 0;
-    while ((1LL << lg) < d) ++lg;
-    *shift = 30 + lg;
-    *mul = static_cast<unsigned>((1ULL << *shift) / static_cast<unsigned long long>(d) + 1ULL);
-}
-
-__device__ __forceinline__ int fdiv(int n, unsigned mul, int shift) {
-    return static_cast<int>((static_cast<unsigned long long>(static_cast<unsigned>(n)) * mul) >> shift);
-}
-
-typedef __attribute__((ext_vector_type(2))) short s16x2_t;
-
-// bf16 are sign-magnitude: x ^ ((x >> 15) & 0x7fff) per 16-bit half maps a pair of them to two
-// signed integers in the same order, and back (the map is its own inverse).  The maximum of
-// bf16 values is then a packed 16-bit integer maximum, exact, without unpacking to fp32.
-__device__ __forceinline__ unsigned order_key(unsigned v) {
-    const s16x2_t x = *reinterpret_cast<const s16x2_t *>(&v);
-    const s16x2_t k = x ^ ((x >> 15) & static_cast<short>(0x7fff));
-    return *reinterpret_cast<const unsigned *>(&k);
-}
-__device__ __forceinline__ unsigned max_keys(unsigned a, unsigned b) {
-    const s16x2_t r = __builtin_elementwise_max(*reinterpret_cast<const s16x2_t *>(&a),
-                                                *reinterpret_cast<const s16x2_t *>(&b));
-    return *reinterpret_cast<const unsigned *>(&r);
-}
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short h) {
     return __uint_as_float(static_cast<unsigned>(h) << 16);
@@ -157,11 +128,11 @@ __global__ __launch_bounds__(256) void pool_max_vec8(const PoolParams p) {
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= p.total) return;
     const int cv = p.C >> 3;
-    int t = fdiv(idx, p.cv_mul, p.cv_shift);
+    int t = fdiv(idx, p.d_cv);
     const int c8 = idx - t * cv;
-    const int t1 = fdiv(t, p.q_mul, p.q_shift);
+    const int t1 = fdiv(t, p.d_q);
     const int q = t - t1 * p.Q;
-    const int n = fdiv(t1, p.p_mul, p.p_shift);
+    const int n = fdiv(t1, p.d_p);
     const int pp = t1 - n * p.P;
     const int h0 = pp * p.stride - p.pad, w0 = q * p.stride - p.pad;
     int rowo[K], colo[K];
@@ -175,16 +146,16 @@ __global__ __launch_bounds__(256) void pool_max_vec8(const PoolParams p) {
     for (int r = 0; r < K; ++r)
 #pragma unroll
         for (int sx = 0; sx < K; ++sx) v[r * K + sx] = *reinterpret_cast<const uint4 *>(p.x + rowo[r] + colo[sx]);
-    unsigned k[4] = {order_key(v[0].x), order_key(v[0].y), order_key(v[0].z), order_key(v[0].w)};
+    unsigned k[4] = {bf16_pair_order_key(v[0].x), bf16_pair_order_key(v[0].y), bf16_pair_order_key(v[0].z), bf16_pair_order_key(v[0].w)};
 #pragma unroll
     for (int j = 1; j < K * K; ++j) {
-        k[0] = max_keys(k[0], order_key(v[j].x));
-        k[1] = max_keys(k[1], order_key(v[j].y));
-        k[2] = max_keys(k[2], order_key(v[j].z));
-        k[3] = max_keys(k[3], order_key(v[j].w));
+        k[0] = max_keys(k[0], bf16_pair_order_key(v[j].x));
+        k[1] = max_keys(k[1], bf16_pair_order_key(v[j].y));
+        k[2] = max_keys(k[2], bf16_pair_order_key(v[j].z));
+        k[3] = max_keys(k[3], bf16_pair_order_key(v[j].w));
     }
     *reinterpret_cast<uint4 *>(p.y + (((n * p.P + pp) * p.Q + q) * p.C + c8 * 8)) =
-        make_uint4(order_key(k[0]), order_key(k[1]), order_key(k[2]), order_key(k[3]));
+        make_uint4(bf16_pair_order_key(k[0]), bf16_pair_order_key(k[1]), bf16_pair_order_key(k[2]), bf16_pair_order_key(k[3]));
 }
 
 // Window pooling for channel counts that are not multiples of 8: one element per thread.
@@ -310,9 +281,9 @@ hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P
     const unsigned blocks = static_cast<unsigned>((p.total + 255) / 256);
     const bool avg = mode == GPULET_POOL_AVG;
     if (vec && !avg && (k == 2 || k == 3)) {
-        fastdiv_for(C / 8, &p.cv_mul, &p.cv_shift);
-        fastdiv_for(Q, &p.q_mul, &p.q_shift);
-        fastdiv_for(P, &p.p_mul, &p.p_shift);
+        p.d_cv = make_fastdiv(C / 8);
+        p.d_q = make_fastdiv(Q);
+        p.d_p = make_fastdiv(P);
         if (k == 3)
             hipLaunchKernelGGL(pool_max_vec8<3>, dim3(blocks), dim3(256), 0, stream, p);
         else
