@@ -27,8 +27,9 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak, all 256 CUs
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    # a step is about 10 us: 20000 of them (0.2 s) let the clocks settle; 2000 read 3 % slower
+    ap.add_argument("--steps", type=int, default=20000)
+    ap.add_argument("--warmup", type=int, default=2000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     args = ap.parse_args()
