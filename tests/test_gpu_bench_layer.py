@@ -33,3 +33,34 @@ def test_streaming_1x1_kernel_on_small_gpulets(pct, which):
         assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
         got, _ = gpu_conv(small, x, w, b, 1, 0, True, tile=8)
         assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+
+
+@pytest.mark.parametrize("pct,which", [(20, 0), (60, 1)])
+def test_walking_kernels_on_small_gpulets(pct, which):
+    # the kernels whose workgroups walk over many tiles size their grids from the gpu-let's CU
+    # count: 64 and 160 CUs here, with one and three filter tiles (a grid that is and is not a
+    # multiple of the eight dies)
+    import numpy as np
+    import torch
+    from paper_2109_01611_amd import inputs, lowering
+    with gpulet.Partition(0, pct, which) as small:
+        for K in (64, 136):
+            x, w, b = conv_tensors(23, 3, 64, 40, 24, K, 3)            # weights in registers (tile 10)
+            ref = oracle.conv2d(x, w, b, 1, 1, True)
+            got, raw = gpu_conv(small, x, w, b, 1, 1, True, tile=10)
+            assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
+            _, gathered = gpu_conv(small, x, w, b, 1, 1, True, tile=1)
+            assert torch.equal(raw, gathered)
+        x, w, b = conv_tensors(23, 3, 3, 70, 50, 64, 7)                 # stem kernel (tile 9)
+        got, _ = gpu_conv(small, x, w, b, 2, 3, True, tile=9)
+        assert oracle.rel_err(got, oracle.conv2d(x, w, b, 2, 3, True))[1] <= LAYER_TOL
+        N, In, Out = 20, 8192, 200                                      # long-row FC: depth split sized from the CU count
+        xf = inputs.tensor(23, "sfx", (N, In), "uniform")
+        wf = inputs.he_normal(23, "sfw", (Out, In))
+        bf = inputs.bias(23, "sfb", Out)
+        xd, wd = lowering.to_device_bf16(xf, "cuda:0"), lowering.to_device_bf16(wf, "cuda:0")
+        yd = torch.full((N, Out), -512.0, dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        gpulet.fc(xd, wd, torch.from_numpy(bf).to("cuda:0"), yd, N, In, Out, True, True, small.stream)
+        small.sync()
+        assert oracle.rel_err(yd.cpu().numpy().astype(np.float64), oracle.fc(xf, wf, bf, True))[1] <= 1e-4
