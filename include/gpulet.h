@@ -191,7 +191,7 @@ gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const fl
  *   7: 128x64 with the input patch of a tile resident in LDS (3x3 filters,
  *      stride 1, pad 1, C a multiple of 64; other shapes run tile 1 instead)
  *   8: 64x128 walked by workgroups that keep their weights in LDS and stream
- *      over many pixel tiles (1x1 filters, C of 64 or 128; other shapes run
+ *      over many pixel tiles (1x1 filters, C a multiple of 8 up to 128; other shapes run
  *      tile 2 instead)
  *   9: 4 rows x 32 columns of one image by 32 or 64 channels, for inputs of at
  *      most 4 channels (image stems): the tile's input patch sits in LDS as

@@ -73,7 +73,9 @@ __global__ __launch_bounds__(12 * 64) void conv1x1_stream_kernel(const ConvParam
 #pragma unroll
             for (int i = 0; i < WINS; ++i) {
                 const int k = n0 + i * PROWS + lrow;
-                const unsigned off = k < p.K ? static_cast<unsigned>((k * p.C + q * BK + cc * CHUNK) * 2) : OOB;
+                // chunks past the last channel (C below a whole number of slices) read as zeros
+                const bool in = k < p.K && q * BK + cc * CHUNK < p.C;
+                const unsigned off = in ? static_cast<unsigned>((k * p.C + q * BK + cc * CHUNK) * 2) : OOB;
                 dma16(rw, lds_addr(wlds + q * BN * BK) + (i * PROWS + pw * 8) * (BK * 2), off);
             }
         auto issue_tile = [&](int t) {
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(12 * 64) void conv1x1_stream_kernel(const ConvParam
                 }
 #pragma unroll
                 for (int q = 0; q < NK; ++q)
-                    dma16(rx, base + (q * BM + i * PROWS) * (BK * 2), pix == OOB ? OOB : pix + q * (BK * 2));
+                    dma16(rx, base + (q * BM + i * PROWS) * (BK * 2),
+                          (pix == OOB || q * BK + cc * CHUNK >= p.C) ? OOB : pix + q * (BK * 2));
             }
         };
         issue_tile(0);
@@ -139,18 +142,18 @@ __global__ __launch_bounds__(12 * 64) void conv1x1_stream_kernel(const ConvParam
 
 }  // namespace
 
-// The streaming 1x1 kernel: C of 64 or 128, unit filter, enough pixel tiles that every
-// workgroup walks over several of them.
+// The streaming 1x1 kernel: at most 128 input channels (one or two depth slices, the last one
+// possibly partial), unit filter.
 bool stream_applicable(const ConvParams &p, bool vec) {
-    return vec && p.R == 1 && p.S == 1 && p.pad == 0 && (p.C == 64 || p.C == 128);
+    return vec && p.R == 1 && p.S == 1 && p.pad == 0 && p.C <= 2 * BK;
 }
 
-// Chosen automatically for one depth slice (C = 64: two workgroups per CU) and at least four tiles
+// Chosen automatically for one depth slice (C <= 64: two workgroups per CU) and at least four tiles
 // per CU, where it measured 11 % faster than the best one-tile-per-workgroup tile (1x1 64->256 on
 // 56x56 at batch 32: 20.3 -> 18.0 us); with two slices (C = 128) it was 8 % slower.
 bool stream_eligible(const ConvParams &p, bool vec, int n_cu) {
     const long long tiles = 1LL * ((p.M + STREAM_BM - 1) / STREAM_BM) * ((p.K + STREAM_BN - 1) / STREAM_BN);
-    return stream_applicable(p, vec) && p.C == 64 && tiles >= 4LL * n_cu;
+    return stream_applicable(p, vec) && p.C <= BK && tiles >= 4LL * n_cu;
 }
 
 hipError_t launch_stream(ConvParams p, int n_cu, hipStream_t stream) {
@@ -159,10 +162,10 @@ hipError_t launch_stream(ConvParams p, int n_cu, hipStream_t stream) {
     p.n_tiles = tiles_m * p.tiles_n;
     p.split_k = 1;
     // two workgroups per CU with one depth slice (75 KB of LDS each), one with two (115 KB)
-    const int slots = n_cu * (p.C == 64 ? 2 : 1);
+    const int slots = n_cu * (p.C <= BK ? 2 : 1);
     const int wgs_per_col = std::max(1, std::min(tiles_m, slots / p.tiles_n));
     const dim3 grid(static_cast<unsigned>(wgs_per_col * p.tiles_n));
-    if (p.C == 64)
+    if (p.C <= BK)
         hipLaunchKernelGGL(conv1x1_stream_kernel<1>, grid, dim3(12 * 64), 0, stream, p, wgs_per_col, tiles_m);
     else
         hipLaunchKernelGGL(conv1x1_stream_kernel<2>, grid, dim3(12 * 64), 0, stream, p, wgs_per_col, tiles_m);

@@ -169,7 +169,7 @@ def test_conv_3x3_c64_resident_weights_kernel_parity(part, case):
     assert np.all(got[:, :16] == -512.0) and np.all(got[:, 16 + K:] == -512.0)
 
 
-# N, C, H, W, K, stride: 1x1 filters with 64 or 128 input channels -> the streaming kernel (tile 8)
+# N, C, H, W, K, stride: 1x1 filters with at most 128 input channels -> the streaming kernel (tile 8)
 STREAM_CASES = [
     (1, 64, 5, 5, 24, 1),          # a single ragged tile
     (2, 64, 19, 17, 136, 1),       # M = 646: eleven tiles, last one ragged; two channel tiles, second ragged
@@ -177,6 +177,9 @@ STREAM_CASES = [
     (2, 128, 21, 21, 264, 2),      # strided 1x1 (projection shortcut), three channel tiles
     (8, 64, 56, 56, 256, 1),       # many tiles per workgroup
     (4, 128, 28, 28, 512, 1),
+    (3, 32, 30, 30, 64, 1),        # half a depth slice (MobileNet's first pointwise layer)
+    (2, 96, 13, 13, 40, 1),        # one and a half slices
+    (2, 8, 9, 9, 16, 1),           # a single 16-byte chunk of depth
 ]
 
 
