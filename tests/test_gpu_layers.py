@@ -478,3 +478,45 @@ def test_long_row_fc_is_reproducible_and_batch_independent(part):
     assert torch.equal(runs[0], runs[1])
     assert torch.equal(runs[0][:16], runs[2]) and torch.equal(runs[0][:1], runs[3])
     assert oracle.rel_err(runs[0].cpu().numpy().astype(np.float64), oracle.fc(x, w, b, False))[1] <= 1e-4
+
+
+def _random_conv_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < n:
+        kind = rng.integers(0, 5)
+        N = int(rng.integers(1, 5))
+        H, W = int(rng.integers(1, 41)), int(rng.integers(1, 41))
+        if kind == 0:       # stem-like: few channels
+            C, R = int(rng.integers(1, 5)), int(rng.choice([3, 5, 7]))
+            K, stride, pad = int(rng.choice([8, 16, 24, 32, 40, 64, 72])), int(rng.integers(1, 3)), int(rng.integers(0, R // 2 + 2))
+        elif kind == 1:     # 3x3 over exactly 64 channels
+            C, R, stride, pad = 64, 3, 1, 1
+            K = int(rng.choice([8, 24, 64, 72, 136]))
+        elif kind == 2:     # 1x1 with a short depth
+            C, R, stride, pad = int(rng.choice([8, 16, 32, 64, 96, 128])), 1, int(rng.integers(1, 3)), 0
+            K = int(rng.choice([8, 20, 64, 100, 136, 264]))
+        elif kind == 3:     # 3x3 over multiples of 64 channels (patch kernel)
+            C, R, stride, pad = int(rng.choice([64, 128, 192])), 3, 1, 1
+            K = int(rng.choice([16, 64, 72]))
+        else:               # anything
+            C, R = int(rng.integers(1, 80)), int(rng.choice([1, 2, 3, 5]))
+            K, stride, pad = int(rng.integers(1, 90)), int(rng.integers(1, 4)), int(rng.integers(0, 3))
+        if H + 2 * pad < R or W + 2 * pad < R:
+            continue
+        cases.append((N, C, H, W, K, R, stride, pad))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_conv_cases(40, 2024), ids=lambda c: "x".join(map(str, c)))
+def test_conv_random_shapes_through_every_kernel_family(part, case):
+    # seeded random shapes: automatic selection and every special-purpose kernel forced (a forced
+    # kernel that does not apply to a shape falls back to a gathering tile inside the library)
+    N, C, H, W, K, R, stride, pad = case
+    x, w, b = conv_tensors(29, N, C, H, W, K, R)
+    relu = bool((N + K) % 2)
+    ref = oracle.conv2d(x, w, b, stride, pad, relu)
+    for tile in (-1, 7, 8, 9, 10, 3):
+        got, _ = gpu_conv(part, x, w, b, stride, pad, relu, tile=tile)
+        whole, per_img = oracle.rel_err(got, ref)
+        assert max(whole, per_img) <= LAYER_TOL, (tile, whole, per_img)
