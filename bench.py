@@ -34,7 +34,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build measures one GPU only (gpu-lets partition a single device and "
+        sys.exit("bench.py: this benchmark measures one GPU only (gpu-lets partition a single device and "
                  "never exchange data); run with --gpus 1")
 
     import numpy as np
