@@ -171,6 +171,21 @@ gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, const float *b,
                                    int y_ch_offset, void *stream);
 
 /*
+ * Same as gpulet_conv2d_fwd_ex for an input that is a channel slice of a wider
+ * tensor: the layer reads x[((n*H+h)*W+w)*x_ch_stride + x_ch_offset + c] for
+ * c < C (x_ch_stride 0 means C).  Used when several layers that read the same
+ * tensor are computed as one layer and their consumers each take a slice of the
+ * result (the two reduce layers of an inception block).  Only the gathering
+ * tiles 0..6 read slices; another forced tile falls back as documented at
+ * gpulet_set_conv_tile.  Results have the bits of the same layer on a dense copy
+ * of the slice.  Extra error: x_ch_offset < 0 or x_ch_offset + C > x_ch_stride.
+ */
+gpulet_status gpulet_conv2d_fwd_slices(const void *x, const void *w, const float *b, void *y, int N,
+                                       int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                       int relu, const void *residual, int x_ch_stride, int x_ch_offset,
+                                       int y_ch_stride, int y_ch_offset, void *stream);
+
+/*
  * Pooling branch of an inception block (GoogLeNet of Table 4) in one kernel:
  *   y = act(b + conv1x1(maxpool(x, window 3x3, stride 1, pad 1), w))
  * with the pool's maximum taken over in-image taps only, as in gpulet_pool.
@@ -288,6 +303,9 @@ typedef struct gpulet_layer {
     int32_t out_fp32;      /* FC: store fp32 instead of bf16 */
     int32_t pre_pool;      /* CONV: 0, or 3 = a 3x3 / stride 1 / pad 1 max pool of in_buf comes first
                               (gpulet_maxpool3_conv1x1_fwd; 1x1 filters, stride 1, pad 0, C % 8 == 0) */
+    int32_t in_ch_total;   /* CONV: channels of in_buf when this layer reads only C of them (the
+                              output of several layers computed as one); 0 means C */
+    int32_t in_ch_offset;  /* CONV: first channel read */
     const void *w;         /* device: CONV KRSC bf16, DWCONV RSC bf16, FC [Out][In] bf16 */
     const float *b;        /* device: fp32 bias or NULL */
 } gpulet_layer;

@@ -38,20 +38,25 @@ gpulet_status check_conv(const ConvArgs &a) {
     if (a.y_ch_offset < 0 || a.y_ch_offset + a.K > a.y_ch_stride) return GPULET_EINVAL;
     if (a.pre_pool != 0 && (a.pre_pool != 3 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % 8 != 0))
         return GPULET_EINVAL;
+    const int ldx = a.x_ch_stride ? a.x_ch_stride : a.C;
+    if (a.x_ch_offset < 0 || a.x_ch_offset + a.C > ldx) return GPULET_EINVAL;
+    if (ldx != a.C && a.pre_pool) return GPULET_EINVAL;
     // Byte offsets are 32-bit with the top bit reserved as the out-of-range marker.
     const long long lim = 1LL << 30;
-    const long long xe = 1LL * a.N * a.H * a.W * a.C;
+    const long long xe = 1LL * a.N * a.H * a.W * ldx;
     const long long we = 1LL * a.K * a.R * a.S * a.C;
     const long long ye = 1LL * a.N * a.P * a.Q * a.y_ch_stride;
     // The gather indexes from (h, w) = (-pad, -pad) and may step past the last tap.
-    const long long slack = (1LL * (a.pad + a.R) * a.W + a.pad + a.S) * a.C + 64;
+    const long long slack = (1LL * (a.pad + a.R) * a.W + a.pad + a.S) * ldx + 64;
     if (xe + slack >= lim || we + 64 >= lim || ye >= lim) return GPULET_EINVAL;
     return GPULET_OK;
 }
 
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream) {
     ConvParams p;
-    p.x = static_cast<const __bf16 *>(a.x);
+    p.ldx = a.x_ch_stride ? a.x_ch_stride : a.C;
+    const bool dense = p.ldx == a.C;
+    p.x = static_cast<const __bf16 *>(a.x) + a.x_ch_offset;
     p.w = static_cast<const __bf16 *>(a.w);
     p.b = a.b;
     p.y = static_cast<__bf16 *>(a.y);
@@ -63,7 +68,8 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.ldy = a.y_ch_stride;
     p.y_off = a.y_ch_offset;
     p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
-    p.x_bytes = static_cast<unsigned>(2LL * a.N * a.H * a.W * a.C);
+    // up to the last channel the layer reads of the last pixel
+    p.x_bytes = static_cast<unsigned>(2LL * ((1LL * a.N * a.H * a.W - 1) * p.ldx + a.C));
     p.w_bytes = static_cast<unsigned>(2LL * a.K * a.R * a.S * a.C);
     p.tap_inner = (a.C % BK == 0 && a.R * a.S > 1) ? 1 : 0;
     p.vec_store = (a.y_ch_stride % 8 == 0 && a.y_ch_offset % 8 == 0 && reinterpret_cast<uintptr_t>(a.y) % 16 == 0 &&
@@ -83,12 +89,12 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.d_s = make_fastdiv(a.S);
     p.d_tiles_n = p.d_split_k = p.d_tw = p.d_ncb = p.d_pwt = p.d_hp = make_fastdiv(1);
 
-    const bool vec = (a.C % CHUNK == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0) &&
+    const bool vec = (a.C % CHUNK == 0) && (p.ldx % CHUNK == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
     if (a.pre_pool) {
         // checked by check_conv: 3x3 window, 1x1 filter, stride 1, no padding, C % 8 == 0; the
         // callers check the 16-byte alignment of x and w
-        if (!vec) return hipErrorInvalidValue;
+        if (!vec || !dense) return hipErrorInvalidValue;
         return launch_pooled_conv(p, stream);
     }
 

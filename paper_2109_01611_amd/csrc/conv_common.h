@@ -33,6 +33,8 @@ struct ConvParams {
     int N, C, H, W, K, R, S, stride, pad, relu, P, Q;
     int M, Kg;          // GEMM rows and depth
     int ldy, y_off;     // channels per output pixel of the destination, first channel
+    int ldx;            // channels per input pixel as stored (x points at the layer's first channel);
+                        // only the gathering kernels accept ldx != C
     int tiles_n, n_tiles, tiles_per_xcd;
     unsigned x_bytes, w_bytes;
     int tap_inner;      // depth order: 64-channel block outermost, filter taps inside it

@@ -140,7 +140,7 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
                 const int pp = fdiv(pq, p.d_q), qq = pq - pp * p.Q;
                 a_h0[i] = pp * p.stride - p.pad;
                 a_w0[i] = qq * p.stride - p.pad;
-                a_off[i] = (((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C) * 2;
+                a_off[i] = (((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.ldx) * 2;
             } else {
                 a_h0[i] = -(1 << 28);  // fails every bounds test
                 a_w0[i] = -(1 << 28);
@@ -156,9 +156,11 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
 
         // Depth position of the chunk this lane fetches next: element index g, its
         // filter tap (r, s), channel c, and the tap's byte offset inside the image.
-        // Advancing s by one and c by -C leaves the address unchanged (a filter row
-        // covers a contiguous span of the image row), so the offset only jumps when
-        // the filter moves to its next row.
+        // With dense pixels (ldx == C) advancing s by one and c by -C leaves the
+        // address unchanged (a filter row covers a contiguous span of the image row),
+        // so the offset only jumps when the filter moves to its next row; when the
+        // layer reads a channel slice of wider pixels it also skips ldx - C elements
+        // from one pixel to the next.
         //
         // Two depth orders.  Linear: g runs through (r, s, c) as the weights are
         // stored.  Tap-inner (C a multiple of 64, filter larger than 1x1): for each
@@ -175,22 +177,23 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
             cblk = cb * BK;
             c = cblk + cc * CHUNK;
             g = t * p.C + c;
-            tap = ((r * p.W + s) * p.C + c) * 2;
+            tap = ((r * p.W + s) * p.ldx + c) * 2;
         } else {
             g = k_first * BK + cc * CHUNK;
             const int t = fdiv(g, p.d_c);
             c = g - t * p.C;
             r = fdiv(t, p.d_s);
             s = t - r * p.S;
-            tap = ((r * p.W + s) * p.C + c) * 2;
+            tap = ((r * p.W + s) * p.ldx + c) * 2;
         }
         auto normalise = [&]() {
             while (c >= p.C) {
                 c -= p.C;
+                tap += (p.ldx - p.C) * 2;  // nothing when the pixels are dense
                 if (++s == p.S) {
                     s = 0;
                     ++r;
-                    tap += (p.W - p.S) * p.C * 2;
+                    tap += (p.W - p.S) * p.ldx * 2;
                 }
             }
         };
@@ -217,10 +220,10 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
             ++issued;
             if (!POINTWISE && p.tap_inner) {
                 g += p.C;
-                tap += p.C * 2;
+                tap += p.ldx * 2;
                 if (++s == p.S) {
                     s = 0;
-                    tap += (p.W - p.S) * p.C * 2;
+                    tap += (p.W - p.S) * p.ldx * 2;
                     if (++r == p.R) {
                         r = 0;
                         cblk += BK;
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_any_kernel(const ConvPara
             const int pp = pq / p.Q, qq = pq - pp * p.Q;
             a_h0[i] = pp * p.stride - p.pad;
             a_w0[i] = qq * p.stride - p.pad;
-            a_base[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C;
+            a_base[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.ldx;
         } else {
             a_h0[i] = -(1 << 28);
             a_w0[i] = -(1 << 28);
@@ -464,7 +467,7 @@ __global__ __launch_bounds__(NTHREADS) void conv_igemm_any_kernel(const ConvPara
 #pragma unroll
         for (int e = 0; e < CHUNK; ++e) {
             const bool g_ok = g0 + e < p.Kg;
-            const int tap = (r * p.W + s) * p.C + c;
+            const int tap = (r * p.W + s) * p.ldx + c;
 #pragma unroll
             for (int i = 0; i < AROWS; ++i) {
                 const bool ok = g_ok && (unsigned)(a_h0[i] + r) < (unsigned)p.H &&

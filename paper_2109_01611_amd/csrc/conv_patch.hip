@@ -492,7 +492,7 @@ bool patch_geometry(const ConvParams &p, int *tw_out) {
 }  // namespace
 
 bool patch_eligible(const ConvParams &p, bool vec, int *tw_out) {
-    return vec && p.R == 3 && p.S == 3 && p.stride == 1 && p.pad == 1 && p.C % BK == 0 && p.P == p.H &&
+    return vec && p.ldx == p.C && p.R == 3 && p.S == 3 && p.stride == 1 && p.pad == 1 && p.C % BK == 0 && p.P == p.H &&
            p.Q == p.W && patch_geometry(p, tw_out);
 }
 

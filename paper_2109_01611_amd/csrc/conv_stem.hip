@@ -299,7 +299,7 @@ hipError_t launch_stem_r(const ConvParams &p, int n_cu, int tiles_m, int tiles_q
 // The stem kernel: at most four channels, a filter row of at most eight pixels, 3, 5 or 7
 // filter rows, a tile's input patch within the staged limit, 16-byte stores possible, no residual.
 bool stem_applicable(const ConvParams &p) {
-    if (p.C > 4 || p.S > 8 || !(p.R == 3 || p.R == 5 || p.R == 7)) return false;
+    if (p.C > 4 || p.ldx != p.C || p.S > 8 || !(p.R == 3 || p.R == 5 || p.R == 7)) return false;
     if (!p.vec_store || p.K % 8 != 0 || p.res) return false;
     if (p.C == 4 && reinterpret_cast<uintptr_t>(p.x) % 8 != 0) return false;  // 8-byte pixel loads
     const int krow = p.S <= 4 ? 16 : 32;

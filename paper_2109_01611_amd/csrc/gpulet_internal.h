@@ -82,6 +82,9 @@ struct ConvArgs {
     const void *residual;
     int N, C, H, W, K, R, S, stride, pad, relu, P, Q, y_ch_stride, y_ch_offset;
     int pre_pool = 0;  // 3: a 3x3 / stride 1 / pad 1 max pool is applied to x first (1x1 filters only)
+    // The layer reads channels [x_ch_offset, x_ch_offset + C) of pixels that hold x_ch_stride
+    // channels (0: the pixels hold exactly C).
+    int x_ch_stride = 0, x_ch_offset = 0;
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 void set_conv_tile(int tile);

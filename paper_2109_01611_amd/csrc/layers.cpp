@@ -38,6 +38,22 @@ extern "C" gpulet_status gpulet_conv2d_fwd_ex(const void *x, const void *w, cons
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_conv2d_fwd_slices(const void *x, const void *w, const float *b, void *y, int N,
+                                                  int C, int H, int W, int K, int R, int S, int stride,
+                                                  int pad, int relu, const void *residual, int x_ch_stride,
+                                                  int x_ch_offset, int y_ch_stride, int y_ch_offset,
+                                                  void *stream) {
+    ConvArgs a;
+    a.x_ch_stride = x_ch_stride;
+    a.x_ch_offset = x_ch_offset;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual,
+                                      y_ch_stride, y_ch_offset);
+    if (st != GPULET_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv(a, stream_ctx(s), s));
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const float *b, void *y, int N,
                                                      int C, int H, int W, int K, int relu, int y_ch_stride,
                                                      int y_ch_offset, void *stream) {

@@ -164,7 +164,8 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         s.record = false;
         int oc = 0, oh = 0, ow = 0, oelem = 2;
         if (L.op == GPULET_OP_CONV) {
-            if (L.C != src.C || !L.w) return GPULET_EINVAL;
+            // in_ch_total > 0: the layer reads L.C channels from in_ch_offset on of wider pixels
+            if ((L.in_ch_total > 0 ? L.in_ch_total : L.C) != src.C || !L.w) return GPULET_EINVAL;
             if (L.stride < 1 || L.R < 1 || L.S < 1 || L.pad < 0) return GPULET_EINVAL;
             ConvArgs &a = s.conv;
             a.x = nullptr; a.w = L.w; a.b = L.b; a.y = nullptr; a.residual = nullptr;
@@ -176,6 +177,8 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
             a.y_ch_stride = L.out_ch_total > 0 ? L.out_ch_total : L.K;
             a.y_ch_offset = L.out_ch_total > 0 ? L.out_ch_offset : 0;
             s.slice = L.out_ch_total > 0;
+            a.x_ch_stride = L.in_ch_total > 0 ? L.in_ch_total : 0;
+            a.x_ch_offset = L.in_ch_total > 0 ? L.in_ch_offset : 0;
             // Pointers are filled in at run time; validate the rest with stand-ins.
             ConvArgs chk = a;
             chk.x = chk.w = chk.y = &chk;

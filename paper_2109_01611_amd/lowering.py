@@ -53,7 +53,7 @@ class DeviceModel:
     ``reuse=False`` gives every tensor its own buffer so intermediates can be
     read back after a run."""
 
-    def __init__(self, model, params, device="cuda:0", reuse=True, fuse_pools=False):
+    def __init__(self, model, params, device="cuda:0", reuse=True, fuse_pools=False, merge_siblings=True):
         self.model = model
         self.device = torch.device(device)
         self.in_shape = tuple(model.in_shape)
@@ -117,6 +117,86 @@ class DeviceModel:
                     nd = nd._replace(src=moved[nd.src], attr=dict(a, pre_pool=3))
                 kept.append(nd)
             nodes = kept
+        # With ``merge_siblings`` convolutions that read the same tensor run as ONE convolution over
+        # their concatenated filters where the result can be used in place:
+        #   * plain 1x1 convolutions that feed only other convolutions (the two reduce layers of an
+        #     inception block): each consumer reads its channel slice of the merged result;
+        #   * convolutions of equal geometry that store into adjacent slices of the same
+        #     concatenated tensor (the box and class heads of an SSD feature map): the merged
+        #     layer stores the combined slice.
+        # Every output element is the same sum in the same order, so the bits do not change;
+        # ``merged`` lists the groups.
+        self.merged = []
+        if merge_siblings:
+            readers = {}
+            for nd in nodes:
+                reads = list(nd.src) if nd.op == "concat" else [nd.src]
+                if nd.op == "conv" and nd.attr["residual"]:
+                    reads.append(nd.attr["residual"])
+                for t in reads:
+                    readers.setdefault(t, []).append(nd)
+            sliced, stored = {}, {}
+            for nd in nodes:
+                a = nd.attr
+                if nd.op != "conv" or a["residual"] or a.get("pre_pool") or nd.src == "x" or nd.dst == model.out:
+                    continue
+                rs = readers.get(nd.dst, [])
+                geom = (a["k"], a["stride"], a["pad"], bool(a["relu"]))
+                if nd.dst in alias:
+                    if len(rs) == 1 and rs[0].op == "concat":
+                        stored.setdefault((nd.src, alias[nd.dst][0]) + geom, []).append(nd)
+                elif (geom[:3] == (1, 1, 0) and a["K"] % 8 == 0 and rs
+                      and all(r.op == "conv" and r.src == nd.dst and r.attr["residual"] != nd.dst for r in rs)):
+                    sliced.setdefault((nd.src,) + geom, []).append(nd)
+            in_slice, first, dropped, renamed = {}, {}, set(), {}
+
+            def merge(g):
+                name = "+".join(n.name for n in g)
+                first[g[0].name] = g[0]._replace(name=name, dst=name, attr=dict(
+                    g[0].attr, K=sum(n.attr["K"] for n in g), parts=[n.name for n in g]))
+                dropped.update(n.name for n in g)
+                chans[name] = sum(n.attr["K"] for n in g)
+                self.merged.append([n.name for n in g])
+                return name
+
+            for g in sliced.values():
+                if len(g) >= 2:
+                    name, off = merge(g), 0
+                    for n in g:
+                        in_slice[n.dst] = (name, off, chans[name])
+                        off += n.attr["K"]
+            for g in stored.values():
+                g.sort(key=lambda n: alias[n.dst][1])
+                runs = [[g[0]]]
+                for n in g[1:]:
+                    last = runs[-1][-1]
+                    if alias[n.dst][1] == alias[last.dst][1] + last.attr["K"]:
+                        runs[-1].append(n)
+                    else:
+                        runs.append([n])
+                for run in runs:
+                    if len(run) >= 2:
+                        cat, off, total = alias[run[0].dst]
+                        name = merge(run)
+                        for n in run:
+                            del alias[n.dst]
+                            renamed[n.dst] = None
+                        renamed[run[0].dst] = name
+                        alias[name] = (cat, off, total)
+            kept = []
+            for nd in nodes:
+                if nd.name in first:
+                    kept.append(first[nd.name])
+                elif nd.name in dropped:
+                    continue
+                elif nd.op == "conv" and nd.src in in_slice:
+                    t, off, total = in_slice[nd.src]
+                    kept.append(nd._replace(src=t, attr=dict(nd.attr, in_slice=(off, total))))
+                elif nd.op == "concat":
+                    kept.append(nd._replace(src=[renamed.get(t, t) for t in nd.src if renamed.get(t, t) is not None]))
+                else:
+                    kept.append(nd)
+            nodes = kept
         producers = {nd.dst: nd for nd in nodes}
         for s in alias:
             if producers[s].op != "conv":
@@ -156,7 +236,11 @@ class DeviceModel:
                 raise ValueError("reading a concat slice on its own is not supported")
             a = nd.attr
             if nd.op == "conv":
-                w, b = params[nd.name]
+                if "parts" in a:
+                    w = np.concatenate([np.asarray(params[n][0]) for n in a["parts"]], axis=0)
+                    b = np.concatenate([np.asarray(params[n][1]) for n in a["parts"]], axis=0)
+                else:
+                    w, b = params[nd.name]
                 C = a["C"]
                 if nd.src == "x" and self.in_pad:
                     w = np.pad(np.asarray(w), ((0, 0), (0, self.in_pad), (0, 0), (0, 0)))
@@ -167,6 +251,8 @@ class DeviceModel:
                 L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, C, a["K"], a["k"], a["k"]
                 L.stride, L.pad, L.relu = a["stride"], a["pad"], int(a["relu"])
                 L.pre_pool = a.get("pre_pool", 0)
+                if "in_slice" in a:
+                    L.in_ch_offset, L.in_ch_total = a["in_slice"]
                 if a["residual"]:
                     L.res_buf = buf_of[storage(a["residual"])]
                 if nd.dst in alias:

@@ -121,6 +121,10 @@ def test_layer_calls_reject_bad_arguments_before_touching_the_gpu():
             gpulet.conv2d_fwd(*args, **ok)
     with pytest.raises(gpulet.GpuletError):   # slice does not fit the destination
         gpulet.conv2d_fwd_ex(x, w, None, y, residual=None, y_ch_stride=12, y_ch_offset=8, **ok)
+    for xs, xo in ((12, 8), (16, -8), (4, 0)):   # slice does not fit the source pixels
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.conv2d_fwd_slices(x, w, None, y, residual=None, x_ch_stride=xs, x_ch_offset=xo, **ok)
+        assert e.value.status == gpulet.EINVAL
     with pytest.raises(gpulet.GpuletError):
         gpulet.pool(x, y, 1, 8, 8, 8, gpulet.POOL_MAX, k=2, stride=2, pad=2)    # pad >= k
     with pytest.raises(gpulet.GpuletError):
@@ -212,6 +216,15 @@ def test_model_description_errors():
     bad([good], batch=0)
     bad([good], in_buf=1, out_buf=1)
     bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])
+    # a layer reading a channel slice: the stated pixel width must be the source's, the slice inside it
+    reduce_ = _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=24, R=1, S=1, stride=1, pad=0, w=W)
+    take = dict(op=gpulet.OP_CONV, in_buf=2, out_buf=1, C=8, K=8, R=3, S=3, stride=1, pad=1, w=W)
+    assert gpulet.model_workspace_bytes(_desc([reduce_, _layer(in_ch_total=24, in_ch_offset=16, **take)], 3,
+                                              (3, 8, 8)), 2) == 2 * 24 * 8 * 8 * 2
+    bad([reduce_, _layer(**take)])
+    bad([reduce_, _layer(in_ch_total=32, in_ch_offset=16, **take)])
+    bad([reduce_, _layer(in_ch_total=24, in_ch_offset=17, **take)])
+    bad([reduce_, _layer(in_ch_total=24, in_ch_offset=-1, **take)])
     # residual of the wrong shape
     bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=2, pad=1, w=W),
          _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])

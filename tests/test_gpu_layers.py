@@ -139,6 +139,61 @@ def test_maxpool_fused_conv_rejects_what_it_cannot_run(part):
     assert e.value.status == gpulet.EINVAL
 
 
+# N, channels per stored pixel, first channel read, C, H, W, K, R, stride, pad
+SLICE_CASES = [
+    (3, 112, 0, 96, 28, 28, 128, 3, 1, 1),     # inception 3a: 3x3 over the first 96 of 112 channels
+    (3, 112, 96, 16, 28, 28, 32, 5, 1, 2),     # ... and the 5x5 over the last 16: four taps per depth slice
+    (2, 224, 64, 128, 14, 14, 200, 3, 1, 1),   # C a multiple of 64: taps innermost
+    (2, 160, 32, 64, 9, 11, 72, 1, 1, 0),      # 1x1 filter
+    (2, 40, 8, 24, 13, 13, 40, 3, 2, 1),       # stride 2, three taps per slice
+    (2, 21, 5, 9, 10, 10, 20, 3, 1, 1),        # nothing aligned: element-wise gather
+    (1, 64, 24, 40, 7, 7, 16, 5, 1, 2),        # a tap straddles depth slices
+]
+
+
+@pytest.mark.parametrize("case", SLICE_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_reading_a_channel_slice(part, case):
+    N, ldx, off, C, H, W, K, R, stride, pad = case
+    tag = "sl/" + "_".join(map(str, case))
+    wide = inputs.tensor(31, tag + "x", (N, ldx, H, W), "normal")
+    w = inputs.he_normal(31, tag + "w", (K, C, R, R))
+    b = inputs.bias(31, tag + "b", K)
+    x = np.ascontiguousarray(wide[:, off:off + C])
+    ref = oracle.conv2d(x, w, b, stride, pad, True)
+    _, dense = gpu_conv(part, x, w, b, stride, pad, True)
+    P, Q = ref.shape[2], ref.shape[3]
+    xd = lowering.nchw_to_nhwc(wide, DEV)
+    wd = lowering.kcrs_to_krsc(w, DEV)
+    bd = torch.from_numpy(b).to(DEV)
+    ct, co = K + 16, 8
+    for tile in range(-1, 11):
+        yd = torch.full((N, P, Q, ct), -512.0, dtype=torch.bfloat16, device=DEV)
+        torch.cuda.synchronize()
+        gpulet.set_conv_tile(tile)
+        try:
+            gpulet.conv2d_fwd_slices(xd, wd, bd, yd, N, C, H, W, K, R, R, stride, pad, True, None, ldx, off, ct, co,
+                                     part.stream)
+            part.sync()
+        finally:
+            gpulet.set_conv_tile(-1)
+        got = lowering.nhwc_to_nchw(yd[..., co:co + K])
+        assert oracle.rel_err(got, ref)[1] <= LAYER_TOL, tile
+        # the bits of the same layer on a dense copy of the slice, and nothing written outside the slice
+        assert torch.equal(yd[..., co:co + K], dense), tile
+        assert bool((yd[..., :co] == -512.0).all()) and bool((yd[..., co + K:] == -512.0).all()), tile
+
+
+def test_conv_slice_arguments_are_checked(part):
+    x = torch.zeros((1, 4, 4, 32), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((8, 1, 1, 16), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros((1, 4, 4, 8), dtype=torch.bfloat16, device=DEV)
+    for stride_, off in ((32, 24), (32, -8), (8, 0)):
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.conv2d_fwd_slices(x, w, None, y, 1, 16, 4, 4, 8, 1, 1, 1, 0, True, None, stride_, off, 0, 0,
+                                     part.stream)
+        assert e.value.status == gpulet.EINVAL
+
+
 # N, H, W, K: 3x3, stride 1, pad 1, exactly 64 input channels -> weights resident in registers (tile 10)
 C64_CASES = [
     (3, 14, 14, 64),        # whole rows per block; M = 588: ragged last tile, fewer tiles than workgroups

@@ -204,6 +204,41 @@ def test_inception_pool_branches_run_inside_their_projection():
     _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(3, -1), ref)
 
 
+@pytest.mark.parametrize("width_div,in_hw,groups", [(2, 96, 7), (1, 224, 9)])
+def test_inception_reduce_layers_run_as_one_convolution(width_div, in_hw, groups):
+    # at half width two blocks have a reduce layer whose filter count is not a multiple of 8: left alone
+    model = workloads.googlenet(width_div=width_div, in_hw=in_hw, n_class=20)
+    params = workloads.parameters(model, 11)
+    x = workloads.batch_input(model, 2, 11)
+    merged = lowering.DeviceModel(model, params, DEV, merge_siblings=True)
+    plain = lowering.DeviceModel(model, params, DEV, merge_siblings=False)
+    assert len(merged.merged) == groups and all(len(g) == 2 for g in merged.merged) and not plain.merged
+    assert merged.desc.n_layers == plain.desc.n_layers - groups
+    with gpulet.Partition(0, 100, 0) as p:
+        a, _ = merged.run(p, merged.input_to_device(x))
+        b, _ = plain.run(p, plain.input_to_device(x))
+    assert torch.equal(a, b)            # merging does not change a bit
+    ref = oracle.run_model(model, params, x).reshape(2, -1)
+    _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(2, -1), ref)
+
+
+def test_ssd_box_and_class_heads_run_as_one_convolution():
+    model = workloads.ssd_mobilenet(width_div=4, in_hw=128, n_class=5)
+    params = workloads.parameters(model, 12)
+    x = workloads.batch_input(model, 3, 12)
+    merged = lowering.DeviceModel(model, params, DEV, reuse=False, merge_siblings=True)
+    plain = lowering.DeviceModel(model, params, DEV, reuse=False, merge_siblings=False)
+    assert merged.merged == [["box%d" % m, "cls%d" % m] for m in range(1, 7)] and not plain.merged
+    with gpulet.Partition(0, 100, 0) as p:
+        a, _ = merged.run(p, merged.input_to_device(x))
+        b, _ = plain.run(p, plain.input_to_device(x))
+    assert torch.equal(a, b)
+    for m in range(1, 6):               # the heads of the larger maps stay in the workspace
+        assert torch.equal(merged.read_tensor("head%d" % m, 3), plain.read_tensor("head%d" % m, 3)), m
+    ref = oracle.run_model(model, params, x).reshape(3, -1)
+    _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(3, -1), ref)
+
+
 def test_batch_size_does_not_change_an_images_result():
     # default: no depth splitting, so an image's logits are independent of its batch and gpu-let
     model = workloads.resnet50(width_div=2, in_hw=96, n_class=50)
