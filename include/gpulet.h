@@ -186,6 +186,26 @@ gpulet_status gpulet_conv2d_fwd_slices(const void *x, const void *w, const float
                                        int y_ch_stride, int y_ch_offset, void *stream);
 
 /*
+ * A 1x1 convolution (pad 0) whose filters are stored to two tensors: filters
+ * [0, k2) to y and filters [k2, K) to y2, each optionally as a channel slice of
+ * wider pixels (y_ch_stride / y_ch_offset and y2_ch_stride / y2_ch_offset, 0 =
+ * dense), the input optionally a slice too (as gpulet_conv2d_fwd_slices).  One
+ * launch then serves layers that read the same tensor but whose results live in
+ * different places: in an inception block the 1x1 branch, which belongs to the
+ * concatenated output, and the two reduce layers, whose result feeds the 3x3 and
+ * 5x5 layers.  w: K*C bf16 and b: K fp32 hold the filters of both parts in order.
+ * Each output element has the bits gpulet_conv2d_fwd_ex gives for its filter.
+ * Errors: those of gpulet_conv2d_fwd_ex; GPULET_EINVAL unless 0 < k2 < K and
+ * y2 is not NULL, or when a slice does not fit its pixels; C must be a multiple
+ * of 8 and x, w 16-byte aligned (GPULET_EINVAL otherwise).
+ */
+gpulet_status gpulet_conv1x1_fwd_two_outputs(const void *x, const void *w, const float *b, void *y,
+                                             void *y2, int N, int C, int H, int W, int K, int k2,
+                                             int stride, int relu, int x_ch_stride, int x_ch_offset,
+                                             int y_ch_stride, int y_ch_offset, int y2_ch_stride,
+                                             int y2_ch_offset, void *stream);
+
+/*
  * Pooling branch of an inception block (GoogLeNet of Table 4) in one kernel:
  *   y = act(b + conv1x1(maxpool(x, window 3x3, stride 1, pad 1), w))
  * with the pool's maximum taken over in-image taps only, as in gpulet_pool.
@@ -306,6 +326,12 @@ typedef struct gpulet_layer {
     int32_t in_ch_total;   /* CONV: channels of in_buf when this layer reads only C of them (the
                               output of several layers computed as one); 0 means C */
     int32_t in_ch_offset;  /* CONV: first channel read */
+    int32_t K2;            /* CONV, 1x1 filters without residual: when > 0 the last K2 of the K filters are
+                              stored to out2_buf and only the first K - K2 to out_buf (several layers
+                              that read one tensor computed as one; see gpulet_conv1x1_fwd_two_outputs) */
+    int32_t out2_buf;      /* CONV with K2 > 0: second buffer written */
+    int32_t out2_ch_total; /* CONV with K2 > 0: channels of out2_buf when a slice is written; 0 means K2 */
+    int32_t out2_ch_offset;/* CONV with K2 > 0: first channel written in out2_buf */
     const void *w;         /* device: CONV KRSC bf16, DWCONV RSC bf16, FC [Out][In] bf16 */
     const float *b;        /* device: fp32 bias or NULL */
 } gpulet_layer;

@@ -35,7 +35,13 @@ gpulet_status check_conv(const ConvArgs &a) {
         a.pad < 0)
         return GPULET_EINVAL;
     if (a.P < 1 || a.Q < 1) return GPULET_EINVAL;
-    if (a.y_ch_offset < 0 || a.y_ch_offset + a.K > a.y_ch_stride) return GPULET_EINVAL;
+    if (a.y2) {
+        if (a.k2 < 1 || a.k2 >= a.K || a.R != 1 || a.S != 1 || a.pad != 0 || a.residual || a.pre_pool)
+            return GPULET_EINVAL;
+        if (a.y2_ch_offset < 0 || a.y2_ch_offset + (a.K - a.k2) > a.y2_ch_stride) return GPULET_EINVAL;
+        if (1LL * a.N * a.P * a.Q * a.y2_ch_stride >= (1LL << 30)) return GPULET_EINVAL;
+    }
+    if (a.y_ch_offset < 0 || a.y_ch_offset + (a.y2 ? a.k2 : a.K) > a.y_ch_stride) return GPULET_EINVAL;
     if (a.pre_pool != 0 && (a.pre_pool != 3 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % 8 != 0))
         return GPULET_EINVAL;
     const int ldx = a.x_ch_stride ? a.x_ch_stride : a.C;
@@ -67,6 +73,10 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.Kg = a.R * a.S * a.C;
     p.ldy = a.y_ch_stride;
     p.y_off = a.y_ch_offset;
+    p.y2 = static_cast<__bf16 *>(a.y2);
+    p.k2 = a.y2 ? a.k2 : a.K;
+    p.ldy2 = a.y2_ch_stride;
+    p.y2_off = a.y2_ch_offset;
     p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
     // up to the last channel the layer reads of the last pixel
     p.x_bytes = static_cast<unsigned>(2LL * ((1LL * a.N * a.H * a.W - 1) * p.ldx + a.C));
@@ -74,7 +84,9 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.tap_inner = (a.C % BK == 0 && a.R * a.S > 1) ? 1 : 0;
     p.vec_store = (a.y_ch_stride % 8 == 0 && a.y_ch_offset % 8 == 0 && reinterpret_cast<uintptr_t>(a.y) % 16 == 0 &&
                    reinterpret_cast<uintptr_t>(a.b) % 16 == 0 &&
-                   (!a.residual || (a.K % 8 == 0 && reinterpret_cast<uintptr_t>(a.residual) % 16 == 0)))
+                   (!a.residual || (a.K % 8 == 0 && reinterpret_cast<uintptr_t>(a.residual) % 16 == 0)) &&
+                   (!a.y2 || (a.k2 % 8 == 0 && a.y2_ch_stride % 8 == 0 && a.y2_ch_offset % 8 == 0 &&
+                              reinterpret_cast<uintptr_t>(a.y2) % 16 == 0)))
                       ? 1
                       : 0;
     p.split_k = 1;
@@ -91,6 +103,7 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
 
     const bool vec = (a.C % CHUNK == 0) && (p.ldx % CHUNK == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
+    if (a.y2 && !vec) return hipErrorInvalidValue;  // only the 16-byte gathering kernels store to two tensors
     if (a.pre_pool) {
         // checked by check_conv: 3x3 window, 1x1 filter, stride 1, no padding, C % 8 == 0; the
         // callers check the 16-byte alignment of x and w

@@ -33,6 +33,10 @@ struct ConvParams {
     int N, C, H, W, K, R, S, stride, pad, relu, P, Q;
     int M, Kg;          // GEMM rows and depth
     int ldy, y_off;     // channels per output pixel of the destination, first channel
+    // Second destination (1x1 gathering kernels only): filters k >= k2 are stored to
+    // y2[m * ldy2 + y2_off + k - k2] instead; k2 == K means there is none.
+    __bf16 *y2;
+    int k2, ldy2, y2_off;
     int ldx;            // channels per input pixel as stored (x points at the layer's first channel);
                         // only the gathering kernels accept ldx != C
     int tiles_n, n_tiles, tiles_per_xcd;
@@ -122,7 +126,7 @@ __device__ __forceinline__ BiasRegs load_bias(const ConvParams &p, int n0) {
     return r;
 }
 
-template <int BM, int BN, int NTHR, typename PixelOf>
+template <int BM, int BN, int NTHR, bool DUAL = false, typename PixelOf>
 __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *stg, int n0, const BiasRegs &br,
                                             PixelOf pixel_of) {
     constexpr int LDT = BN + 8;
@@ -140,13 +144,19 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
         const int c = threadIdx.x % BN, kc = n0 + c;
         if (kc >= p.K) return;
         const float bias1 = p.b ? p.b[kc] : 0.f;
+        __bf16 *yb = p.y + p.y_off + kc;
+        int ld = p.ldy;
+        if (DUAL && kc >= p.k2) {
+            yb = p.y2 + p.y2_off + (kc - p.k2);
+            ld = p.ldy2;
+        }
         for (int row = threadIdx.x / BN; row < BM; row += ROWS) {
             const int m = pixel_of(row);
             if (m < 0) continue;
             float a = stg[row * LDT + c] + bias1;
             if (p.res) a += static_cast<float>(p.res[m * p.K + kc]);
             if (p.relu) a = a > 0.f ? a : 0.f;
-            p.y[m * p.ldy + p.y_off + kc] = static_cast<__bf16>(a);
+            yb[m * ld] = static_cast<__bf16>(a);
         }
         return;
     }
@@ -154,6 +164,13 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
     const int k = n0 + cv * 8;
     if (k >= p.K) return;
     {
+        // a thread keeps its 8 channels, so it also keeps its destination
+        __bf16 *yb = p.y + p.y_off + k;
+        int ld = p.ldy;
+        if (DUAL && k >= p.k2) {
+            yb = p.y2 + p.y2_off + (k - p.k2);
+            ld = p.ldy2;
+        }
         const float bias[8] = {br.lo.x, br.lo.y, br.lo.z, br.lo.w, br.hi.x, br.hi.y, br.hi.z, br.hi.w};
         const unsigned limit = relu_limit(p.relu);
         int m[ITEMS];
@@ -191,7 +208,7 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 pk[e] = relu_or_pass(pack_bf16(v[2 * e], v[2 * e + 1]), limit);
-            *reinterpret_cast<uint4 *>(p.y + (m[i] * p.ldy + p.y_off + k)) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            *reinterpret_cast<uint4 *>(yb + m[i] * ld) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
     }
 }

@@ -400,7 +400,9 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
         }
         // each thread re-reads only what it wrote itself, in the same iteration order
     }
-    finish_tile<BM, BN, NTHR>(p, stg, n0, bias_regs, [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
+    // only 1x1 layers are ever given a second destination
+    finish_tile<BM, BN, NTHR, POINTWISE>(p, stg, n0, bias_regs,
+                                         [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
 }
 
 // ---------------------------------------------------------------------------

@@ -85,6 +85,11 @@ struct ConvArgs {
     // The layer reads channels [x_ch_offset, x_ch_offset + C) of pixels that hold x_ch_stride
     // channels (0: the pixels hold exactly C).
     int x_ch_stride = 0, x_ch_offset = 0;
+    // Second destination (1x1 filters, no residual): when y2 is set, filters [k2, K) are stored to
+    // channels [y2_ch_offset, y2_ch_offset + K - k2) of y2's pixels (y2_ch_stride channels each)
+    // and only filters [0, k2) to y.
+    void *y2 = nullptr;
+    int k2 = 0, y2_ch_stride = 0, y2_ch_offset = 0;
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 void set_conv_tile(int tile);

@@ -54,6 +54,31 @@ extern "C" gpulet_status gpulet_conv2d_fwd_slices(const void *x, const void *w, 
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_conv1x1_fwd_two_outputs(const void *x, const void *w, const float *b, void *y,
+                                                        void *y2, int N, int C, int H, int W, int K, int k2,
+                                                        int stride, int relu, int x_ch_stride, int x_ch_offset,
+                                                        int y_ch_stride, int y_ch_offset, int y2_ch_stride,
+                                                        int y2_ch_offset, void *stream) {
+    if (!y2 || k2 < 1 || k2 >= K) return GPULET_EINVAL;
+    ConvArgs a;
+    a.x_ch_stride = x_ch_stride;
+    a.x_ch_offset = x_ch_offset;
+    a.y2 = y2;
+    a.k2 = k2;
+    a.y2_ch_stride = y2_ch_stride == 0 ? K - k2 : y2_ch_stride;
+    a.y2_ch_offset = y2_ch_offset;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, 1, 1, stride, 0, relu, nullptr,
+                                      y_ch_stride == 0 ? k2 : y_ch_stride, y_ch_offset);
+    if (st != GPULET_OK) return st;
+    const int ldx = x_ch_stride ? x_ch_stride : C;
+    if (C % 8 != 0 || ldx % 8 != 0 || x_ch_offset % 8 != 0 || reinterpret_cast<uintptr_t>(x) % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(w) % 16 != 0)
+        return GPULET_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv(a, stream_ctx(s), s));
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const float *b, void *y, int N,
                                                      int C, int H, int W, int K, int relu, int y_ch_stride,
                                                      int y_ch_offset, void *stream) {

@@ -27,12 +27,14 @@ struct BufState {
 struct Step {
     int op;
     int in_buf, out_buf, res_buf;
+    int out2_buf;   // CONV storing its last filters to a second buffer, else -1
     ConvArgs conv;  // CONV
     int N, C, H, W, P, Q, mode, k, k2, stride, pad;  // POOL (k); DWCONV (k x k2, relu)
     int In, Out, relu, out_fp32;                     // FC
     const void *w;
     const float *b;
     bool slice;             // CONV writing a channel slice of a wider (concatenated) tensor
+    bool slice2;            // the same for the second buffer
     int lane;               // stream of the gpu-let this layer runs on
     std::vector<int> wait;  // earlier layers on other lanes this one must wait for
     bool record;            // a later layer on another lane waits for this one
@@ -76,18 +78,22 @@ void assign_lanes(Plan &plan, int n_bufs, int n_lanes) {
         };
         reads(s.in_buf);
         if (s.res_buf >= 0) reads(s.res_buf);
-        Hazard &o = hz[static_cast<size_t>(s.out_buf)];
-        const bool joins = s.slice && o.sliced && o.readers.empty();  // another slice of the same tensor
-        if (joins) {
-            deps.insert(deps.end(), o.guard.begin(), o.guard.end());
-        } else {
-            o.guard = o.readers;
-            o.guard.insert(o.guard.end(), o.writers.begin(), o.writers.end());
-            deps.insert(deps.end(), o.guard.begin(), o.guard.end());
-            o.writers.clear();
-            o.readers.clear();
-            o.sliced = s.slice;
-        }
+        auto writes = [&](int buf, bool slice) {
+            Hazard &o = hz[static_cast<size_t>(buf)];
+            const bool joins = slice && o.sliced && o.readers.empty();  // another slice of the same tensor
+            if (joins) {
+                deps.insert(deps.end(), o.guard.begin(), o.guard.end());
+            } else {
+                o.guard = o.readers;
+                o.guard.insert(o.guard.end(), o.writers.begin(), o.writers.end());
+                deps.insert(deps.end(), o.guard.begin(), o.guard.end());
+                o.writers.clear();
+                o.readers.clear();
+                o.sliced = slice;
+            }
+        };
+        writes(s.out_buf, s.slice);
+        if (s.out2_buf >= 0) writes(s.out2_buf, s.slice2);
         std::sort(deps.begin(), deps.end());
         deps.erase(std::unique(deps.begin(), deps.end()), deps.end());
 
@@ -121,7 +127,8 @@ void assign_lanes(Plan &plan, int n_bufs, int n_lanes) {
         // this layer now reads and writes
         hz[static_cast<size_t>(s.in_buf)].readers.push_back(i);
         if (s.res_buf >= 0) hz[static_cast<size_t>(s.res_buf)].readers.push_back(i);
-        o.writers.push_back(i);
+        hz[static_cast<size_t>(s.out_buf)].writers.push_back(i);
+        if (s.out2_buf >= 0) hz[static_cast<size_t>(s.out2_buf)].writers.push_back(i);
     }
 }
 
@@ -157,6 +164,8 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         s.in_buf = L.in_buf;
         s.out_buf = L.out_buf;
         s.res_buf = -1;
+        s.out2_buf = -1;
+        s.slice2 = false;
         s.w = L.w;
         s.b = L.b;
         s.slice = false;
@@ -174,9 +183,23 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
             a.P = out_extent(src.H, L.R, L.stride, L.pad);
             a.Q = out_extent(src.W, L.S, L.stride, L.pad);
             a.pre_pool = L.pre_pool;
-            a.y_ch_stride = L.out_ch_total > 0 ? L.out_ch_total : L.K;
+            // K2 > 0: the last K2 filters are stored to out2_buf, the first K - K2 to out_buf
+            if (L.K2 < 0 || (L.K2 > 0 && L.K2 >= L.K)) return GPULET_EINVAL;
+            const int k1 = L.K - L.K2;
+            a.y_ch_stride = L.out_ch_total > 0 ? L.out_ch_total : k1;
             a.y_ch_offset = L.out_ch_total > 0 ? L.out_ch_offset : 0;
             s.slice = L.out_ch_total > 0;
+            if (L.K2 > 0) {
+                if (L.out2_buf < 0 || L.out2_buf >= m->n_bufs || L.out2_buf == m->in_buf ||
+                    L.out2_buf == L.in_buf || L.out2_buf == L.out_buf || L.res_buf >= 0)
+                    return GPULET_EINVAL;
+                a.y2 = &a;  // stand-in, filled in at run time
+                a.k2 = k1;
+                a.y2_ch_stride = L.out2_ch_total > 0 ? L.out2_ch_total : L.K2;
+                a.y2_ch_offset = L.out2_ch_total > 0 ? L.out2_ch_offset : 0;
+                s.out2_buf = L.out2_buf;
+                s.slice2 = L.out2_ch_total > 0;
+            }
             a.x_ch_stride = L.in_ch_total > 0 ? L.in_ch_total : 0;
             a.x_ch_offset = L.in_ch_total > 0 ? L.in_ch_offset : 0;
             // Pointers are filled in at run time; validate the rest with stand-ins.
@@ -192,6 +215,11 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
                 s.res_buf = L.res_buf;
             }
             oc = a.y_ch_stride; oh = a.P; ow = a.Q;
+            if (s.out2_buf >= 0) {
+                BufState &d2 = plan.bufs[static_cast<size_t>(s.out2_buf)];
+                d2.C = a.y2_ch_stride; d2.H = a.P; d2.W = a.Q; d2.elem = 2; d2.written = true;
+                d2.bytes_per_image = std::max(d2.bytes_per_image, static_cast<size_t>(2) * a.y2_ch_stride * a.P * a.Q);
+            }
         } else if (L.op == GPULET_OP_POOL) {
             if (L.C != src.C) return GPULET_EINVAL;
             int P = 0, Q = 0;
@@ -298,6 +326,7 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
             ConvArgs a = s.conv;
             a.x = bd.ptr(s.in_buf);
             a.y = bd.ptr(s.out_buf);
+            a.y2 = s.out2_buf >= 0 ? bd.ptr(s.out2_buf) : nullptr;
             a.residual = s.res_buf >= 0 ? bd.ptr(s.res_buf) : nullptr;
             e = launch_conv(a, ctx, stream);
         } else if (s.op == GPULET_OP_POOL) {

@@ -119,11 +119,14 @@ class DeviceModel:
             nodes = kept
         # With ``merge_siblings`` convolutions that read the same tensor run as ONE convolution over
         # their concatenated filters where the result can be used in place:
-        #   * plain 1x1 convolutions that feed only other convolutions (the two reduce layers of an
-        #     inception block): each consumer reads its channel slice of the merged result;
         #   * convolutions of equal geometry that store into adjacent slices of the same
         #     concatenated tensor (the box and class heads of an SSD feature map): the merged
-        #     layer stores the combined slice.
+        #     layer stores the combined slice;
+        #   * plain 1x1 convolutions that feed only other convolutions (the two reduce layers of an
+        #     inception block): each consumer reads its channel slice of the merged result;
+        #   * with those, one 1x1 convolution of the same tensor that stores into a concatenated
+        #     tensor (the block's 1x1 branch): its filters come first and go to the concatenated
+        #     tensor, the others to the second output of the same launch.
         # Every output element is the same sum in the same order, so the bits do not change;
         # ``merged`` lists the groups.
         self.merged = []
@@ -135,6 +138,7 @@ class DeviceModel:
                     reads.append(nd.attr["residual"])
                 for t in reads:
                     readers.setdefault(t, []).append(nd)
+            index = {nd.name: i for i, nd in enumerate(nodes)}
             sliced, stored = {}, {}
             for nd in nodes:
                 a = nd.attr
@@ -150,21 +154,21 @@ class DeviceModel:
                     sliced.setdefault((nd.src,) + geom, []).append(nd)
             in_slice, first, dropped, renamed = {}, {}, set(), {}
 
-            def merge(g):
-                name = "+".join(n.name for n in g)
-                first[g[0].name] = g[0]._replace(name=name, dst=name, attr=dict(
-                    g[0].attr, K=sum(n.attr["K"] for n in g), parts=[n.name for n in g]))
-                dropped.update(n.name for n in g)
+            def merge(g, lead=None):
+                parts = ([lead] if lead else []) + g
+                name = "+".join(n.name for n in g)          # the tensor that holds the outputs of g
+                attr = dict(parts[0].attr, K=sum(n.attr["K"] for n in parts), parts=[n.name for n in parts])
+                if lead:
+                    attr.update(K2=sum(n.attr["K"] for n in g), dst2=name)
+                    node = lead._replace(name="+".join(n.name for n in parts), attr=attr)
+                else:
+                    node = g[0]._replace(name=name, dst=name, attr=attr)
+                first[min(parts, key=lambda n: index[n.name]).name] = node
+                dropped.update(n.name for n in parts)
                 chans[name] = sum(n.attr["K"] for n in g)
-                self.merged.append([n.name for n in g])
+                self.merged.append([n.name for n in parts])
                 return name
 
-            for g in sliced.values():
-                if len(g) >= 2:
-                    name, off = merge(g), 0
-                    for n in g:
-                        in_slice[n.dst] = (name, off, chans[name])
-                        off += n.attr["K"]
             for g in stored.values():
                 g.sort(key=lambda n: alias[n.dst][1])
                 runs = [[g[0]]]
@@ -183,6 +187,20 @@ class DeviceModel:
                             renamed[n.dst] = None
                         renamed[run[0].dst] = name
                         alias[name] = (cat, off, total)
+            for key, g in sliced.items():
+                lead = None
+                if chans[key[0]] % 8 == 0:
+                    for k2, cand in stored.items():
+                        if k2[0] == key[0] and k2[2:] == key[1:]:
+                            for n in cand:
+                                if (n.name not in dropped and n.attr["K"] % 8 == 0 and alias[n.dst][1] % 8 == 0
+                                        and alias[n.dst][2] % 8 == 0 and lead is None):
+                                    lead = n
+                if len(g) + (lead is not None) >= 2:
+                    name, off = merge(g, lead), 0
+                    for n in g:
+                        in_slice[n.dst] = (name, off, chans[name])
+                        off += n.attr["K"]
             kept = []
             for nd in nodes:
                 if nd.name in first:
@@ -191,7 +209,9 @@ class DeviceModel:
                     continue
                 elif nd.op == "conv" and nd.src in in_slice:
                     t, off, total = in_slice[nd.src]
-                    kept.append(nd._replace(src=t, attr=dict(nd.attr, in_slice=(off, total))))
+                    if (off, total) != (0, nd.attr["C"]):
+                        nd = nd._replace(attr=dict(nd.attr, in_slice=(off, total)))
+                    kept.append(nd._replace(src=t))
                 elif nd.op == "concat":
                     kept.append(nd._replace(src=[renamed.get(t, t) for t in nd.src if renamed.get(t, t) is not None]))
                 else:
@@ -232,6 +252,14 @@ class DeviceModel:
                     n_bufs += 1
             L = gpulet.Layer()
             L.in_buf, L.out_buf, L.res_buf = buf_of[storage(nd.src)], buf_of[st], -1
+            if nd.op == "conv" and "dst2" in nd.attr:      # the second output has a buffer of its own
+                if free:
+                    buf_of[nd.attr["dst2"]] = free.pop()
+                else:
+                    buf_of[nd.attr["dst2"]] = n_bufs
+                    n_bufs += 1
+                L.K2, L.out2_buf = nd.attr["K2"], buf_of[nd.attr["dst2"]]
+                self.tensor_buf[nd.attr["dst2"]] = L.out2_buf
             if storage(nd.src) != nd.src:
                 raise ValueError("reading a concat slice on its own is not supported")
             a = nd.attr

@@ -225,6 +225,19 @@ def test_model_description_errors():
     bad([reduce_, _layer(in_ch_total=32, in_ch_offset=16, **take)])
     bad([reduce_, _layer(in_ch_total=24, in_ch_offset=17, **take)])
     bad([reduce_, _layer(in_ch_total=24, in_ch_offset=-1, **take)])
+    # a layer with two outputs: 1x1 only, no residual, a second buffer of its own, 0 < K2 < K
+    two = dict(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=24, R=1, S=1, stride=1, pad=0, w=W)
+    use = [_layer(op=gpulet.OP_CONV, in_buf=3, out_buf=1, C=16, K=8, R=3, S=3, stride=1, pad=1, w=W)]
+    assert gpulet.model_workspace_bytes(_desc([_layer(K2=16, out2_buf=3, **two)] + use, 4, (3, 8, 8)), 2) == \
+        2 * (8 + 16) * 8 * 8 * 2
+    assert gpulet.model_buffer_info(_desc([_layer(K2=16, out2_buf=3, **two)] + use, 4, (3, 8, 8)), 2, 2)[:3] == (8, 8, 8)
+    bad([_layer(K2=24, out2_buf=3, **two)] + use, n_bufs=4)
+    bad([_layer(K2=-1, out2_buf=3, **two)] + use, n_bufs=4)
+    bad([_layer(K2=16, out2_buf=2, **two)] + use, n_bufs=4)          # both parts to one buffer
+    bad([_layer(K2=16, out2_buf=0, **two)] + use, n_bufs=4)          # the model input
+    bad([_layer(K2=16, out2_buf=4, **two)] + use, n_bufs=4)          # bad index
+    bad([_layer(K2=16, out2_buf=3, out2_ch_total=8, **two)] + use, n_bufs=4)   # slice does not fit
+    bad([_layer(K2=16, out2_buf=3, **dict(two, R=3, S=3, pad=1))] + use, n_bufs=4)
     # residual of the wrong shape
     bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=2, pad=1, w=W),
          _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])

@@ -194,6 +194,67 @@ def test_conv_slice_arguments_are_checked(part):
         assert e.value.status == gpulet.EINVAL
 
 
+# N, C, H, W, K, k2, stride, (channels per stored input pixel, first channel read),
+# (y pixel width, y offset), (y2 pixel width, y2 offset); 0 width = dense
+TWO_OUTPUT_CASES = [
+    (3, 192, 28, 28, 176, 64, 1, (0, 0), (256, 0), (0, 0)),        # inception 3a: 1x1 branch + both reduce layers
+    (2, 480, 14, 14, 304, 192, 1, (0, 0), (512, 0), (0, 0)),       # 4a: ragged pixel tile
+    (2, 64, 9, 11, 72, 40, 1, (96, 32), (48, 8), (64, 16)),        # slices on all three tensors
+    (2, 40, 13, 13, 56, 8, 2, (0, 0), (0, 0), (0, 0)),             # stride 2, everything dense
+    (1, 24, 6, 5, 21, 8, 1, (0, 0), (16, 8), (13, 0)),             # second part cannot take 16-byte stores
+    (1, 16, 4, 4, 30, 12, 1, (0, 0), (0, 0), (0, 0)),              # the boundary falls inside an 8-channel group
+    (2, 128, 33, 17, 520, 264, 1, (0, 0), (0, 0), (0, 0)),         # several filter tiles on both sides
+]
+
+
+@pytest.mark.parametrize("case", TWO_OUTPUT_CASES, ids=lambda c: "x".join(map(str, c[:7])))
+def test_1x1_conv_with_two_outputs(part, case):
+    N, C, H, W, K, k2, stride, (ldx, xo), (ldy, yo), (ldy2, yo2) = case
+    tag = "two/" + "_".join(map(str, case[:7]))
+    wide = inputs.tensor(33, tag + "x", (N, ldx or C, H, W), "normal")
+    w = inputs.he_normal(33, tag + "w", (K, C, 1, 1))
+    b = inputs.bias(33, tag + "b", K)
+    x = np.ascontiguousarray(wide[:, xo:xo + C])
+    ref = oracle.conv2d(x, w, b, stride, 0, True)
+    _, dense = gpu_conv(part, x, w, b, stride, 0, True)         # all K filters to one dense tensor
+    P, Q = ref.shape[2], ref.shape[3]
+    xd = lowering.nchw_to_nhwc(wide, DEV)
+    wd = lowering.kcrs_to_krsc(w, DEV)
+    bd = torch.from_numpy(b).to(DEV)
+    for tile in range(-1, 11):
+        y1 = torch.full((N, P, Q, ldy or k2), -512.0, dtype=torch.bfloat16, device=DEV)
+        y2 = torch.full((N, P, Q, ldy2 or K - k2), -512.0, dtype=torch.bfloat16, device=DEV)
+        torch.cuda.synchronize()
+        gpulet.set_conv_tile(tile)
+        try:
+            gpulet.conv1x1_fwd_two_outputs(xd, wd, bd, y1, y2, N, C, H, W, K, k2, stride, True, ldx, xo, ldy, yo,
+                                           ldy2, yo2, part.stream)
+            part.sync()
+        finally:
+            gpulet.set_conv_tile(-1)
+        a, c = y1[..., yo:yo + k2], y2[..., yo2:yo2 + K - k2]
+        got = torch.cat([a, c], dim=3)
+        assert oracle.rel_err(lowering.nhwc_to_nchw(got), ref)[1] <= LAYER_TOL, tile
+        assert torch.equal(got, dense), tile                       # the bits of the plain layer
+        for t, lo, hi in ((y1, yo, yo + k2), (y2, yo2, yo2 + K - k2)):
+            assert bool((t[..., :lo] == -512.0).all()) and bool((t[..., hi:] == -512.0).all()), tile
+
+
+def test_two_output_arguments_are_checked(part):
+    x = torch.zeros((1, 4, 4, 16), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((24, 1, 1, 16), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros((1, 4, 4, 24), dtype=torch.bfloat16, device=DEV)
+    ok = dict(N=1, C=16, H=4, W=4, K=24, k2=8, stride=1, relu=True, stream=part.stream)
+    for kw in (dict(ok, k2=0), dict(ok, k2=24), dict(ok, y_ch_stride=4), dict(ok, y2_ch_stride=8),
+               dict(ok, y2_ch_stride=24, y2_ch_offset=16), dict(ok, C=12)):
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.conv1x1_fwd_two_outputs(x, w, None, y, y, **kw)
+        assert e.value.status == gpulet.EINVAL, kw
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.conv1x1_fwd_two_outputs(x, w, None, y, None, **ok)
+    assert e.value.status == gpulet.EINVAL
+
+
 # N, H, W, K: 3x3, stride 1, pad 1, exactly 64 input channels -> weights resident in registers (tile 10)
 C64_CASES = [
     (3, 14, 14, 64),        # whole rows per block; M = 588: ragged last tile, fewer tiles than workgroups

@@ -204,16 +204,18 @@ def test_inception_pool_branches_run_inside_their_projection():
     _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(3, -1), ref)
 
 
-@pytest.mark.parametrize("width_div,in_hw,groups", [(2, 96, 7), (1, 224, 9)])
-def test_inception_reduce_layers_run_as_one_convolution(width_div, in_hw, groups):
-    # at half width two blocks have a reduce layer whose filter count is not a multiple of 8: left alone
+@pytest.mark.parametrize("width_div,in_hw,sizes", [(2, 96, [3, 3, 3, 2, 2, 3, 3, 3, 3]), (1, 224, [3] * 9)])
+def test_inception_1x1_layers_of_a_block_run_as_one_convolution(width_div, in_hw, sizes):
+    # the 1x1 branch and the two reduce layers of every block; at half width two blocks have a 5x5 reduce
+    # layer whose filter count is not a multiple of 8, which is left alone
     model = workloads.googlenet(width_div=width_div, in_hw=in_hw, n_class=20)
     params = workloads.parameters(model, 11)
     x = workloads.batch_input(model, 2, 11)
     merged = lowering.DeviceModel(model, params, DEV, merge_siblings=True)
     plain = lowering.DeviceModel(model, params, DEV, merge_siblings=False)
-    assert len(merged.merged) == groups and all(len(g) == 2 for g in merged.merged) and not plain.merged
-    assert merged.desc.n_layers == plain.desc.n_layers - groups
+    assert [len(g) for g in merged.merged] == sizes and not plain.merged
+    assert all(g[0].endswith("_1x1") for g in merged.merged)
+    assert merged.desc.n_layers == plain.desc.n_layers - sum(n - 1 for n in sizes)
     with gpulet.Partition(0, 100, 0) as p:
         a, _ = merged.run(p, merged.input_to_device(x))
         b, _ = plain.run(p, plain.input_to_device(x))

@@ -35,28 +35,42 @@ def _happens_before(n, lane, waits):
     return reach
 
 
+def _writes(L):
+    """(buffer, channel slice or None) for everything a layer writes."""
+    k1 = L.K - L.K2
+    out = [(L.out_buf, (L.out_ch_offset, L.out_ch_offset + k1, L.out_ch_total) if L.out_ch_total > 0 else None)]
+    if L.K2 > 0:
+        out.append((L.out2_buf, (L.out2_ch_offset, L.out2_ch_offset + L.K2, L.out2_ch_total)
+                    if L.out2_ch_total > 0 else None))
+    return out
+
+
 def _conflicts(layers):
     """Pairs (i, j), i < j, that must not run concurrently or out of order."""
-    out = []
+    out = set()
     for j, Lj in enumerate(layers):
         reads_j = {Lj.in_buf} | ({Lj.res_buf} if Lj.res_buf >= 0 else set())
         for i in range(j):
             Li = layers[i]
             reads_i = {Li.in_buf} | ({Li.res_buf} if Li.res_buf >= 0 else set())
-            if Li.out_buf in reads_j or Lj.out_buf in reads_i:
-                out.append((i, j))
-            elif Li.out_buf == Lj.out_buf:
-                si = (Li.out_ch_offset, Li.out_ch_offset + Li.K) if Li.out_ch_total > 0 else None
-                sj = (Lj.out_ch_offset, Lj.out_ch_offset + Lj.K) if Lj.out_ch_total > 0 else None
-                disjoint = (si and sj and Li.out_ch_total == Lj.out_ch_total and (si[1] <= sj[0] or sj[1] <= si[0]))
-                # disjoint slices of one tensor are independent only while nobody has read or rewritten
-                # the buffer in between; otherwise j starts a new tensor in a reused buffer
-                between = any(layers[k].in_buf == Li.out_buf or layers[k].res_buf == Li.out_buf or
-                              (layers[k].out_buf == Li.out_buf and layers[k].out_ch_total <= 0)
-                              for k in range(i + 1, j))
-                if not disjoint or between:
-                    out.append((i, j))
-    return out
+            for bi, si in _writes(Li):
+                if bi in reads_j:
+                    out.add((i, j))
+            for bj, sj in _writes(Lj):
+                if bj in reads_i:
+                    out.add((i, j))
+                for bi, si in _writes(Li):
+                    if bi != bj:
+                        continue
+                    disjoint = (si and sj and si[2] == sj[2] and (si[1] <= sj[0] or sj[1] <= si[0]))
+                    # disjoint slices of one tensor are independent only while nobody has read or rewritten
+                    # the buffer in between; otherwise j starts a new tensor in a reused buffer
+                    between = any(layers[k].in_buf == bi or layers[k].res_buf == bi or
+                                  any(b == bi and sl is None for b, sl in _writes(layers[k]))
+                                  for k in range(i + 1, j))
+                    if not disjoint or between:
+                        out.add((i, j))
+    return sorted(out)
 
 
 @pytest.mark.parametrize("model", MODELS, ids=lambda m: m.name)
