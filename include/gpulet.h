@@ -240,7 +240,9 @@ gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const fl
  * CU has the least work for the launch's shape and the stream's CU count, and
  * tile 9 wherever it applies.  Tiles 0..8 and 10 give bit-identical results; tile 9
  * groups the same ascending sum differently (zero padding inside the depth),
- * so it agrees with them to rounding.  GPULET_EINVAL outside -1..10.
+ * so it agrees with them to rounding.  Tiles 7..10 need dense input pixels and
+ * a single output: a layer that reads a channel slice or stores to two tensors
+ * counts as another shape for them.  GPULET_EINVAL outside -1..10.
  */
 enum { GPULET_CONV_TILES = 11 };
 gpulet_status gpulet_set_conv_tile(int tile);
