@@ -206,6 +206,22 @@ gpulet_status gpulet_conv1x1_fwd_two_outputs(const void *x, const void *w, const
                                              int y2_ch_offset, void *stream);
 
 /*
+ * A 1x1 convolution (pad 0, stride 1) that also writes, from the same launch,
+ * pool_y = maxpool(x, window 3x3, stride 1, pad 1) (N*H*W*C bf16, maximum over
+ * in-image taps only, the bits of gpulet_pool): extra workgroups at the end of
+ * the convolution's grid do the pooling, so the pool costs no launch of its own.
+ * In an inception block the pool of the block's input feeds the pooling branch
+ * while the 1x1 layers read the same input.  y2 may be NULL (one output, k2
+ * ignored) or, as in gpulet_conv1x1_fwd_two_outputs, receive filters [k2, K).
+ * x must be dense (no input slice).  Errors as gpulet_conv1x1_fwd_two_outputs,
+ * and GPULET_EINVAL for a NULL or misaligned pool_y.
+ */
+gpulet_status gpulet_conv1x1_maxpool3_fwd(const void *x, const void *w, const float *b, void *y, void *y2,
+                                          void *pool_y, int N, int C, int H, int W, int K, int k2,
+                                          int relu, int y_ch_stride, int y_ch_offset, int y2_ch_stride,
+                                          int y2_ch_offset, void *stream);
+
+/*
  * Pooling branch of an inception block (GoogLeNet of Table 4) in one kernel:
  *   y = act(b + conv1x1(maxpool(x, window 3x3, stride 1, pad 1), w))
  * with the pool's maximum taken over in-image taps only, as in gpulet_pool.
@@ -334,6 +350,10 @@ typedef struct gpulet_layer {
     int32_t out2_buf;      /* CONV with K2 > 0: second buffer written */
     int32_t out2_ch_total; /* CONV with K2 > 0: channels of out2_buf when a slice is written; 0 means K2 */
     int32_t out2_ch_offset;/* CONV with K2 > 0: first channel written in out2_buf */
+    int32_t side_pool;     /* CONV, 1x1 filters, pad 0, C % 8 == 0, dense input: 0, or 3 = the launch also
+                              writes the 3x3 / stride 1 / pad 1 max pool of in_buf to pool_buf
+                              (gpulet_conv1x1_maxpool3_fwd) */
+    int32_t pool_buf;      /* CONV with side_pool: buffer that receives the pooled tensor */
     const void *w;         /* device: CONV KRSC bf16, DWCONV RSC bf16, FC [Out][In] bf16 */
     const float *b;        /* device: fp32 bias or NULL */
 } gpulet_layer;

@@ -42,6 +42,9 @@ gpulet_status check_conv(const ConvArgs &a) {
         if (1LL * a.N * a.P * a.Q * a.y2_ch_stride >= (1LL << 30)) return GPULET_EINVAL;
     }
     if (a.y_ch_offset < 0 || a.y_ch_offset + (a.y2 ? a.k2 : a.K) > a.y_ch_stride) return GPULET_EINVAL;
+    if (a.pool_y && (a.R != 1 || a.S != 1 || a.pad != 0 || a.pre_pool || a.C % 8 != 0 ||
+                     (a.x_ch_stride != 0 && a.x_ch_stride != a.C)))
+        return GPULET_EINVAL;
     if (a.pre_pool != 0 && (a.pre_pool != 3 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % 8 != 0))
         return GPULET_EINVAL;
     const int ldx = a.x_ch_stride ? a.x_ch_stride : a.C;
@@ -104,6 +107,19 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     const bool vec = (a.C % CHUNK == 0) && (p.ldx % CHUNK == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
     if (a.y2 && !vec) return hipErrorInvalidValue;  // only the 16-byte gathering kernels store to two tensors
+    p.side_blocks = 0;
+    p.side_pool = PoolParams{};
+    if (a.pool_y) {
+        if (!vec || reinterpret_cast<uintptr_t>(a.pool_y) % 16 != 0) return hipErrorInvalidValue;
+        PoolParams &sp = p.side_pool;
+        sp.x = static_cast<const __bf16 *>(a.x);
+        sp.y = static_cast<__bf16 *>(a.pool_y);
+        sp.N = a.N; sp.C = a.C; sp.H = a.H; sp.W = a.W; sp.P = a.H; sp.Q = a.W; sp.k = 3; sp.stride = 1; sp.pad = 1;
+        sp.total = a.N * a.H * a.W * (a.C / 8);
+        sp.d_cv = make_fastdiv(a.C / 8);
+        sp.d_q = make_fastdiv(a.W);
+        sp.d_p = make_fastdiv(a.H);
+    }
     if (a.pre_pool) {
         // checked by check_conv: 3x3 window, 1x1 filter, stride 1, no padding, C % 8 == 0; the
         // callers check the 16-byte alignment of x and w

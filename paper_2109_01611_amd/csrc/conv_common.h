@@ -12,6 +12,7 @@
 
 #include "device_util.h"
 #include "gpulet_internal.h"
+#include "pool_device.h"
 
 namespace gpulet {
 namespace conv {
@@ -37,6 +38,10 @@ struct ConvParams {
     // y2[m * ldy2 + y2_off + k - k2] instead; k2 == K means there is none.
     __bf16 *y2;
     int k2, ldy2, y2_off;
+    // Side job (1x1 gathering kernels only): side_blocks extra workgroups at the end of the grid
+    // compute the 3x3 / stride 1 / pad 1 max pool side_pool of the layer's (dense) input.
+    PoolParams side_pool;
+    int side_blocks;
     int ldx;            // channels per input pixel as stored (x points at the layer's first channel);
                         // only the gathering kernels accept ldx != C
     int tiles_n, n_tiles, tiles_per_xcd;

@@ -99,6 +99,15 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
     constexpr int RING = NS * STAGE > BM * LDT * 2 ? NS * STAGE : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 ring[RING];
 
+    // Workgroups past the tiles carry the layer's side job: a max pool of the same input,
+    // which would otherwise be a launch of its own with nothing but fixed cost to it.
+    if (POINTWISE && p.side_blocks > 0 && static_cast<int>(blockIdx.x) >= p.tiles_per_xcd * 8) {
+        const int idx = (static_cast<int>(blockIdx.x) - p.tiles_per_xcd * 8) * ((CWM * CWN + NPROD) * 64) +
+                        static_cast<int>(threadIdx.x);
+        if (idx < p.side_pool.total) pool_max_item<3>(p.side_pool, idx);
+        return;
+    }
+
     // Split-K: consecutive work items share an output tile and each takes a
     // contiguous range of depth slices.
     const int item = tile_of_block(p);
@@ -556,9 +565,12 @@ hipError_t launch_tile(ConvParams p, bool vec, int split_k, hipStream_t stream) 
     p.d_split_k = make_fastdiv(p.split_k);
     p.sps = (nk + p.split_k - 1) / p.split_k;
     p.tiles_per_xcd = (p.n_tiles * p.split_k + 7) / 8;  // work items per die
-    const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8));
-    const dim3 block((CWM * CWN + NPROD) * 64);
     const bool pointwise = p.R == 1 && p.S == 1 && p.pad == 0;
+    constexpr int THREADS = (CWM * CWN + NPROD) * 64;
+    p.side_blocks = (vec && pointwise && p.side_pool.y) ? (p.side_pool.total + THREADS - 1) / THREADS : 0;
+    if (p.side_pool.y && !p.side_blocks) return hipErrorInvalidValue;  // nobody would compute the pool
+    const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8 + p.side_blocks));
+    const dim3 block(THREADS);
     if (vec && pointwise)
         hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, CWM, CWN, NPROD, NS, true>), grid, block, 0, stream, p);
     else if (vec)

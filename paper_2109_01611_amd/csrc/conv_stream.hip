@@ -145,7 +145,7 @@ __global__ __launch_bounds__(12 * 64) void conv1x1_stream_kernel(const ConvParam
 // The streaming 1x1 kernel: at most 128 input channels (one or two depth slices, the last one
 // possibly partial), unit filter.
 bool stream_applicable(const ConvParams &p, bool vec) {
-    return vec && p.ldx == p.C && p.k2 == p.K && p.R == 1 && p.S == 1 && p.pad == 0 && p.C <= 2 * BK;
+    return vec && p.ldx == p.C && p.k2 == p.K && !p.side_pool.y && p.R == 1 && p.S == 1 && p.pad == 0 && p.C <= 2 * BK;
 }
 
 // Chosen automatically for one depth slice (C <= 64: two workgroups per CU) and at least four tiles

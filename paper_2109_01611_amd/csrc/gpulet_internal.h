@@ -90,6 +90,9 @@ struct ConvArgs {
     // and only filters [0, k2) to y.
     void *y2 = nullptr;
     int k2 = 0, y2_ch_stride = 0, y2_ch_offset = 0;
+    // Side job (1x1 filters, dense input, C % 8 == 0): when set, the launch also writes the
+    // 3x3 / stride 1 / pad 1 max pool of x (N*H*W*C bf16) to pool_y.
+    void *pool_y = nullptr;
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 void set_conv_tile(int tile);

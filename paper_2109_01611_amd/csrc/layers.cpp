@@ -79,6 +79,30 @@ extern "C" gpulet_status gpulet_conv1x1_fwd_two_outputs(const void *x, const voi
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_conv1x1_maxpool3_fwd(const void *x, const void *w, const float *b, void *y,
+                                                     void *y2, void *pool_y, int N, int C, int H, int W, int K,
+                                                     int k2, int relu, int y_ch_stride, int y_ch_offset,
+                                                     int y2_ch_stride, int y2_ch_offset, void *stream) {
+    if (!pool_y || reinterpret_cast<uintptr_t>(pool_y) % 16 != 0) return GPULET_EINVAL;
+    if (y2 && (k2 < 1 || k2 >= K)) return GPULET_EINVAL;
+    ConvArgs a;
+    a.pool_y = pool_y;
+    const int k1 = y2 ? k2 : K;
+    if (y2) {
+        a.y2 = y2;
+        a.k2 = k2;
+        a.y2_ch_stride = y2_ch_stride == 0 ? K - k2 : y2_ch_stride;
+        a.y2_ch_offset = y2_ch_offset;
+    }
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, 1, 1, 1, 0, relu, nullptr,
+                                      y_ch_stride == 0 ? k1 : y_ch_stride, y_ch_offset);
+    if (st != GPULET_OK) return st;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0) return GPULET_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv(a, stream_ctx(s), s));
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const float *b, void *y, int N,
                                                      int C, int H, int W, int K, int relu, int y_ch_stride,
                                                      int y_ch_offset, void *stream) {

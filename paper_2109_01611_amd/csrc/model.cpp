@@ -28,6 +28,7 @@ struct Step {
     int op;
     int in_buf, out_buf, res_buf;
     int out2_buf;   // CONV storing its last filters to a second buffer, else -1
+    int pool_buf;   // CONV that also writes the 3x3 max pool of its input, else -1
     ConvArgs conv;  // CONV
     int N, C, H, W, P, Q, mode, k, k2, stride, pad;  // POOL (k); DWCONV (k x k2, relu)
     int In, Out, relu, out_fp32;                     // FC
@@ -94,6 +95,7 @@ void assign_lanes(Plan &plan, int n_bufs, int n_lanes) {
         };
         writes(s.out_buf, s.slice);
         if (s.out2_buf >= 0) writes(s.out2_buf, s.slice2);
+        if (s.pool_buf >= 0) writes(s.pool_buf, false);
         std::sort(deps.begin(), deps.end());
         deps.erase(std::unique(deps.begin(), deps.end()), deps.end());
 
@@ -129,6 +131,7 @@ void assign_lanes(Plan &plan, int n_bufs, int n_lanes) {
         if (s.res_buf >= 0) hz[static_cast<size_t>(s.res_buf)].readers.push_back(i);
         hz[static_cast<size_t>(s.out_buf)].writers.push_back(i);
         if (s.out2_buf >= 0) hz[static_cast<size_t>(s.out2_buf)].writers.push_back(i);
+        if (s.pool_buf >= 0) hz[static_cast<size_t>(s.pool_buf)].writers.push_back(i);
     }
 }
 
@@ -165,6 +168,7 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         s.out_buf = L.out_buf;
         s.res_buf = -1;
         s.out2_buf = -1;
+        s.pool_buf = -1;
         s.slice2 = false;
         s.w = L.w;
         s.b = L.b;
@@ -200,6 +204,13 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
                 s.out2_buf = L.out2_buf;
                 s.slice2 = L.out2_ch_total > 0;
             }
+            if (L.side_pool != 0) {
+                if (L.side_pool != 3 || L.pool_buf < 0 || L.pool_buf >= m->n_bufs || L.pool_buf == m->in_buf ||
+                    L.pool_buf == L.in_buf || L.pool_buf == L.out_buf || (L.K2 > 0 && L.pool_buf == L.out2_buf))
+                    return GPULET_EINVAL;
+                a.pool_y = &a;  // stand-in, filled in at run time
+                s.pool_buf = L.pool_buf;
+            }
             a.x_ch_stride = L.in_ch_total > 0 ? L.in_ch_total : 0;
             a.x_ch_offset = L.in_ch_total > 0 ? L.in_ch_offset : 0;
             // Pointers are filled in at run time; validate the rest with stand-ins.
@@ -215,6 +226,11 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
                 s.res_buf = L.res_buf;
             }
             oc = a.y_ch_stride; oh = a.P; ow = a.Q;
+            if (s.pool_buf >= 0) {
+                BufState &dp = plan.bufs[static_cast<size_t>(s.pool_buf)];
+                dp.C = src.C; dp.H = src.H; dp.W = src.W; dp.elem = 2; dp.written = true;
+                dp.bytes_per_image = std::max(dp.bytes_per_image, static_cast<size_t>(2) * src.C * src.H * src.W);
+            }
             if (s.out2_buf >= 0) {
                 BufState &d2 = plan.bufs[static_cast<size_t>(s.out2_buf)];
                 d2.C = a.y2_ch_stride; d2.H = a.P; d2.W = a.Q; d2.elem = 2; d2.written = true;
@@ -327,6 +343,7 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
             a.x = bd.ptr(s.in_buf);
             a.y = bd.ptr(s.out_buf);
             a.y2 = s.out2_buf >= 0 ? bd.ptr(s.out2_buf) : nullptr;
+            a.pool_y = s.pool_buf >= 0 ? bd.ptr(s.pool_buf) : nullptr;
             a.residual = s.res_buf >= 0 ? bd.ptr(s.res_buf) : nullptr;
             e = launch_conv(a, ctx, stream);
         } else if (s.op == GPULET_OP_POOL) {

@@ -40,7 +40,7 @@ class Layer(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in (
         "op", "in_buf", "out_buf", "res_buf", "C", "K", "R", "S", "stride", "pad", "relu", "mode",
         "out_ch_total", "out_ch_offset", "out_fp32", "pre_pool", "in_ch_total", "in_ch_offset", "K2", "out2_buf",
-        "out2_ch_total", "out2_ch_offset")] + [("w", c_void_p), ("b", c_void_p)]
+        "out2_ch_total", "out2_ch_offset", "side_pool", "pool_buf")] + [("w", c_void_p), ("b", c_void_p)]
 
 
 class SchedModel(ctypes.Structure):
@@ -96,6 +96,7 @@ def _load():
         "gpulet_conv2d_fwd_ex": ([P, P, P, P] + [I] * 10 + [P, I, I, P], c_int32),
         "gpulet_conv2d_fwd_slices": ([P, P, P, P] + [I] * 10 + [P, I, I, I, I, P], c_int32),
         "gpulet_conv1x1_fwd_two_outputs": ([P, P, P, P, P] + [I] * 14 + [P], c_int32),
+        "gpulet_conv1x1_maxpool3_fwd": ([P, P, P, P, P, P] + [I] * 11 + [P], c_int32),
         "gpulet_set_conv_tile": ([I], c_int32),
         "gpulet_set_conv_split_k": ([I], c_int32),
         "gpulet_depthwise_conv2d_fwd": ([P, P, P, P] + [I] * 9 + [P], c_int32),
@@ -231,6 +232,13 @@ def conv1x1_fwd_two_outputs(x, w, b, y, y2, N, C, H, W, K, k2, stride, relu, x_c
     _check(lib.gpulet_conv1x1_fwd_two_outputs(ptr(x), ptr(w), ptr(b), ptr(y), ptr(y2), N, C, H, W, K, k2, stride,
                                               int(relu), x_ch_stride, x_ch_offset, y_ch_stride, y_ch_offset,
                                               y2_ch_stride, y2_ch_offset, stream), "gpulet_conv1x1_fwd_two_outputs")
+
+
+def conv1x1_maxpool3_fwd(x, w, b, y, y2, pool_y, N, C, H, W, K, k2, relu, y_ch_stride=0, y_ch_offset=0,
+                         y2_ch_stride=0, y2_ch_offset=0, stream=None):
+    _check(lib.gpulet_conv1x1_maxpool3_fwd(ptr(x), ptr(w), ptr(b), ptr(y), ptr(y2), ptr(pool_y), N, C, H, W, K, k2,
+                                           int(relu), y_ch_stride, y_ch_offset, y2_ch_stride, y2_ch_offset, stream),
+           "gpulet_conv1x1_maxpool3_fwd")
 
 
 def set_conv_tile(tile):

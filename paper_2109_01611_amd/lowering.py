@@ -129,7 +129,7 @@ class DeviceModel:
         #     tensor, the others to the second output of the same launch.
         # Every output element is the same sum in the same order, so the bits do not change;
         # ``merged`` lists the groups.
-        self.merged = []
+        self.merged, self.side_pools = [], []
         if merge_siblings:
             readers = {}
             for nd in nodes:
@@ -217,6 +217,30 @@ class DeviceModel:
                 else:
                     kept.append(nd)
             nodes = kept
+            # A 3x3 / stride 1 / pad 1 max pool whose input is also read by a plain 1x1 convolution
+            # (an inception block's pooling branch next to its 1x1 layers) rides along with that
+            # convolution's launch: extra workgroups of the same grid do the pooling.
+            hosts, first_read = {}, {}
+            for i, nd in enumerate(nodes):
+                a = nd.attr
+                if (nd.op == "conv" and (a["k"], a["stride"], a["pad"]) == (1, 1, 0) and not a["residual"]
+                        and not a.get("pre_pool") and "in_slice" not in a and nd.src != "x"
+                        and nd.src not in alias and chans[nd.src] % 8 == 0):
+                    hosts.setdefault(nd.src, (i, nd.name))
+                for t in (list(nd.src) if nd.op == "concat" else [nd.src]):
+                    first_read.setdefault(t, i)
+            riders, kept = {}, []
+            for i, nd in enumerate(nodes):
+                a = nd.attr
+                if (nd.op == "maxpool" and (a["k"], a["stride"], a["pad"]) == (3, 1, 1) and nd.dst != model.out
+                        and nd.src in hosts and hosts[nd.src][1] not in riders
+                        and hosts[nd.src][0] < first_read.get(nd.dst, len(nodes))):
+                    riders[hosts[nd.src][1]] = nd
+                    continue
+                kept.append(nd)
+            nodes = [nd._replace(attr=dict(nd.attr, pool_dst=riders[nd.name].dst)) if nd.name in riders else nd
+                     for nd in kept]
+            self.side_pools = [r.name for r in riders.values()]
         producers = {nd.dst: nd for nd in nodes}
         for s in alias:
             if producers[s].op != "conv":
@@ -260,6 +284,14 @@ class DeviceModel:
                     n_bufs += 1
                 L.K2, L.out2_buf = nd.attr["K2"], buf_of[nd.attr["dst2"]]
                 self.tensor_buf[nd.attr["dst2"]] = L.out2_buf
+            if nd.op == "conv" and "pool_dst" in nd.attr:  # and so has the pooled input
+                if free:
+                    buf_of[nd.attr["pool_dst"]] = free.pop()
+                else:
+                    buf_of[nd.attr["pool_dst"]] = n_bufs
+                    n_bufs += 1
+                L.side_pool, L.pool_buf = 3, buf_of[nd.attr["pool_dst"]]
+                self.tensor_buf[nd.attr["pool_dst"]] = L.pool_buf
             if storage(nd.src) != nd.src:
                 raise ValueError("reading a concat slice on its own is not supported")
             a = nd.attr

@@ -238,6 +238,19 @@ def test_model_description_errors():
     bad([_layer(K2=16, out2_buf=4, **two)] + use, n_bufs=4)          # bad index
     bad([_layer(K2=16, out2_buf=3, out2_ch_total=8, **two)] + use, n_bufs=4)   # slice does not fit
     bad([_layer(K2=16, out2_buf=3, **dict(two, R=3, S=3, pad=1))] + use, n_bufs=4)
+    # a 1x1 layer that carries the max pool of its input: a buffer of its own, window 3 only, dense input
+    rider = dict(op=gpulet.OP_CONV, in_buf=2, out_buf=3, C=8, K=8, R=1, S=1, stride=1, pad=0, w=W)
+    head = [_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)]
+    tail = [_layer(op=gpulet.OP_CONV, in_buf=4, out_buf=1, C=8, K=8, R=1, S=1, stride=1, pad=0, w=W, res_buf=3)]
+    d = _desc(head + [_layer(side_pool=3, pool_buf=4, **rider)] + tail, 5, (3, 8, 8))
+    assert gpulet.model_workspace_bytes(d, 2) == 3 * 2 * 8 * 8 * 8 * 2
+    assert gpulet.model_buffer_info(d, 2, 4)[:4] == (8, 8, 8, 2)
+    bad(head + [_layer(side_pool=2, pool_buf=4, **rider)] + tail, n_bufs=5)
+    bad(head + [_layer(side_pool=3, pool_buf=3, **rider)] + tail, n_bufs=5)      # the layer's own output
+    bad(head + [_layer(side_pool=3, pool_buf=2, **rider)] + tail, n_bufs=5)      # its input
+    bad(head + [_layer(side_pool=3, pool_buf=5, **rider)] + tail, n_bufs=5)
+    bad(head + [_layer(side_pool=3, pool_buf=4, **dict(rider, R=3, S=3, pad=1))] + tail, n_bufs=5)
+    bad(head + [_layer(**rider)] + tail, n_bufs=5)                               # buffer 4 never written
     # residual of the wrong shape
     bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=2, pad=1, w=W),
          _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])

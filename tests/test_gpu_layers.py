@@ -255,6 +255,65 @@ def test_two_output_arguments_are_checked(part):
     assert e.value.status == gpulet.EINVAL
 
 
+# N, C, H, W, K, k2 (0 = one output)
+SIDE_POOL_CASES = [
+    (3, 192, 28, 28, 176, 64),      # inception 3a: 1x1 branch, reduce layers and the pool in one launch
+    (2, 480, 14, 14, 304, 192),     # 4a
+    (2, 832, 7, 7, 96, 0),          # one output; more pool work than convolution tiles
+    (1, 8, 5, 3, 8, 0),             # smaller than anything
+    (2, 72, 9, 11, 40, 16),         # ragged tiles
+    (4, 64, 1, 9, 24, 0),           # one row: vertical taps clamp
+]
+
+
+@pytest.mark.parametrize("case", SIDE_POOL_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_1x1_conv_carrying_the_max_pool_of_its_input(part, case):
+    N, C, H, W, K, k2 = case
+    tag = "sp/" + "_".join(map(str, case))
+    x = inputs.tensor(34, tag + "x", (N, C, H, W), "normal")
+    w = inputs.he_normal(34, tag + "w", (K, C, 1, 1))
+    b = inputs.bias(34, tag + "b", K)
+    _, dense = gpu_conv(part, x, w, b, 1, 0, True)
+    pooled_ref = oracle.maxpool(x, 3, 1, 1)
+    xd = lowering.nchw_to_nhwc(x, DEV)
+    wd = lowering.kcrs_to_krsc(w, DEV)
+    bd = torch.from_numpy(b).to(DEV)
+    for tile in range(-1, 11):
+        y1 = torch.full((N, H, W, k2 or K), -512.0, dtype=torch.bfloat16, device=DEV)
+        y2 = torch.full((N, H, W, K - k2), -512.0, dtype=torch.bfloat16, device=DEV) if k2 else None
+        pool = torch.full((N, H, W, C), -512.0, dtype=torch.bfloat16, device=DEV)
+        torch.cuda.synchronize()
+        gpulet.set_conv_tile(tile)
+        try:
+            gpulet.conv1x1_maxpool3_fwd(xd, wd, bd, y1, y2, pool, N, C, H, W, K, k2, True, stream=part.stream)
+            part.sync()
+        finally:
+            gpulet.set_conv_tile(-1)
+        got = torch.cat([y1, y2], dim=3) if k2 else y1
+        assert torch.equal(got, dense), tile                                  # the plain layer's bits
+        assert np.array_equal(lowering.nhwc_to_nchw(pool), pooled_ref), tile  # a max pool is exact
+
+
+def test_side_pool_arguments_are_checked(part):
+    x = torch.zeros((1, 4, 4, 16), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((24, 1, 1, 16), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros((1, 4, 4, 24), dtype=torch.bfloat16, device=DEV)
+    pool = torch.zeros((1, 4, 4, 16), dtype=torch.bfloat16, device=DEV)
+    ok = dict(N=1, C=16, H=4, W=4, K=24, k2=0, relu=True, stream=part.stream)
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.conv1x1_maxpool3_fwd(x, w, None, y, None, None, **ok)
+    assert e.value.status == gpulet.EINVAL
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.conv1x1_maxpool3_fwd(x, w, None, y, None, pool, **dict(ok, C=12))
+    assert e.value.status == gpulet.EINVAL
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.conv1x1_maxpool3_fwd(x, w, None, y, y, pool, **dict(ok, k2=24))
+    assert e.value.status == gpulet.EINVAL
+    with pytest.raises(gpulet.GpuletError) as e:       # misaligned destination for the pooled tensor
+        gpulet.conv1x1_maxpool3_fwd(x, w, None, y, None, pool.data_ptr() + 2, **ok)
+    assert e.value.status == gpulet.EINVAL
+
+
 # N, H, W, K: 3x3, stride 1, pad 1, exactly 64 input channels -> weights resident in registers (tile 10)
 C64_CASES = [
     (3, 14, 14, 64),        # whole rows per block; M = 588: ragged last tile, fewer tiles than workgroups

@@ -215,7 +215,9 @@ def test_inception_1x1_layers_of_a_block_run_as_one_convolution(width_div, in_hw
     plain = lowering.DeviceModel(model, params, DEV, merge_siblings=False)
     assert [len(g) for g in merged.merged] == sizes and not plain.merged
     assert all(g[0].endswith("_1x1") for g in merged.merged)
-    assert merged.desc.n_layers == plain.desc.n_layers - sum(n - 1 for n in sizes)
+    # and every block's 3x3 / stride 1 max pool rides along with that launch
+    assert merged.side_pools == ["i%s_pool" % b for b in ("3a", "3b", "4a", "4b", "4c", "4d", "4e", "5a", "5b")]
+    assert merged.desc.n_layers == plain.desc.n_layers - sum(n - 1 for n in sizes) - 9
     with gpulet.Partition(0, 100, 0) as p:
         a, _ = merged.run(p, merged.input_to_device(x))
         b, _ = plain.run(p, plain.input_to_device(x))

@@ -42,6 +42,8 @@ def _writes(L):
     if L.K2 > 0:
         out.append((L.out2_buf, (L.out2_ch_offset, L.out2_ch_offset + L.K2, L.out2_ch_total)
                     if L.out2_ch_total > 0 else None))
+    if L.side_pool:
+        out.append((L.pool_buf, None))
     return out
 
 
