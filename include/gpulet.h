@@ -206,6 +206,32 @@ gpulet_status gpulet_conv1x1_fwd_two_outputs(const void *x, const void *w, const
                                              int y2_ch_offset, void *stream);
 
 /*
+ * Up to 4 independent convolution layers in ONE launch: the workgroups of all
+ * layers form one grid, so small layers that do not depend on one another (the
+ * 3x3, 5x5 and pooling-branch layers of an inception block; a projection
+ * shortcut and the first layer of its residual block) pay the fixed cost of a
+ * launch once and fill the GPU together.  Each member is described as for
+ * gpulet_conv2d_fwd_slices.  Members must not read (x, residual) or overwrite
+ * memory another member writes; channel slices of one tensor (same y, same
+ * y_ch_stride, disjoint channels) count as different destinations.  Each
+ * member's result has the bits of its own gpulet_conv2d_fwd_slices call.  When a
+ * member cannot share (channel count not a multiple of 8, misaligned operands,
+ * or a shape for which a specialised kernel is chosen) the members are launched
+ * one after the other on `stream` instead: same results.
+ * Errors: GPULET_EINVAL for n outside 1..4, a member that gpulet_conv2d_fwd_slices
+ * would reject, or members that depend on one another.
+ */
+typedef struct gpulet_conv_desc {
+    const void *x, *w;
+    const float *b;
+    void *y;
+    const void *residual;
+    int32_t N, C, H, W, K, R, S, stride, pad, relu;
+    int32_t x_ch_stride, x_ch_offset, y_ch_stride, y_ch_offset;
+} gpulet_conv_desc;
+gpulet_status gpulet_conv2d_group_fwd(const gpulet_conv_desc *layers, int n, void *stream);
+
+/*
  * A 1x1 convolution (pad 0, stride 1) that also writes, from the same launch,
  * pool_y = maxpool(x, window 3x3, stride 1, pad 1) (N*H*W*C bf16, maximum over
  * in-image taps only, the bits of gpulet_pool): extra workgroups at the end of
@@ -354,6 +380,8 @@ typedef struct gpulet_layer {
                               writes the 3x3 / stride 1 / pad 1 max pool of in_buf to pool_buf
                               (gpulet_conv1x1_maxpool3_fwd) */
     int32_t pool_buf;      /* CONV with side_pool: buffer that receives the pooled tensor */
+    int32_t group_next;    /* CONV: 1 = the next layer (a CONV too) is independent of this one and may
+                              share its launch (gpulet_conv2d_group_fwd); chains of up to 4 layers */
     const void *w;         /* device: CONV KRSC bf16, DWCONV RSC bf16, FC [Out][In] bf16 */
     const float *b;        /* device: fp32 bias or NULL */
 } gpulet_layer;

@@ -26,6 +26,11 @@ struct TileChoice {
     float eff;  // relative MFMA efficiency of the tile shape (bigger tiles reuse LDS reads more)
 };
 
+// The gathering tiles (index = tile id) and the order in which they are tried.
+const TileChoice kTiles[] = {{128, 128, 0.90f}, {128, 64, 0.72f}, {64, 128, 0.72f}, {64, 64, 0.58f},
+                             {128, 32, 0.30f},  {32, 128, 0.40f}, {256, 128, 1.00f}};
+const int kOrder[] = {6, 0, 2, 1, 3, 5, 4};
+
 
 }  // namespace
 
@@ -61,10 +66,12 @@ gpulet_status check_conv(const ConvArgs &a) {
     return GPULET_OK;
 }
 
-hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream) {
-    ConvParams p;
+namespace {
+
+// The kernel's parameter block for one layer (tile-dependent fields are filled in by the
+// launchers) and whether its operands allow 16-byte gathers.
+hipError_t make_params(const ConvArgs &a, const LaunchCtx &ctx, ConvParams &p, bool &vec) {
     p.ldx = a.x_ch_stride ? a.x_ch_stride : a.C;
-    const bool dense = p.ldx == a.C;
     p.x = static_cast<const __bf16 *>(a.x) + a.x_ch_offset;
     p.w = static_cast<const __bf16 *>(a.w);
     p.b = a.b;
@@ -104,7 +111,7 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     p.d_s = make_fastdiv(a.S);
     p.d_tiles_n = p.d_split_k = p.d_tw = p.d_ncb = p.d_pwt = p.d_hp = make_fastdiv(1);
 
-    const bool vec = (a.C % CHUNK == 0) && (p.ldx % CHUNK == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
+    vec = (a.C % CHUNK == 0) && (p.ldx % CHUNK == 0) && (reinterpret_cast<uintptr_t>(p.x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
     if (a.y2 && !vec) return hipErrorInvalidValue;  // only the 16-byte gathering kernels store to two tensors
     p.side_blocks = 0;
@@ -120,21 +127,22 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
         sp.d_q = make_fastdiv(a.W);
         sp.d_p = make_fastdiv(a.H);
     }
-    if (a.pre_pool) {
-        // checked by check_conv: 3x3 window, 1x1 filter, stride 1, no padding, C % 8 == 0; the
-        // callers check the 16-byte alignment of x and w
-        if (!vec || !dense) return hipErrorInvalidValue;
-        return launch_pooled_conv(p, stream);
-    }
+    return hipSuccess;
+}
 
+// Which kernel runs a layer: 0..6 a gathering tile (with `split` workgroups per tile), 7 the
+// patch kernel (column block `tw`), 8 the streaming 1x1 kernel, 9 the stem kernel, 10 the
+// resident-weight kernel (column block `tw64`).
+struct Choice {
+    int best, split, tw, tw64;
+};
+
+Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     // Pick the tile and the split of the depth that minimise
     //   (work items on the busiest CU) x (tile area) x (share of the depth + fixed cost of a split) / efficiency.
     // The efficiencies are measured throughput ratios on MI355X (large layers, all CUs busy);
     // on a tie the earlier entry wins.  A split needs the gpu-let's scratch, at least four
     // slices per workgroup, and pays for parking and re-reading fp32 partial tiles.
-    static const TileChoice kTiles[] = {{128, 128, 0.90f}, {128, 64, 0.72f}, {64, 128, 0.72f}, {64, 64, 0.58f},
-                                        {128, 32, 0.30f},  {32, 128, 0.40f}, {256, 128, 1.00f}};
-    static const int kOrder[] = {6, 0, 2, 1, 3, 5, 4};
     const int nk = (p.Kg + BK - 1) / BK;
     const int forced = g_tile_override.load();
     const int max_split = (vec && ctx.scratch && forced < 0) ? g_max_split_k.load() : 1;
@@ -207,16 +215,79 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     }
     if (best == 9 && !stem_applicable(p)) best = 1;
     if (forced < 0 && stem_applicable(p)) best = 9;  // by shape alone: the same bits in every batch and gpu-let
-    switch (best) {
-        case 10: return launch_c64(p, tw64, n_cu, stream);
+    return Choice{best, best_split, tw, tw64};
+}
+
+}  // namespace
+
+hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream) {
+    ConvParams p;
+    bool vec = false;
+    const hipError_t st = make_params(a, ctx, p, vec);
+    if (st != hipSuccess) return st;
+    if (a.pre_pool) {
+        // checked by check_conv: 3x3 window, 1x1 filter, stride 1, no padding, C % 8 == 0; the
+        // callers check the 16-byte alignment of x and w
+        if (!vec || p.ldx != a.C) return hipErrorInvalidValue;
+        return launch_pooled_conv(p, stream);
+    }
+
+    const Choice c = choose_kernel(p, vec, ctx);
+    const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
+    switch (c.best) {
+        case 10: return launch_c64(p, c.tw64, n_cu, stream);
         case 9: return launch_stem(p, n_cu, stream);
         case 8: return launch_stream(p, n_cu, stream);
-        case 7: return launch_patch(p, tw, stream);
+        case 7: return launch_patch(p, c.tw, stream);
         default: {
             const long long tiles128 = 1LL * ((p.M + 127) / 128) * ((p.K + 127) / 128);
-            return launch_igemm(p, vec, best, best_split, tiles128 > n_cu, stream);
+            return launch_igemm(p, vec, c.best, c.split, tiles128 > n_cu, stream);
         }
     }
+}
+
+// Independent layers in one launch.  Every member must be a layer the gathering kernel would
+// run anyway, unsplit: 16-byte gathers, no fused pool, one output, and none of the specialised
+// kernels chosen for its shape; otherwise the members are launched one after the other.  The
+// tile shared by all members minimises the work on the busiest CU over the members' tiles
+// together.  Results are those of separate launches, bit for bit.
+hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hipStream_t stream) {
+    ConvParams p[MAX_GROUP];
+    bool together = n >= 2 && n <= MAX_GROUP;
+    const int forced = g_tile_override.load();
+    for (int j = 0; j < n && together; ++j) {
+        bool vec = false;
+        if (make_params(a[j], ctx, p[j], vec) != hipSuccess || !vec || a[j].pre_pool || a[j].y2 || a[j].pool_y) {
+            together = false;
+            break;
+        }
+        const Choice c = choose_kernel(p[j], vec, ctx);
+        if (c.best > 6 || c.split > 1) together = false;
+    }
+    if (!together) {
+        for (int j = 0; j < n; ++j) {
+            const hipError_t st = launch_conv(a[j], ctx, stream);
+            if (st != hipSuccess) return st;
+        }
+        return hipSuccess;
+    }
+    const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
+    int best = 0;
+    double best_cost = 0.0;
+    for (int o = 0; o < static_cast<int>(sizeof(kOrder) / sizeof(kOrder[0])); ++o) {
+        const TileChoice &t = kTiles[kOrder[o]];
+        long long tiles = 0;
+        for (int j = 0; j < n; ++j) tiles += 1LL * ((p[j].M + t.bm - 1) / t.bm) * ((p[j].K + t.bn - 1) / t.bn);
+        const double cost = static_cast<double>((tiles + n_cu - 1) / n_cu) * t.bm * t.bn / t.eff;
+        if (o == 0 || cost < best_cost) {
+            best = kOrder[o];
+            best_cost = cost;
+        }
+    }
+    if (forced >= 0 && forced <= 6) best = forced;
+    long long tiles128 = 0;
+    for (int j = 0; j < n; ++j) tiles128 += 1LL * ((p[j].M + 127) / 128) * ((p[j].K + 127) / 128);
+    return launch_igemm_group(p, n, best, tiles128 > n_cu, stream);
 }
 
 void set_conv_split_k(int max_split) { g_max_split_k.store(max_split); }

@@ -68,9 +68,10 @@ __device__ __forceinline__ int lds_pos(int row, int chunk) {
 // Workgroups are dealt round-robin to the eight dies, each with its own L2.
 // Give every die a contiguous run of tiles so that tiles sharing a pixel block
 // (all their channel tiles) hit the same L2.
-__device__ __forceinline__ int tile_of_block(const ConvParams &p) {
-    return (blockIdx.x & 7) * p.tiles_per_xcd + (blockIdx.x >> 3);
+__device__ __forceinline__ int tile_of_block(const ConvParams &p, int bid) {
+    return (bid & 7) * p.tiles_per_xcd + (bid >> 3);
 }
+__device__ __forceinline__ int tile_of_block(const ConvParams &p) { return tile_of_block(p, blockIdx.x); }
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
@@ -218,6 +219,14 @@ __device__ __forceinline__ void finish_tile(const ConvParams &p, const float *st
     }
 }
 
+// Several independent layers in one launch of the gathering kernel: workgroups first[j] ..
+// first[j+1]-1 work on layer j (unused entries of `first` hold INT_MAX).
+constexpr int MAX_GROUP = kMaxGroup;
+struct ConvGroup {
+    ConvParams p[MAX_GROUP];
+    int first[MAX_GROUP + 1];
+};
+
 // Patch-based 3x3 kernels: pixels per tile and patch positions per LDS buffer (32 KB).
 constexpr int PATCH_BM = 128;
 constexpr int PATCH_PMAX = 256;
@@ -230,6 +239,8 @@ constexpr int PATCH_PMAX = 256;
 // conv_igemm.hip: gathering tiles 0..6 of gpulet_set_conv_tile (scalar-gather variant when !vec).
 // `two_stage` selects the 64 KB ring of tile 0 (two workgroups per CU).
 hipError_t launch_igemm(const ConvParams &p, bool vec, int tile, int split_k, bool two_stage, hipStream_t stream);
+// n (2..MAX_GROUP) layers, all with 16-byte gathers, one tile shape, no depth split, one launch.
+hipError_t launch_igemm_group(const ConvParams *p, int n, int tile, bool two_stage, hipStream_t stream);
 
 // conv_patch.hip: tile 7 (input patch in LDS) and tile 10 (64 input channels, weights in registers).
 bool patch_eligible(const ConvParams &p, bool vec, int *tw_out);

@@ -29,6 +29,8 @@
 //
 // Channel counts that are not multiples of 8 (image stems, LeNet) take a
 // scalar-gather variant of the same tiling with four wavefronts.
+#include <climits>
+
 #include "conv_common.h"
 
 namespace gpulet {
@@ -83,7 +85,7 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, const f32x16 (&a
 // step has one workgroup barrier: before it a producer waits for its own
 // transfers of slice j, after it the stage slice j-1 occupied is free again.
 template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE>
-__global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int bid) {
     constexpr int NCONS = CWM * CWN;
     constexpr int WM = BM / CWM, WN = BN / CWN;  // consumer wavefront tile
     constexpr int MT = WM / 32, NT = WN / 32;    // MFMA tiles per consumer
@@ -101,16 +103,15 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
 
     // Workgroups past the tiles carry the layer's side job: a max pool of the same input,
     // which would otherwise be a launch of its own with nothing but fixed cost to it.
-    if (POINTWISE && p.side_blocks > 0 && static_cast<int>(blockIdx.x) >= p.tiles_per_xcd * 8) {
-        const int idx = (static_cast<int>(blockIdx.x) - p.tiles_per_xcd * 8) * ((CWM * CWN + NPROD) * 64) +
-                        static_cast<int>(threadIdx.x);
+    if (POINTWISE && p.side_blocks > 0 && bid >= p.tiles_per_xcd * 8) {
+        const int idx = (bid - p.tiles_per_xcd * 8) * ((CWM * CWN + NPROD) * 64) + static_cast<int>(threadIdx.x);
         if (idx < p.side_pool.total) pool_max_item<3>(p.side_pool, idx);
         return;
     }
 
     // Split-K: consecutive work items share an output tile and each takes a
     // contiguous range of depth slices.
-    const int item = tile_of_block(p);
+    const int item = tile_of_block(p, bid);
     if (item >= p.n_tiles * p.split_k) return;
     const int tile = fdiv(item, p.d_split_k), ks = item - tile * p.split_k;
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
@@ -414,6 +415,26 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
                                          [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
 }
 
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE>
+__global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(const ConvParams p) {
+    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, POINTWISE>(p, blockIdx.x);
+}
+
+// Several independent layers in one launch (branches of an inception block, a projection
+// shortcut next to the first layer of its block): each workgroup finds the layer its block
+// index falls into and runs that layer's tile as above.  The general instance serves 1x1
+// members too (its bounds tests always pass for them), so every member's results are the
+// bits of its own launch.
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS>
+__global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_group_kernel(const ConvGroup g) {
+    const int b = blockIdx.x;
+    int j = 0;
+#pragma unroll
+    for (int i = 1; i < MAX_GROUP; ++i)
+        if (b >= g.first[i]) j = i;
+    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, false>(g.p[j], b - g.first[j]);
+}
+
 // ---------------------------------------------------------------------------
 // Any channel count: every element of a chunk is decoded and loaded on its own.
 // Used by the image stems (C = 3) and LeNet (C = 1, 6); one slice of prefetch.
@@ -580,7 +601,48 @@ hipError_t launch_tile(ConvParams p, bool vec, int split_k, hipStream_t stream) 
     return hipGetLastError();
 }
 
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS>
+hipError_t launch_group_tile(const ConvParams *ps, int n, hipStream_t stream) {
+    ConvGroup g;
+    int blocks = 0;
+    for (int j = 0; j < MAX_GROUP; ++j) {
+        g.first[j] = j < n ? blocks : INT_MAX;
+        g.p[j] = ps[j < n ? j : 0];
+        if (j >= n) continue;
+        ConvParams &p = g.p[j];
+        const int tiles_m = (p.M + BM - 1) / BM;
+        p.tiles_n = (p.K + BN - 1) / BN;
+        p.n_tiles = tiles_m * p.tiles_n;
+        p.split_k = 1;
+        p.d_tiles_n = make_fastdiv(p.tiles_n);
+        p.d_split_k = make_fastdiv(1);
+        p.sps = (p.Kg + BK - 1) / BK;
+        p.tiles_per_xcd = (p.n_tiles + 7) / 8;
+        p.side_blocks = 0;
+        blocks += p.tiles_per_xcd * 8;
+    }
+    g.first[MAX_GROUP] = INT_MAX;
+    hipLaunchKernelGGL((conv_igemm_group_kernel<BM, BN, CWM, CWN, NPROD, NS>), dim3(static_cast<unsigned>(blocks)),
+                       dim3((CWM * CWN + NPROD) * 64), 0, stream, g);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_igemm_group(const ConvParams *p, int n, int tile, bool two_stage, hipStream_t stream) {
+    if (n < 2 || n > MAX_GROUP) return hipErrorInvalidValue;
+    switch (tile) {
+        case 0:
+            if (two_stage) return launch_group_tile<128, 128, 4, 2, 4, 2>(p, n, stream);
+            return launch_group_tile<128, 128, 4, 2, 4, 3>(p, n, stream);
+        case 1: return launch_group_tile<128, 64, 4, 2, 4, 3>(p, n, stream);
+        case 2: return launch_group_tile<64, 128, 2, 4, 4, 3>(p, n, stream);
+        case 3: return launch_group_tile<64, 64, 2, 2, 2, 3>(p, n, stream);
+        case 4: return launch_group_tile<128, 32, 4, 1, 2, 3>(p, n, stream);
+        case 5: return launch_group_tile<32, 128, 1, 4, 2, 3>(p, n, stream);
+        default: return launch_group_tile<256, 128, 4, 2, 4, 3>(p, n, stream);
+    }
+}
 
 hipError_t launch_igemm(const ConvParams &p, bool vec, int tile, int split_k, bool two_stage, hipStream_t stream) {
     switch (tile) {

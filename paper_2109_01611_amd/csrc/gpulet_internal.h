@@ -75,6 +75,8 @@ LaunchCtx stream_ctx(hipStream_t stream);
 LaunchCtx partition_ctx(const gpulet_partition *p);
 
 // Kernel launchers (conv.hip, dwconv.hip, pool.hip, fc.hip).  Arguments are validated by the callers.
+constexpr int kMaxGroup = 4;  // layers per launch group
+
 struct ConvArgs {
     const void *x, *w;
     const float *b;
@@ -95,6 +97,9 @@ struct ConvArgs {
     void *pool_y = nullptr;
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
+// n independent layers (no member reads or overwrites what another writes), in one launch where
+// the kernels allow it.
+hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hipStream_t stream);
 void set_conv_tile(int tile);
 void set_conv_split_k(int max_split);
 hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P, int Q, int mode,

@@ -79,6 +79,44 @@ extern "C" gpulet_status gpulet_conv1x1_fwd_two_outputs(const void *x, const voi
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_conv2d_group_fwd(const gpulet_conv_desc *layers, int n, void *stream) {
+    if (!layers || n < 1 || n > kMaxGroup) return GPULET_EINVAL;
+    ConvArgs a[kMaxGroup];
+    struct Range { uintptr_t lo, hi; };
+    Range xr[kMaxGroup], rr[kMaxGroup], yr[kMaxGroup];
+    for (int j = 0; j < n; ++j) {
+        const gpulet_conv_desc &d = layers[j];
+        a[j].x_ch_stride = d.x_ch_stride;
+        a[j].x_ch_offset = d.x_ch_offset;
+        gpulet_status st = make_conv_args(a[j], d.x, d.w, d.b, d.y, d.N, d.C, d.H, d.W, d.K, d.R, d.S, d.stride,
+                                          d.pad, d.relu, d.residual, d.y_ch_stride, d.y_ch_offset);
+        if (st != GPULET_OK) return st;
+        const uintptr_t ldx = static_cast<uintptr_t>(d.x_ch_stride ? d.x_ch_stride : d.C);
+        const uintptr_t px = static_cast<uintptr_t>(d.N) * d.H * d.W, py = static_cast<uintptr_t>(d.N) * a[j].P * a[j].Q;
+        xr[j] = {reinterpret_cast<uintptr_t>(d.x), reinterpret_cast<uintptr_t>(d.x) + 2 * px * ldx};
+        rr[j] = {reinterpret_cast<uintptr_t>(d.residual),
+                 d.residual ? reinterpret_cast<uintptr_t>(d.residual) + 2 * py * d.K : 0};
+        yr[j] = {reinterpret_cast<uintptr_t>(d.y), reinterpret_cast<uintptr_t>(d.y) + 2 * py * a[j].y_ch_stride};
+    }
+    auto meet = [](const Range &p, const Range &q) { return p.lo < q.hi && q.lo < p.hi; };
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) {
+            if (i == j) continue;
+            if (meet(yr[i], xr[j]) || (rr[j].hi && meet(yr[i], rr[j]))) return GPULET_EINVAL;
+            if (i < j && meet(yr[i], yr[j])) {
+                // only as disjoint channel slices of one tensor
+                const bool slices = a[i].y == a[j].y && a[i].y_ch_stride == a[j].y_ch_stride && a[i].P == a[j].P &&
+                                    a[i].Q == a[j].Q && a[i].N == a[j].N &&
+                                    (a[i].y_ch_offset + a[i].K <= a[j].y_ch_offset ||
+                                     a[j].y_ch_offset + a[j].K <= a[i].y_ch_offset);
+                if (!slices) return GPULET_EINVAL;
+            }
+        }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv_group(a, n, stream_ctx(s), s));
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_conv1x1_maxpool3_fwd(const void *x, const void *w, const float *b, void *y,
                                                      void *y2, void *pool_y, int N, int C, int H, int W, int K,
                                                      int k2, int relu, int y_ch_stride, int y_ch_offset,

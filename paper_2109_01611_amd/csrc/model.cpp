@@ -4,6 +4,7 @@
 // interference).
 #include <algorithm>
 #include <atomic>
+#include <climits>
 #include <chrono>
 #include <cmath>
 #include <mutex>
@@ -36,6 +37,7 @@ struct Step {
     const float *b;
     bool slice;             // CONV writing a channel slice of a wider (concatenated) tensor
     bool slice2;            // the same for the second buffer
+    int group_len;          // CONV: layers launched together starting here (1: alone; 0: inside a group)
     int lane;               // stream of the gpu-let this layer runs on
     std::vector<int> wait;  // earlier layers on other lanes this one must wait for
     bool record;            // a later layer on another lane waits for this one
@@ -169,6 +171,7 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         s.res_buf = -1;
         s.out2_buf = -1;
         s.pool_buf = -1;
+        s.group_len = 1;
         s.slice2 = false;
         s.w = L.w;
         s.b = L.b;
@@ -266,6 +269,46 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         plan.steps.push_back(s);
     }
     if (!plan.bufs[static_cast<size_t>(m->out_buf)].written) return GPULET_EINVAL;
+    // Launch groups: runs of layers chained by group_next.  All members are convolutions and
+    // none reads or overwrites what another member writes (channel slices of one concatenated
+    // tensor count as different destinations when they do not intersect).
+    for (int i = 0; i < m->n_layers;) {
+        int len = 1;
+        while (m->layers[i + len - 1].group_next) {
+            if (i + len >= m->n_layers || len >= kMaxGroup) return GPULET_EINVAL;
+            ++len;
+        }
+        if (len > 1) {
+            struct Span { int buf, lo, hi; };  // channels [lo, hi) of a buffer; the whole buffer: lo = 0, hi = INT_MAX
+            auto writes = [&](int li) {
+                const Step &s = plan.steps[static_cast<size_t>(li)];
+                std::vector<Span> w;
+                w.push_back(s.slice ? Span{s.out_buf, s.conv.y_ch_offset, s.conv.y_ch_offset + (s.out2_buf >= 0 ? s.conv.k2 : s.conv.K)}
+                                    : Span{s.out_buf, 0, INT_MAX});
+                if (s.out2_buf >= 0)
+                    w.push_back(s.slice2 ? Span{s.out2_buf, s.conv.y2_ch_offset, s.conv.y2_ch_offset + s.conv.K - s.conv.k2}
+                                         : Span{s.out2_buf, 0, INT_MAX});
+                if (s.pool_buf >= 0) w.push_back(Span{s.pool_buf, 0, INT_MAX});
+                return w;
+            };
+            for (int a = i; a < i + len; ++a) {
+                if (plan.steps[static_cast<size_t>(a)].op != GPULET_OP_CONV) return GPULET_EINVAL;
+                for (int b = i; b < i + len; ++b) {
+                    if (a == b) continue;
+                    const Step &sb = plan.steps[static_cast<size_t>(b)];
+                    for (const Span &w : writes(a)) {
+                        if (w.buf == sb.in_buf || w.buf == sb.res_buf) return GPULET_EINVAL;
+                        if (a < b)
+                            for (const Span &v : writes(b))
+                                if (v.buf == w.buf && v.lo < w.hi && w.lo < v.hi) return GPULET_EINVAL;
+                    }
+                }
+            }
+            plan.steps[static_cast<size_t>(i)].group_len = len;
+            for (int a = i + 1; a < i + len; ++a) plan.steps[static_cast<size_t>(a)].group_len = 0;
+        }
+        i += len;
+    }
     assign_lanes(plan, m->n_bufs, g_model_lanes.load());
 
     plan.offset.assign(static_cast<size_t>(m->n_bufs), static_cast<size_t>(-1));
@@ -337,6 +380,41 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
             e = pool_event(p, kMaxLanes + static_cast<size_t>(d), &ev);
             if (e == hipSuccess) e = hipStreamWaitEvent(stream, ev, 0);
             if (e != hipSuccess) return e;
+        }
+        // A launch group whose members all sit on this lane goes out as one launch, after the
+        // waits of every member; otherwise its members are launched one by one as usual.
+        size_t len = s.group_len > 1 ? static_cast<size_t>(s.group_len) : 1;
+        for (size_t k = 1; k < len; ++k)
+            if (steps[i + k].lane != s.lane) len = 1;
+        if (len > 1) {
+            ConvArgs args[kMaxGroup];
+            for (size_t k = 0; k < len; ++k) {
+                const Step &sk = steps[i + k];
+                for (int d : sk.wait) {
+                    if (k == 0) break;  // waited for above
+                    hipEvent_t ev;
+                    e = pool_event(p, kMaxLanes + static_cast<size_t>(d), &ev);
+                    if (e == hipSuccess) e = hipStreamWaitEvent(stream, ev, 0);
+                    if (e != hipSuccess) return e;
+                }
+                args[k] = sk.conv;
+                args[k].x = bd.ptr(sk.in_buf);
+                args[k].y = bd.ptr(sk.out_buf);
+                args[k].residual = sk.res_buf >= 0 ? bd.ptr(sk.res_buf) : nullptr;
+                args[k].y2 = sk.out2_buf >= 0 ? bd.ptr(sk.out2_buf) : nullptr;
+                args[k].pool_y = sk.pool_buf >= 0 ? bd.ptr(sk.pool_buf) : nullptr;
+            }
+            e = launch_conv_group(args, static_cast<int>(len), ctx, stream);
+            if (e != hipSuccess) return e;
+            for (size_t k = 0; k < len; ++k) {
+                if (!steps[i + k].record) continue;
+                hipEvent_t ev;
+                e = pool_event(p, kMaxLanes + i + k, &ev);
+                if (e == hipSuccess) e = hipEventRecord(ev, stream);
+                if (e != hipSuccess) return e;
+            }
+            i += len - 1;
+            continue;
         }
         if (s.op == GPULET_OP_CONV) {
             ConvArgs a = s.conv;

@@ -40,7 +40,15 @@ class Layer(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in (
         "op", "in_buf", "out_buf", "res_buf", "C", "K", "R", "S", "stride", "pad", "relu", "mode",
         "out_ch_total", "out_ch_offset", "out_fp32", "pre_pool", "in_ch_total", "in_ch_offset", "K2", "out2_buf",
-        "out2_ch_total", "out2_ch_offset", "side_pool", "pool_buf")] + [("w", c_void_p), ("b", c_void_p)]
+        "out2_ch_total", "out2_ch_offset", "side_pool", "pool_buf",
+        "group_next")] + [("w", c_void_p), ("b", c_void_p)]
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of ``gpulet_conv_desc``."""
+    _fields_ = [("x", c_void_p), ("w", c_void_p), ("b", c_void_p), ("y", c_void_p), ("residual", c_void_p)] + \
+               [(n, c_int32) for n in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad", "relu",
+                                       "x_ch_stride", "x_ch_offset", "y_ch_stride", "y_ch_offset")]
 
 
 class SchedModel(ctypes.Structure):
@@ -97,6 +105,7 @@ def _load():
         "gpulet_conv2d_fwd_slices": ([P, P, P, P] + [I] * 10 + [P, I, I, I, I, P], c_int32),
         "gpulet_conv1x1_fwd_two_outputs": ([P, P, P, P, P] + [I] * 14 + [P], c_int32),
         "gpulet_conv1x1_maxpool3_fwd": ([P, P, P, P, P, P] + [I] * 11 + [P], c_int32),
+        "gpulet_conv2d_group_fwd": ([POINTER(ConvDesc), I, P], c_int32),
         "gpulet_set_conv_tile": ([I], c_int32),
         "gpulet_set_conv_split_k": ([I], c_int32),
         "gpulet_depthwise_conv2d_fwd": ([P, P, P, P] + [I] * 9 + [P], c_int32),
@@ -239,6 +248,16 @@ def conv1x1_maxpool3_fwd(x, w, b, y, y2, pool_y, N, C, H, W, K, k2, relu, y_ch_s
     _check(lib.gpulet_conv1x1_maxpool3_fwd(ptr(x), ptr(w), ptr(b), ptr(y), ptr(y2), ptr(pool_y), N, C, H, W, K, k2,
                                            int(relu), y_ch_stride, y_ch_offset, y2_ch_stride, y2_ch_offset, stream),
            "gpulet_conv1x1_maxpool3_fwd")
+
+
+def conv2d_group_fwd(layers, stream=None):
+    """``layers``: dicts with the fields of ``gpulet_conv_desc`` (tensors or addresses for the pointers;
+    residual, b and the slice fields optional)."""
+    arr = (ConvDesc * len(layers))()
+    for d, kw in zip(arr, layers):
+        for k, v in kw.items():
+            setattr(d, k, ptr(v) if k in ("x", "w", "b", "y", "residual") else int(v))
+    _check(lib.gpulet_conv2d_group_fwd(arr, len(layers), stream), "gpulet_conv2d_group_fwd")
 
 
 def set_conv_tile(tile):

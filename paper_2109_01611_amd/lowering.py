@@ -129,7 +129,7 @@ class DeviceModel:
         #     tensor, the others to the second output of the same launch.
         # Every output element is the same sum in the same order, so the bits do not change;
         # ``merged`` lists the groups.
-        self.merged, self.side_pools = [], []
+        self.merged, self.side_pools, self.groups = [], [], []
         if merge_siblings:
             readers = {}
             for nd in nodes:
@@ -241,6 +241,53 @@ class DeviceModel:
             nodes = [nd._replace(attr=dict(nd.attr, pool_dst=riders[nd.name].dst)) if nd.name in riders else nd
                      for nd in kept]
             self.side_pools = [r.name for r in riders.values()]
+            # Independent convolutions share a launch (``groups``): a sibling that reads the same
+            # tensor is first moved next to its sibling when nothing in between stands in the way (a
+            # projection shortcut next to the first layer of its residual block), then runs of
+            # adjacent convolutions that neither read nor overwrite one another's tensors are chained.
+            def reads_of(nd):
+                r = list(nd.src) if nd.op == "concat" else [nd.src]
+                if nd.op == "conv" and nd.attr["residual"]:
+                    r.append(nd.attr["residual"])
+                return r
+
+            def shareable(nd):
+                a = nd.attr
+                return (nd.op == "conv" and a["C"] % 8 == 0 and nd.src != "x" and not a.get("pre_pool")
+                        and "dst2" not in a and "pool_dst" not in a)
+
+            def independent(p, q):
+                if p.dst in reads_of(q) or q.dst in reads_of(p):
+                    return False
+                sp, sq = storage(p.dst), storage(q.dst)
+                return sp != sq or (p.dst in alias and q.dst in alias)
+
+            def storage(t):
+                return alias[t][0] if t in alias else t
+
+            i = 0
+            while i < len(nodes):
+                if shareable(nodes[i]):
+                    for j in range(i + 2, min(i + 4, len(nodes))):
+                        between = nodes[i + 1:j]
+                        if (shareable(nodes[j]) and nodes[j].src == nodes[i].src
+                                and all(b.op != "concat" and independent(b, nodes[j]) for b in between)):
+                            nodes.insert(i + 1, nodes.pop(j))
+                            break
+                i += 1
+            self.groups, run = [], []
+            for k, nd in enumerate(nodes + [None]):
+                if nd is not None and nd.op == "concat":
+                    continue            # emits no layer: members on either side of it stay neighbours
+                if (nd is not None and shareable(nd) and len(run) < 4
+                        and all(independent(nodes[m], nd) for m in run)):
+                    run.append(k)
+                    continue
+                if len(run) >= 2:
+                    for m in run[:-1]:
+                        nodes[m] = nodes[m]._replace(attr=dict(nodes[m].attr, group_next=1))
+                    self.groups.append([nodes[m].name for m in run])
+                run = [k] if nd is not None and shareable(nd) else []
         producers = {nd.dst: nd for nd in nodes}
         for s in alias:
             if producers[s].op != "conv":
@@ -311,6 +358,7 @@ class DeviceModel:
                 L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, C, a["K"], a["k"], a["k"]
                 L.stride, L.pad, L.relu = a["stride"], a["pad"], int(a["relu"])
                 L.pre_pool = a.get("pre_pool", 0)
+                L.group_next = a.get("group_next", 0)
                 if "in_slice" in a:
                     L.in_ch_offset, L.in_ch_total = a["in_slice"]
                 if a["residual"]:
@@ -348,9 +396,12 @@ class DeviceModel:
                 raise ValueError("unknown node kind %r" % (nd.op,))
             layers.append(L)
             self.tensor_buf[nd.dst] = buf_of[st]
-            # release buffers whose last reader was this node (never the input or output)
+            # release buffers whose last reader was this node (never the input or output); inside a
+            # launch group only after its last member, whose launch is also the other members'
+            if nd.op == "conv" and nd.attr.get("group_next"):
+                continue
             for t, last in list(last_use.items()):
-                if reuse and last == i and t in buf_of and buf_of[t] > 1:
+                if reuse and last <= i and t in buf_of and buf_of[t] > 1:
                     free.append(buf_of.pop(t))
                     del last_use[t]
 

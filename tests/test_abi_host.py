@@ -125,6 +125,22 @@ def test_layer_calls_reject_bad_arguments_before_touching_the_gpu():
         with pytest.raises(gpulet.GpuletError) as e:
             gpulet.conv2d_fwd_slices(x, w, None, y, residual=None, x_ch_stride=xs, x_ch_offset=xo, **ok)
         assert e.value.status == gpulet.EINVAL
+    # launch groups: members must not depend on one another
+    m0 = dict(x=1 << 20, w=w, y=2 << 20, **ok)
+    for m1 in (dict(x=2 << 20, w=w, y=3 << 20, **ok),                    # reads what the other writes
+               dict(x=1 << 20, w=w, y=2 << 20, **ok),                    # writes the same tensor
+               dict(x=1 << 20, w=w, y=3 << 20, residual=(2 << 20) + 64, **ok),
+               dict(x=1 << 20, w=w, y=(2 << 20) - 64, **ok),             # outputs overlap
+               dict(x=1 << 20, w=w, y=2 << 20, y_ch_stride=16, y_ch_offset=4, **ok)):  # slices of different tensors
+        with pytest.raises(gpulet.GpuletError) as e:
+            gpulet.conv2d_group_fwd([m0, m1])
+        assert e.value.status == gpulet.EINVAL, m1
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.conv2d_group_fwd([m0] * 5)
+    assert e.value.status == gpulet.EINVAL
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.conv2d_group_fwd([m0, dict(m0, y=3 << 20, C=0)])
+    assert e.value.status == gpulet.EINVAL
     with pytest.raises(gpulet.GpuletError):
         gpulet.pool(x, y, 1, 8, 8, 8, gpulet.POOL_MAX, k=2, stride=2, pad=2)    # pad >= k
     with pytest.raises(gpulet.GpuletError):
@@ -251,6 +267,27 @@ def test_model_description_errors():
     bad(head + [_layer(side_pool=3, pool_buf=5, **rider)] + tail, n_bufs=5)
     bad(head + [_layer(side_pool=3, pool_buf=4, **dict(rider, R=3, S=3, pad=1))] + tail, n_bufs=5)
     bad(head + [_layer(**rider)] + tail, n_bufs=5)                               # buffer 4 never written
+    # launch groups: convolutions only, independent of one another, at most four, inside the table
+    g0 = dict(op=gpulet.OP_CONV, in_buf=0, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W)
+    fin = [_layer(op=gpulet.OP_CONV, in_buf=2, out_buf=1, C=8, K=8, R=1, S=1, stride=1, pad=0, w=W, res_buf=3)]
+    assert gpulet.model_workspace_bytes(
+        _desc([_layer(out_buf=2, group_next=1, **g0), _layer(out_buf=3, **g0)] + fin, 4, (3, 8, 8)), 1) == 2 * 8 * 8 * 8 * 2
+    bad([_layer(out_buf=2, group_next=1, **g0), _layer(out_buf=2, **g0)] + fin, n_bufs=4)     # same destination
+    bad([_layer(out_buf=2, group_next=1, **g0),
+         _layer(op=gpulet.OP_CONV, in_buf=2, out_buf=3, C=8, K=8, R=1, S=1, stride=1, pad=0, w=W)] + fin, n_bufs=4)
+    bad([_layer(out_buf=2, group_next=1, **g0), _layer(op=gpulet.OP_POOL, in_buf=0, out_buf=3, C=3, R=3, stride=1,
+                                                       pad=1, mode=gpulet.POOL_MAX)], n_bufs=4)
+    bad([_layer(out_buf=2, **g0), _layer(out_buf=3, **g0),                                    # chain runs off the table
+         _layer(op=gpulet.OP_CONV, in_buf=2, out_buf=1, C=8, K=8, R=1, S=1, stride=1, pad=0, w=W, res_buf=3,
+                group_next=1)], n_bufs=4)
+    bad([_layer(out_buf=b, group_next=1, **g0) for b in (2, 3, 4, 5)] + [_layer(out_buf=6, **g0)] + fin, n_bufs=7)
+    # two slices of one tensor are fine, overlapping ones are not
+    cat = [_layer(op=gpulet.OP_CONV, in_buf=2, out_buf=1, C=16, K=8, R=1, S=1, stride=1, pad=0, w=W)]
+    assert gpulet.model_workspace_bytes(
+        _desc([_layer(out_buf=2, out_ch_total=16, out_ch_offset=0, group_next=1, **g0),
+               _layer(out_buf=2, out_ch_total=16, out_ch_offset=8, **g0)] + cat, 3, (3, 8, 8)), 1) == 16 * 8 * 8 * 2
+    bad([_layer(out_buf=2, out_ch_total=16, out_ch_offset=0, group_next=1, **g0),
+         _layer(out_buf=2, out_ch_total=16, out_ch_offset=4, **g0)] + cat)
     # residual of the wrong shape
     bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=2, pad=1, w=W),
          _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])

@@ -314,6 +314,75 @@ def test_side_pool_arguments_are_checked(part):
     assert e.value.status == gpulet.EINVAL
 
 
+def _group_members(seed, N, H, W, specs, wide_c):
+    """Members reading channel slices of one wide tensor and writing slices of one concatenated tensor.
+    specs: (first input channel, C, K, R, stride, pad, relu)."""
+    wide = inputs.tensor(seed, "grp/x%d_%d_%d_%d" % (N, wide_c, H, W), (N, wide_c, H, W), "normal")
+    out = []
+    for j, (xo, C, K, R, stride, pad, relu) in enumerate(specs):
+        w = inputs.he_normal(seed, "grp/w%d_%d_%d_%d" % (j, K, C, R), (K, C, R, R))
+        b = inputs.bias(seed, "grp/b%d_%d" % (j, K), K)
+        out.append((xo, C, K, R, stride, pad, relu, w, b))
+    return wide, out
+
+
+GROUP_CASES = [
+    # inception 3a after the 1x1 layers: 3x3 over channels 0..95, 5x5 over 96..111, 1x1 over another tensor's worth
+    (3, 28, 28, 112, [(0, 96, 128, 3, 1, 1, True), (96, 16, 32, 5, 1, 2, True), (0, 112, 32, 1, 1, 0, True)]),
+    # a residual block's first layer next to its strided projection (different output sizes: no shared tensor)
+    (2, 28, 28, 256, [(0, 256, 128, 1, 1, 0, True), (0, 256, 512, 1, 2, 0, False)]),
+    # four members, ragged everything
+    (2, 9, 11, 72, [(0, 72, 40, 3, 1, 1, True), (8, 24, 16, 1, 1, 0, False), (32, 40, 72, 5, 1, 2, True),
+                    (0, 8, 8, 3, 1, 1, True)]),
+    # a member with an odd filter count takes the element-wise epilogue
+    (1, 7, 7, 64, [(0, 64, 21, 3, 1, 1, True), (0, 64, 64, 1, 1, 0, True)]),
+]
+
+
+@pytest.mark.parametrize("case", GROUP_CASES, ids=lambda c: "x".join(map(str, c[:4])))
+def test_independent_convs_in_one_launch(part, case):
+    N, H, W, wide_c, specs = case
+    wide, members = _group_members(35, N, H, W, specs, wide_c)
+    xd = lowering.nchw_to_nhwc(wide, DEV)
+    same_size = len({(H + 2 * m[5] - m[3]) // m[4] + 1 for m in members}) == 1
+    total = sum(m[2] for m in members) + 8
+    refs, alone, descs, outs = [], [], [], []
+    off = 8
+    for (xo, C, K, R, stride, pad, relu, w, b) in members:
+        x = np.ascontiguousarray(wide[:, xo:xo + C])
+        refs.append(oracle.conv2d(x, w, b, stride, pad, relu))
+        alone.append(gpu_conv(part, x, w, b, stride, pad, relu)[1])
+        P, Q = refs[-1].shape[2], refs[-1].shape[3]
+        wd, bd = lowering.kcrs_to_krsc(w, DEV), torch.from_numpy(b).to(DEV)
+        descs.append(dict(x=xd, w=wd, b=bd, N=N, C=C, H=H, W=W, K=K, R=R, S=R, stride=stride, pad=pad, relu=relu,
+                          x_ch_stride=wide_c, x_ch_offset=xo))
+        outs.append((P, Q, K, off))
+        off += K
+    for tile in range(-1, 11):
+        if same_size:       # slices of one concatenated tensor
+            cat = torch.full((N, outs[0][0], outs[0][1], total), -512.0, dtype=torch.bfloat16, device=DEV)
+            ys = [cat] * len(members)
+            for d, (P, Q, K, o) in zip(descs, outs):
+                d.update(y=cat, y_ch_stride=total, y_ch_offset=o)
+        else:
+            ys = [torch.full((N, P, Q, K), -512.0, dtype=torch.bfloat16, device=DEV) for (P, Q, K, o) in outs]
+            for d, y in zip(descs, ys):
+                d.update(y=y, y_ch_stride=0, y_ch_offset=0)
+        torch.cuda.synchronize()
+        gpulet.set_conv_tile(tile)
+        try:
+            gpulet.conv2d_group_fwd(descs, part.stream)
+            part.sync()
+        finally:
+            gpulet.set_conv_tile(-1)
+        for j, (P, Q, K, o) in enumerate(outs):
+            got = ys[j][..., o:o + K] if same_size else ys[j]
+            assert torch.equal(got, alone[j]), (tile, j)                 # the bits of the member's own launch
+            assert oracle.rel_err(lowering.nhwc_to_nchw(got), refs[j])[1] <= LAYER_TOL, (tile, j)
+        if same_size:
+            assert bool((cat[..., :8] == -512.0).all())
+
+
 # N, H, W, K: 3x3, stride 1, pad 1, exactly 64 input channels -> weights resident in registers (tile 10)
 C64_CASES = [
     (3, 14, 14, 64),        # whole rows per block; M = 588: ragged last tile, fewer tiles than workgroups

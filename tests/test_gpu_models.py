@@ -218,6 +218,10 @@ def test_inception_1x1_layers_of_a_block_run_as_one_convolution(width_div, in_hw
     # and every block's 3x3 / stride 1 max pool rides along with that launch
     assert merged.side_pools == ["i%s_pool" % b for b in ("3a", "3b", "4a", "4b", "4c", "4d", "4e", "5a", "5b")]
     assert merged.desc.n_layers == plain.desc.n_layers - sum(n - 1 for n in sizes) - 9
+    # and the 3x3, 5x5 and pooling-branch layers of a block share a launch
+    # (at half width two blocks have a 5x5 layer with 12 input channels, which cannot share)
+    assert [len(g) for g in merged.groups] == ([3] * 9 if width_div == 1 else [3, 3, 3, 2, 2, 3, 3, 3, 3])
+    assert not plain.groups
     with gpulet.Partition(0, 100, 0) as p:
         a, _ = merged.run(p, merged.input_to_device(x))
         b, _ = plain.run(p, plain.input_to_device(x))
@@ -233,6 +237,9 @@ def test_ssd_box_and_class_heads_run_as_one_convolution():
     merged = lowering.DeviceModel(model, params, DEV, reuse=False, merge_siblings=True)
     plain = lowering.DeviceModel(model, params, DEV, reuse=False, merge_siblings=False)
     assert merged.merged == [["box%d" % m, "cls%d" % m] for m in range(1, 7)] and not plain.merged
+    # the six merged heads are independent of one another: two launches instead of six
+    assert merged.groups == [["extra4_b"] + ["box%d+cls%d" % (m, m) for m in (1, 2, 3)],
+                             ["box%d+cls%d" % (m, m) for m in (4, 5, 6)]]
     with gpulet.Partition(0, 100, 0) as p:
         a, _ = merged.run(p, merged.input_to_device(x))
         b, _ = plain.run(p, plain.input_to_device(x))
@@ -241,6 +248,24 @@ def test_ssd_box_and_class_heads_run_as_one_convolution():
         assert torch.equal(merged.read_tensor("head%d" % m, 3), plain.read_tensor("head%d" % m, 3)), m
     ref = oracle.run_model(model, params, x).reshape(3, -1)
     _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(3, -1), ref)
+
+
+def test_projection_shortcut_shares_a_launch_with_the_blocks_first_layer():
+    model = workloads.resnet50(width_div=2, in_hw=96, n_class=20, blocks=(2, 2, 2, 2))
+    params = workloads.parameters(model, 13)
+    x = workloads.batch_input(model, 3, 13)
+    grouped = lowering.DeviceModel(model, params, DEV)
+    plain = lowering.DeviceModel(model, params, DEV, merge_siblings=False)
+    assert grouped.groups == [["l%d_0_a" % s, "l%d_0_proj" % s] for s in (1, 2, 3, 4)] and not plain.groups
+    with gpulet.Partition(0, 100, 0) as p:
+        a, _ = grouped.run(p, grouped.input_to_device(x))
+        b, _ = plain.run(p, plain.input_to_device(x))
+        assert torch.equal(a, b)
+    with gpulet.Partition(0, 40, 1) as p:           # another CU count, other tiles
+        c, _ = grouped.run(p, grouped.input_to_device(x))
+    assert torch.equal(a, c)
+    ref = oracle.run_model(model, params, x).reshape(3, -1)
+    _assert_close(a.cpu().numpy().astype(np.float64).reshape(3, -1), ref)
 
 
 def test_batch_size_does_not_change_an_images_result():
