@@ -123,6 +123,12 @@ gpulet_status gpulet_partition_query_mask(const gpulet_partition *p, uint32_t ma
 gpulet_status gpulet_partition_counters(const gpulet_partition *p, uint64_t *batches_run,
                                         uint64_t *images_run);
 
+/* Kernel launches enqueued on this gpu-let by gpulet_run_model, gpulet_profile_model
+ * and gpulet_profile_corun since it was created (layers that share a launch count
+ * once; graph replays launch no kernels from the host and are not counted).  Lets a
+ * profiler attribute per-dispatch counters to batches. */
+gpulet_status gpulet_partition_kernel_launches(const gpulet_partition *p, uint64_t *launches);
+
 /* Blocks until all work enqueued on the gpu-let's stream has finished. */
 gpulet_status gpulet_partition_sync(gpulet_partition *p);
 

@@ -251,7 +251,7 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
 // kernels chosen for its shape; otherwise the members are launched one after the other.  The
 // tile shared by all members minimises the work on the busiest CU over the members' tiles
 // together.  Results are those of separate launches, bit for bit.
-hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hipStream_t stream) {
+hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hipStream_t stream, int *launches) {
     ConvParams p[MAX_GROUP];
     bool together = n >= 2 && n <= MAX_GROUP;
     const int forced = g_tile_override.load();
@@ -264,6 +264,7 @@ hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hip
         const Choice c = choose_kernel(p[j], vec, ctx);
         if (c.best > 6 || c.split > 1) together = false;
     }
+    if (launches) *launches = together ? 1 : n;
     if (!together) {
         for (int j = 0; j < n; ++j) {
             const hipError_t st = launch_conv(a[j], ctx, stream);

@@ -47,6 +47,7 @@ struct gpulet_partition {
     int n_counters;
     std::atomic<uint64_t> batches_run;
     std::atomic<uint64_t> images_run;
+    std::atomic<uint64_t> kernels_enqueued;  // kernel launches of eager model runs (a launch group counts once)
 };
 
 namespace gpulet {
@@ -99,7 +100,9 @@ struct ConvArgs {
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 // n independent layers (no member reads or overwrites what another writes), in one launch where
 // the kernels allow it.
-hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hipStream_t stream);
+// *launches (if not null) receives the number of kernel launches made: 1 or n.
+hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hipStream_t stream,
+                             int *launches = nullptr);
 void set_conv_tile(int tile);
 void set_conv_split_k(int max_split);
 hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P, int Q, int mode,

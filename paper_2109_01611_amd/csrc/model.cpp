@@ -404,8 +404,10 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
                 args[k].y2 = sk.out2_buf >= 0 ? bd.ptr(sk.out2_buf) : nullptr;
                 args[k].pool_y = sk.pool_buf >= 0 ? bd.ptr(sk.pool_buf) : nullptr;
             }
-            e = launch_conv_group(args, static_cast<int>(len), ctx, stream);
+            int launches = 0;
+            e = launch_conv_group(args, static_cast<int>(len), ctx, stream, &launches);
             if (e != hipSuccess) return e;
+            p->kernels_enqueued.fetch_add(static_cast<uint64_t>(launches));
             for (size_t k = 0; k < len; ++k) {
                 if (!steps[i + k].record) continue;
                 hipEvent_t ev;
@@ -435,6 +437,7 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
                           stream);
         }
         if (e != hipSuccess) return e;
+        p->kernels_enqueued.fetch_add(1);
         if (s.record) {
             hipEvent_t ev;
             e = pool_event(p, kMaxLanes + i, &ev);

@@ -162,6 +162,7 @@ extern "C" gpulet_status gpulet_partition_create(int device, int pct, int which,
     p->n_counters = kCounters;
     p->batches_run.store(0);
     p->images_run.store(0);
+    p->kernels_enqueued.store(0);
     g_live.push_back(p);
     *out = p;
     return GPULET_OK;
@@ -226,6 +227,12 @@ extern "C" gpulet_status gpulet_partition_counters(const gpulet_partition *p, ui
     if (!live(p)) return GPULET_EINVAL;
     if (batches_run) *batches_run = p->batches_run.load();
     if (images_run) *images_run = p->images_run.load();
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_partition_kernel_launches(const gpulet_partition *p, uint64_t *launches) {
+    if (!live(p) || !launches) return GPULET_EINVAL;
+    *launches = p->kernels_enqueued.load();
     return GPULET_OK;
 }
 

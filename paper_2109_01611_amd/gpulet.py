@@ -93,6 +93,7 @@ def _load():
                                    POINTER(c_uint32), POINTER(I), POINTER(P)], c_int32),
         "gpulet_partition_query_mask": ([P, POINTER(c_uint32), POINTER(I)], c_int32),
         "gpulet_partition_counters": ([P, POINTER(c_uint64), POINTER(c_uint64)], c_int32),
+        "gpulet_partition_kernel_launches": ([P, POINTER(c_uint64)], c_int32),
         "gpulet_partition_sync": ([P], c_int32),
         "gpulet_partition_probe": ([P, P, I], c_int32),
         "gpulet_partition_probe_ex": ([P, P, I, I], c_int32),
@@ -197,6 +198,11 @@ class Partition:
         b, i = c_uint64(), c_uint64()
         _check(lib.gpulet_partition_counters(self.handle, byref(b), byref(i)), "gpulet_partition_counters")
         return b.value, i.value
+
+    def kernel_launches(self):
+        n = c_uint64()
+        _check(lib.gpulet_partition_kernel_launches(self.handle, byref(n)), "gpulet_partition_kernel_launches")
+        return n.value
 
     def sync(self):
         _check(lib.gpulet_partition_sync(self.handle), "gpulet_partition_sync")

@@ -70,11 +70,13 @@ def solo(manifest_path):
             for name in MODELS:
                 for b in BATCHES:
                     bd = bounds[name][b]
+                    before = part.kernel_launches()
                     for _ in range(2):          # the second run is the one that counts (weights seen once)
                         gpulet.run_model(*bd.args(part))
                         part.sync()
-                    manifest.append({"model": name, "batch": b, "pct": pct, "kernels": int(bd.dm.desc.n_layers),
-                                     "runs": 2})
+                    # launches per run (layers that share a launch count once), as the counter pass sees them
+                    manifest.append({"model": name, "batch": b, "pct": pct,
+                                     "kernels": int(part.kernel_launches() - before) // 2, "runs": 2})
     src = torch.empty(COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda:0").normal_()
     dst = torch.empty_like(src)
     torch.cuda.synchronize()

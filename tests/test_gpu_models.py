@@ -224,8 +224,15 @@ def test_inception_1x1_layers_of_a_block_run_as_one_convolution(width_div, in_hw
     assert not plain.groups
     with gpulet.Partition(0, 100, 0) as p:
         a, _ = merged.run(p, merged.input_to_device(x))
+        n_merged = p.kernel_launches()
         b, _ = plain.run(p, plain.input_to_device(x))
+        n_plain = p.kernel_launches() - n_merged
     assert torch.equal(a, b)            # merging does not change a bit
+    assert n_plain == plain.desc.n_layers == 72
+    if width_div == 1:                  # two launches per block, the stem's five, two pools, average pool, FC
+        assert n_merged == 27
+    else:
+        assert n_merged <= merged.desc.n_layers - 9
     ref = oracle.run_model(model, params, x).reshape(2, -1)
     _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(2, -1), ref)
 
