@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstddef>
 
 #include "device_util.h"
 #include "gpulet_internal.h"
@@ -26,37 +27,55 @@ constexpr int NTHREADS = 256;  // scalar-gather variant: four wavefronts
 constexpr unsigned OOB = 0x80000000u;      // byte offset past every buffer: the load returns zeros
 constexpr int RSRC_FLAGS = 0x00020000;     // raw buffer descriptor, 32-bit data format
 
-struct ConvParams {
+// The argument block of every convolution kernel.  A kernel fetches only the 64-byte lines of
+// it that hold fields it reads, and each line costs a fraction of a microsecond at the start
+// of every workgroup, so the fields are ordered by who reads them: lines 0-2 serve every
+// kernel, line 3 adds what filters larger than 1x1 and the patch kernels need, the rest is
+// for layers with a depth split, a second output or a pooling side job.
+struct alignas(64) ConvParams {
+    // ---- line 0
     const __bf16 *x, *w;
     const float *b;
     __bf16 *y;
     const __bf16 *res;
-    int N, C, H, W, K, R, S, stride, pad, relu, P, Q;
+    int N, C, H, W, K, R;
+    // ---- line 1
+    int S, stride, pad, relu, P, Q;
     int M, Kg;          // GEMM rows and depth
     int ldy, y_off;     // channels per output pixel of the destination, first channel
-    // Second destination (1x1 gathering kernels only): filters k >= k2 are stored to
-    // y2[m * ldy2 + y2_off + k - k2] instead; k2 == K means there is none.
-    __bf16 *y2;
-    int k2, ldy2, y2_off;
-    // Side job (1x1 gathering kernels only): side_blocks extra workgroups at the end of the grid
-    // compute the 3x3 / stride 1 / pad 1 max pool side_pool of the layer's (dense) input.
-    PoolParams side_pool;
-    int side_blocks;
     int ldx;            // channels per input pixel as stored (x points at the layer's first channel);
                         // only the gathering kernels accept ldx != C
+    int k2;             // first filter that goes to the second destination (K: there is none)
+    int side_blocks;    // workgroups at the end of the grid that run the pooling side job
     int tiles_n, n_tiles, tiles_per_xcd;
+    // ---- line 2
     unsigned x_bytes, w_bytes;
     int tap_inner;      // depth order: 64-channel block outermost, filter taps inside it
     int vec_store;      // output (and residual) rows allow aligned 16-byte accesses
     int split_k;        // workgroups sharing one output tile, each taking a contiguous range of slices
     int sps;            // slices per split
+    FastDiv d_pq, d_q, d_tiles_n, d_split_k, d_c;   // by P*Q, Q, tiles_n, split_k, C
+    // ---- line 3
+    FastDiv d_s, d_p;   // by S, P
+    // Patch kernels only: output pixels are grouped in column blocks of `tw` pixels.
+    int tw, n_cb;       // block width, blocks per output row
+    FastDiv d_tw, d_ncb, d_pwt, d_hp;               // by tw, n_cb, tw + 2, H + 2*pad
+    int pad3[2];
+    // ---- line 4 and on
     float *part;        // split-K scratch: [n_tiles * split_k][BM * BN] fp32 partial tiles
     unsigned *cnt;      // split-K scratch: arrival counter per tile (zero between launches)
-    // Patch kernel only: output pixels are grouped in column blocks of `tw` pixels.
-    int tw, n_cb;       // block width, blocks per output row
-    FastDiv d_pq, d_q, d_p, d_tiles_n, d_split_k, d_c, d_s;   // by P*Q, Q, P, tiles_n, split_k, C, S
-    FastDiv d_tw, d_ncb, d_pwt, d_hp;                         // patch kernel: by tw, n_cb, tw + 2, H + 2*pad
+    // Second destination (1x1 gathering kernels only): filters k >= k2 are stored to
+    // y2[m * ldy2 + y2_off + k - k2] instead.
+    __bf16 *y2;
+    int ldy2, y2_off;
+    // Side job (1x1 gathering kernels only): the side_blocks extra workgroups compute the
+    // 3x3 / stride 1 / pad 1 max pool side_pool of the layer's (dense) input.
+    PoolParams side_pool;
 };
+static_assert(offsetof(ConvParams, S) == 64 && offsetof(ConvParams, x_bytes) == 128 &&
+                  offsetof(ConvParams, d_s) == 192 && offsetof(ConvParams, part) == 256,
+              "ConvParams: fields grouped by 64-byte line");
+
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
 // Rows are 128 bytes; XOR-ing the chunk index with bits 1..3 of the row spreads

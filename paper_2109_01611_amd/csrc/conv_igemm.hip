@@ -101,18 +101,20 @@ __device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int b
     constexpr int RING = NS * STAGE > BM * LDT * 2 ? NS * STAGE : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 ring[RING];
 
-    // Workgroups past the tiles carry the layer's side job: a max pool of the same input,
-    // which would otherwise be a launch of its own with nothing but fixed cost to it.
-    if (POINTWISE && p.side_blocks > 0 && bid >= p.tiles_per_xcd * 8) {
-        const int idx = (bid - p.tiles_per_xcd * 8) * ((CWM * CWN + NPROD) * 64) + static_cast<int>(threadIdx.x);
-        if (idx < p.side_pool.total) pool_max_item<3>(p.side_pool, idx);
-        return;
-    }
-
     // Split-K: consecutive work items share an output tile and each takes a
     // contiguous range of depth slices.
+    // Workgroups past the tiles carry the layer's side job, if it has one: a max pool of the same
+    // input, which would otherwise be a launch of its own with nothing but fixed cost to it.
+    // They are told apart inside the early exit that idle workgroups take anyway, so that a
+    // workgroup with a tile does not wait for one more field of the argument block first.
     const int item = tile_of_block(p, bid);
-    if (item >= p.n_tiles * p.split_k) return;
+    if (item >= p.n_tiles * p.split_k || bid >= p.tiles_per_xcd * 8) {
+        if (POINTWISE && bid >= p.tiles_per_xcd * 8 && p.side_blocks > 0) {
+            const int idx = (bid - p.tiles_per_xcd * 8) * ((CWM * CWN + NPROD) * 64) + static_cast<int>(threadIdx.x);
+            if (idx < p.side_pool.total) pool_max_item<3>(p.side_pool, idx);
+        }
+        return;
+    }
     const int tile = fdiv(item, p.d_split_k), ks = item - tile * p.split_k;
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
@@ -423,16 +425,16 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(co
 // Several independent layers in one launch (branches of an inception block, a projection
 // shortcut next to the first layer of its block): each workgroup finds the layer its block
 // index falls into and runs that layer's tile as above.  The general instance serves 1x1
-// members too (its bounds tests always pass for them), so every member's results are the
-// bits of its own launch.
-template <int BM, int BN, int CWM, int CWN, int NPROD, int NS>
+// members too (its bounds tests always pass for them); when every member is 1x1 the instance
+// without bounds tests is used.  Either way a member's results are the bits of its own launch.
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE>
 __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_group_kernel(const ConvGroup g) {
     const int b = blockIdx.x;
     int j = 0;
 #pragma unroll
     for (int i = 1; i < MAX_GROUP; ++i)
         if (b >= g.first[i]) j = i;
-    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, false>(g.p[j], b - g.first[j]);
+    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, POINTWISE>(g.p[j], b - g.first[j]);
 }
 
 // ---------------------------------------------------------------------------
@@ -605,6 +607,8 @@ template <int BM, int BN, int CWM, int CWN, int NPROD, int NS>
 hipError_t launch_group_tile(const ConvParams *ps, int n, hipStream_t stream) {
     ConvGroup g;
     int blocks = 0;
+    bool pointwise = true;
+    for (int j = 0; j < n; ++j) pointwise = pointwise && ps[j].R == 1 && ps[j].S == 1 && ps[j].pad == 0;
     for (int j = 0; j < MAX_GROUP; ++j) {
         g.first[j] = j < n ? blocks : INT_MAX;
         g.p[j] = ps[j < n ? j : 0];
@@ -622,8 +626,11 @@ hipError_t launch_group_tile(const ConvParams *ps, int n, hipStream_t stream) {
         blocks += p.tiles_per_xcd * 8;
     }
     g.first[MAX_GROUP] = INT_MAX;
-    hipLaunchKernelGGL((conv_igemm_group_kernel<BM, BN, CWM, CWN, NPROD, NS>), dim3(static_cast<unsigned>(blocks)),
-                       dim3((CWM * CWN + NPROD) * 64), 0, stream, g);
+    const dim3 grid(static_cast<unsigned>(blocks)), block((CWM * CWN + NPROD) * 64);
+    if (pointwise)
+        hipLaunchKernelGGL((conv_igemm_group_kernel<BM, BN, CWM, CWN, NPROD, NS, true>), grid, block, 0, stream, g);
+    else
+        hipLaunchKernelGGL((conv_igemm_group_kernel<BM, BN, CWM, CWN, NPROD, NS, false>), grid, block, 0, stream, g);
     return hipGetLastError();
 }
 

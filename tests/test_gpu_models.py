@@ -275,6 +275,17 @@ def test_projection_shortcut_shares_a_launch_with_the_blocks_first_layer():
     _assert_close(a.cpu().numpy().astype(np.float64).reshape(3, -1), ref)
 
 
+def test_shared_launches_keep_an_images_result_whatever_the_batch_and_gpulet():
+    # merged filters, two outputs, riding pools and launch groups choose tiles from the batch and the
+    # gpu-let's CU count; none of that may change a bit of an image's logits
+    model = workloads.googlenet(width_div=1, in_hw=128, n_class=30)
+    a, _, _, dm, _, _ = _run(model, 2, seed=14, images=[0])
+    assert dm.merged and dm.side_pools and dm.groups
+    b, _, _, _, _, _ = _run(model, 7, 20, 0, seed=14, images=[0])
+    c, _, _, _, _, _ = _run(model, 7, 60, 1, seed=14, images=[0])
+    assert np.array_equal(a[:2], b[:2]) and np.array_equal(b, c)
+
+
 def test_batch_size_does_not_change_an_images_result():
     # default: no depth splitting, so an image's logits are independent of its batch and gpu-let
     model = workloads.resnet50(width_div=2, in_hw=96, n_class=50)
