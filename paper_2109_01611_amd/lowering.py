@@ -22,6 +22,12 @@ Buffers are reused once their last reader has run, which keeps the working
 set small enough to stay in the last-level cache between layers.  A concat
 node costs nothing: its source convolutions store straight into channel
 slices of the concatenated buffer.
+
+Layers that can share a kernel launch are told so (``merge_siblings``, on by
+default; see the comments in ``DeviceModel.__init__``): sibling convolutions
+are stacked into one layer, an inception block's max pool rides along with
+its 1x1 layers, and independent convolutions are chained into launch groups.
+None of this changes what is computed, only how many launches it takes.
 """
 
 import numpy as np

@@ -1,0 +1,96 @@
+"""Host-only checks of what the lowering does to a model table before any kernel
+runs: which layers it stacks, which pools ride along, which layers are chained
+into launch groups, and that the resulting description is one the library's
+planner accepts (the planner re-derives the independence of group members and
+the shapes of all buffers from the layer table alone)."""
+
+import numpy as np
+import pytest
+
+from paper_2109_01611_amd import gpulet, lowering, workloads
+
+
+def _lower(model, **kw):
+    return lowering.DeviceModel(model, workloads.parameters(model, 3), "cpu", **kw)
+
+
+def test_googlenet_launch_structure():
+    model = workloads.googlenet()
+    dm = _lower(model)
+    blocks = ("3a", "3b", "4a", "4b", "4c", "4d", "4e", "5a", "5b")
+    assert dm.merged == [["i%s_1x1" % b, "i%s_3x3r" % b, "i%s_5x5r" % b] for b in blocks]
+    assert dm.side_pools == ["i%s_pool" % b for b in blocks]
+    assert dm.groups == [["i%s_3x3" % b, "i%s_5x5" % b, "i%s_poolproj" % b] for b in blocks]
+    layers = list(dm.layers)
+    assert len(layers) == 72 - 18 - 9
+    heads = [L for L in layers if L.K2 > 0]
+    assert len(heads) == 9 and all(L.side_pool == 3 and L.out_ch_total > 0 and L.out_ch_offset == 0 for L in heads)
+    # 3a: 64 filters of the 1x1 branch to the concatenated tensor, 96 + 16 reduce filters to the second buffer
+    assert (heads[0].K, heads[0].K2, heads[0].out_ch_total) == (176, 112, 256)
+    readers = [L for L in layers if L.in_ch_total > 0]
+    assert len(readers) == 18         # the 3x3 layers (from channel 0 on) and the 5x5 layers
+    assert (readers[1].in_ch_total, readers[1].in_ch_offset, readers[1].C) == (112, 96, 16)
+    assert sum(L.group_next for L in layers) == 18
+    for batch in (1, 32):
+        assert gpulet.model_workspace_bytes(dm.desc, batch) > 0
+    plain = _lower(model, merge_siblings=False)
+    assert len(plain.layers) == 72 and not (plain.merged or plain.side_pools or plain.groups)
+    assert all(L.K2 == 0 and L.side_pool == 0 and L.group_next == 0 and L.in_ch_total == 0 for L in plain.layers)
+
+
+def test_three_by_three_layers_of_a_block_read_the_first_slice():
+    dm = _lower(workloads.googlenet())
+    layers = list(dm.layers)
+    i = next(k for k, L in enumerate(layers) if L.K2 > 0)
+    three, five = layers[i + 1], layers[i + 2]
+    assert (three.R, three.C, three.in_buf) == (3, 96, layers[i].out2_buf)
+    assert (five.R, five.C, five.in_buf, five.in_ch_offset) == (5, 16, layers[i].out2_buf, 96)
+    # the 3x3 layer reads channels 0..95 of 112: the pixel width must be stated even at offset 0
+    assert three.in_ch_total == 112 and three.in_ch_offset == 0
+
+
+def test_ssd_and_resnet_launch_structure():
+    ssd = _lower(workloads.ssd_mobilenet())
+    assert ssd.merged == [["box%d" % m, "cls%d" % m] for m in range(1, 7)]
+    assert [len(g) for g in ssd.groups] == [4, 3] and not ssd.side_pools
+    heads = [L for L in ssd.layers if L.out_ch_total > 0]
+    assert [(L.K, L.out_ch_total, L.out_ch_offset) for L in heads] == [(285, 285, 0)] + [(570, 570, 0)] * 5
+    rn = _lower(workloads.resnet50())
+    assert rn.groups == [["l%d_0_a" % s, "l%d_0_proj" % s] for s in (1, 2, 3, 4)] and not rn.merged
+    assert len(rn.layers) == 56
+    for dm in (ssd, rn):
+        assert gpulet.model_workspace_bytes(dm.desc, 4) > 0
+
+
+@pytest.mark.parametrize("model", [workloads.vgg16(width_div=8, in_hw=64, n_class=10), workloads.lenet5()], ids=lambda m: m.name)
+def test_plain_chains_are_left_alone(model):
+    dm = _lower(model)
+    assert not (dm.merged or dm.side_pools or dm.groups)
+    assert [(L.op, L.C, L.K) for L in dm.layers] == [(L.op, L.C, L.K) for L in _lower(model, merge_siblings=False).layers]
+
+
+def test_buffers_released_inside_a_group_are_not_reused_by_its_members():
+    # every member's outputs differ from every member's inputs (the planner would refuse the table otherwise,
+    # and does so again here for a table where a member overwrites another member's input)
+    dm = _lower(workloads.googlenet(width_div=2, in_hw=96, n_class=20))
+    layers = list(dm.layers)
+    k = 0
+    while k < len(layers):
+        n = 1
+        while layers[k + n - 1].group_next:
+            n += 1
+        members = layers[k:k + n]
+        ins = {L.in_buf for L in members} | {L.res_buf for L in members if L.res_buf >= 0}
+        outs = {L.out_buf for L in members}
+        assert not (ins & outs)
+        k += n
+    bad = (gpulet.Layer * len(layers))(*layers)
+    first = next(i for i, L in enumerate(layers) if L.group_next)
+    bad[first + 1].out_buf = bad[first].in_buf
+    d = gpulet.ModelDesc()
+    d.n_layers, d.n_bufs = dm.desc.n_layers, dm.desc.n_bufs
+    d.in_C, d.in_H, d.in_W, d.in_buf, d.out_buf = dm.desc.in_C, dm.desc.in_H, dm.desc.in_W, 0, 1
+    d.layers = bad
+    with pytest.raises(gpulet.GpuletError) as e:
+        gpulet.model_workspace_bytes(d, 2)
+    assert e.value.status == gpulet.EINVAL
