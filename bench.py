@@ -94,7 +94,7 @@ def main():
             # HBM-side bytes per launch of this kernel from FETCH_SIZE + WRITE_SIZE counter passes scaled by a
             # 64 MiB copy (profiles/conv3x3_n32_c256_k256_14x14_hbm_traffic.txt); algorithmic bytes are 7.6 MB,
             # the excess is the weights being fetched once per die.  Reset to None when the kernel changes.
-            "traffic": 16569776,
+            "traffic": 16568752,
             "kernel": "conv3x3_patch_kernel<64,4>",
             "avg_launch_us": kernel_ms * 1e3,
         },
