@@ -224,6 +224,38 @@ def corun(model_a, batch_a, model_b, batch_b, pct_a=50, seed=0, warmup=5, window
     return out
 
 
+def shared_launches(names=("googlenet", "ssd_mobilenet", "resnet50"), batches=(32, 8, 1), pct=100, warmup=50,
+                    iters=400, device="cuda:0", log=None):
+    """The same models lowered with and without shared launches (stacked sibling layers, riding
+    pools, launch groups), alternating twice in one process: launches per batch as counted by the
+    gpu-let and milliseconds per batch from back-to-back batches."""
+    import torch
+    from . import gpulet, lowering
+    rows = []
+    for name in names:
+        model = CONFIGS[name][0]()
+        params = workloads.parameters(model, 0)
+        for batch in batches:
+            for rep in range(2):
+                for shared in (False, True):
+                    dm = lowering.DeviceModel(model, params, device, merge_siblings=shared)
+                    b = Bound(dm, batch, 0)
+                    with gpulet.Partition(0, pct, 0) as part:
+                        torch.cuda.synchronize()
+                        before = part.kernel_launches()
+                        gpulet.run_model(*b.args(part))
+                        part.sync()
+                        launches = part.kernel_launches() - before
+                        _, total = gpulet.profile_model(*b.args(part), warmup=warmup, iters=iters, sync_each=False)
+                    rows.append({"model": model.name, "batch": batch, "shared": int(shared), "rep": rep,
+                                 "launches": int(launches), "ms_per_batch": total / iters})
+                    if log:
+                        log("%s b=%d %s: %d launches, %.4f ms/batch" % (model.name, batch, "shared launches" if shared
+                                                                      else "one launch per layer", launches,
+                                                                      total / iters))
+    return rows
+
+
 def write_atomic(path, text):
     """Writes ``text`` to ``path`` through a temporary file and a rename, so a
     killed sweep never leaves a half-written table."""
@@ -261,13 +293,18 @@ GRID_MODELS = ("lenet5", "googlenet", "resnet50", "ssd_mobilenet", "vgg16")
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description="L(b, p) latency table and co-run interference on one MI355X")
-    ap.add_argument("--config", default="conv", choices=sorted(CONFIGS) + ["corun", "all", "grid"])
+    ap.add_argument("--config", default="conv", choices=sorted(CONFIGS) + ["corun", "all", "grid", "shared-launches"])
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--window-ms", type=float, default=2000.0)
     ap.add_argument("--out", default=None, help="CSV (or JSON for corun) path; default prints only")
     args = ap.parse_args(argv)
     log = lambda s: print(s, flush=True)
+    if args.config == "shared-launches":
+        rows = shared_launches(log=log)
+        if args.out:
+            write_atomic(args.out, json.dumps(rows, indent=1) + "\n")
+        return 0
     if args.config == "grid":
         sizes, batches = list(scenarios.SIZES), list(scenarios.BATCHES)
         rows = []
