@@ -84,7 +84,9 @@ __device__ __forceinline__ void store_tile(const ConvParams &p, const f32x16 (&a
 // memory pipeline therefore never holds back matrix instructions.  Every ring
 // step has one workgroup barrier: before it a producer waits for its own
 // transfers of slice j, after it the stage slice j-1 occupied is free again.
-template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE>
+// EXTRA: the layer has a second destination or a pooling side job (1x1 layers only); layers
+// without either run the instance that knows of neither.
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE, bool EXTRA>
 __device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int bid) {
     constexpr int NCONS = CWM * CWN;
     constexpr int WM = BM / CWM, WN = BN / CWN;  // consumer wavefront tile
@@ -109,7 +111,7 @@ __device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int b
     // workgroup with a tile does not wait for one more field of the argument block first.
     const int item = tile_of_block(p, bid);
     if (item >= p.n_tiles * p.split_k || bid >= p.tiles_per_xcd * 8) {
-        if (POINTWISE && bid >= p.tiles_per_xcd * 8 && p.side_blocks > 0) {
+        if (EXTRA && bid >= p.tiles_per_xcd * 8 && p.side_blocks > 0) {
             const int idx = (bid - p.tiles_per_xcd * 8) * ((CWM * CWN + NPROD) * 64) + static_cast<int>(threadIdx.x);
             if (idx < p.side_pool.total) pool_max_item<3>(p.side_pool, idx);
         }
@@ -412,14 +414,12 @@ __device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int b
         }
         // each thread re-reads only what it wrote itself, in the same iteration order
     }
-    // only 1x1 layers are ever given a second destination
-    finish_tile<BM, BN, NTHR, POINTWISE>(p, stg, n0, bias_regs,
-                                         [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
+    finish_tile<BM, BN, NTHR, EXTRA>(p, stg, n0, bias_regs, [&](int row) { return m0 + row < p.M ? m0 + row : -1; });
 }
 
-template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE>
+template <int BM, int BN, int CWM, int CWN, int NPROD, int NS, bool POINTWISE, bool EXTRA = false>
 __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_kernel(const ConvParams p) {
-    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, POINTWISE>(p, blockIdx.x);
+    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, POINTWISE, EXTRA>(p, blockIdx.x);
 }
 
 // Several independent layers in one launch (branches of an inception block, a projection
@@ -434,7 +434,7 @@ __global__ __launch_bounds__((CWM * CWN + NPROD) * 64) void conv_igemm_group_ker
 #pragma unroll
     for (int i = 1; i < MAX_GROUP; ++i)
         if (b >= g.first[i]) j = i;
-    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, POINTWISE>(g.p[j], b - g.first[j]);
+    conv_igemm_body<BM, BN, CWM, CWN, NPROD, NS, POINTWISE, false>(g.p[j], b - g.first[j]);
 }
 
 // ---------------------------------------------------------------------------
@@ -594,7 +594,9 @@ hipError_t launch_tile(ConvParams p, bool vec, int split_k, hipStream_t stream) 
     if (p.side_pool.y && !p.side_blocks) return hipErrorInvalidValue;  // nobody would compute the pool
     const dim3 grid(static_cast<unsigned>(p.tiles_per_xcd * 8 + p.side_blocks));
     const dim3 block(THREADS);
-    if (vec && pointwise)
+    if (vec && pointwise && (p.side_blocks > 0 || p.k2 < p.K))
+        hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, CWM, CWN, NPROD, NS, true, true>), grid, block, 0, stream, p);
+    else if (vec && pointwise)
         hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, CWM, CWN, NPROD, NS, true>), grid, block, 0, stream, p);
     else if (vec)
         hipLaunchKernelGGL((conv_igemm_kernel<BM, BN, CWM, CWN, NPROD, NS, false>), grid, block, 0, stream, p);
