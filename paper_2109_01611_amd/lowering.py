@@ -24,7 +24,7 @@ node costs nothing: its source convolutions store straight into channel
 slices of the concatenated buffer.
 
 Layers that can share a kernel launch are told so (``merge_siblings``, on by
-default; see the comments in ``DeviceModel.__init__``): sibling convolutions
+default; see ``DeviceModel._stack_siblings``, ``_ride_pools`` and ``_chain_groups``): sibling convolutions
 are stacked into one layer, an inception block's max pool rides along with
 its 1x1 layers, and independent convolutions are chained into launch groups.
 None of this changes what is computed, only how many launches it takes.
@@ -123,177 +123,12 @@ class DeviceModel:
                     nd = nd._replace(src=moved[nd.src], attr=dict(a, pre_pool=3))
                 kept.append(nd)
             nodes = kept
-        # With ``merge_siblings`` convolutions that read the same tensor run as ONE convolution over
-        # their concatenated filters where the result can be used in place:
-        #   * convolutions of equal geometry that store into adjacent slices of the same
-        #     concatenated tensor (the box and class heads of an SSD feature map): the merged
-        #     layer stores the combined slice;
-        #   * plain 1x1 convolutions that feed only other convolutions (the two reduce layers of an
-        #     inception block): each consumer reads its channel slice of the merged result;
-        #   * with those, one 1x1 convolution of the same tensor that stores into a concatenated
-        #     tensor (the block's 1x1 branch): its filters come first and go to the concatenated
-        #     tensor, the others to the second output of the same launch.
-        # Every output element is the same sum in the same order, so the bits do not change;
-        # ``merged`` lists the groups.
+        # Fewer launches: stacked sibling layers, pools riding along, launch groups (the passes below).
         self.merged, self.side_pools, self.groups = [], [], []
         if merge_siblings:
-            readers = {}
-            for nd in nodes:
-                reads = list(nd.src) if nd.op == "concat" else [nd.src]
-                if nd.op == "conv" and nd.attr["residual"]:
-                    reads.append(nd.attr["residual"])
-                for t in reads:
-                    readers.setdefault(t, []).append(nd)
-            index = {nd.name: i for i, nd in enumerate(nodes)}
-            sliced, stored = {}, {}
-            for nd in nodes:
-                a = nd.attr
-                if nd.op != "conv" or a["residual"] or a.get("pre_pool") or nd.src == "x" or nd.dst == model.out:
-                    continue
-                rs = readers.get(nd.dst, [])
-                geom = (a["k"], a["stride"], a["pad"], bool(a["relu"]))
-                if nd.dst in alias:
-                    if len(rs) == 1 and rs[0].op == "concat":
-                        stored.setdefault((nd.src, alias[nd.dst][0]) + geom, []).append(nd)
-                elif (geom[:3] == (1, 1, 0) and a["K"] % 8 == 0 and rs
-                      and all(r.op == "conv" and r.src == nd.dst and r.attr["residual"] != nd.dst for r in rs)):
-                    sliced.setdefault((nd.src,) + geom, []).append(nd)
-            in_slice, first, dropped, renamed = {}, {}, set(), {}
-
-            def merge(g, lead=None):
-                parts = ([lead] if lead else []) + g
-                name = "+".join(n.name for n in g)          # the tensor that holds the outputs of g
-                attr = dict(parts[0].attr, K=sum(n.attr["K"] for n in parts), parts=[n.name for n in parts])
-                if lead:
-                    attr.update(K2=sum(n.attr["K"] for n in g), dst2=name)
-                    node = lead._replace(name="+".join(n.name for n in parts), attr=attr)
-                else:
-                    node = g[0]._replace(name=name, dst=name, attr=attr)
-                first[min(parts, key=lambda n: index[n.name]).name] = node
-                dropped.update(n.name for n in parts)
-                chans[name] = sum(n.attr["K"] for n in g)
-                self.merged.append([n.name for n in parts])
-                return name
-
-            for g in stored.values():
-                g.sort(key=lambda n: alias[n.dst][1])
-                runs = [[g[0]]]
-                for n in g[1:]:
-                    last = runs[-1][-1]
-                    if alias[n.dst][1] == alias[last.dst][1] + last.attr["K"]:
-                        runs[-1].append(n)
-                    else:
-                        runs.append([n])
-                for run in runs:
-                    if len(run) >= 2:
-                        cat, off, total = alias[run[0].dst]
-                        name = merge(run)
-                        for n in run:
-                            del alias[n.dst]
-                            renamed[n.dst] = None
-                        renamed[run[0].dst] = name
-                        alias[name] = (cat, off, total)
-            for key, g in sliced.items():
-                lead = None
-                if chans[key[0]] % 8 == 0:
-                    for k2, cand in stored.items():
-                        if k2[0] == key[0] and k2[2:] == key[1:]:
-                            for n in cand:
-                                if (n.name not in dropped and n.attr["K"] % 8 == 0 and alias[n.dst][1] % 8 == 0
-                                        and alias[n.dst][2] % 8 == 0 and lead is None):
-                                    lead = n
-                if len(g) + (lead is not None) >= 2:
-                    name, off = merge(g, lead), 0
-                    for n in g:
-                        in_slice[n.dst] = (name, off, chans[name])
-                        off += n.attr["K"]
-            kept = []
-            for nd in nodes:
-                if nd.name in first:
-                    kept.append(first[nd.name])
-                elif nd.name in dropped:
-                    continue
-                elif nd.op == "conv" and nd.src in in_slice:
-                    t, off, total = in_slice[nd.src]
-                    if (off, total) != (0, nd.attr["C"]):
-                        nd = nd._replace(attr=dict(nd.attr, in_slice=(off, total)))
-                    kept.append(nd._replace(src=t))
-                elif nd.op == "concat":
-                    kept.append(nd._replace(src=[renamed.get(t, t) for t in nd.src if renamed.get(t, t) is not None]))
-                else:
-                    kept.append(nd)
-            nodes = kept
-            # A 3x3 / stride 1 / pad 1 max pool whose input is also read by a plain 1x1 convolution
-            # (an inception block's pooling branch next to its 1x1 layers) rides along with that
-            # convolution's launch: extra workgroups of the same grid do the pooling.
-            hosts, first_read = {}, {}
-            for i, nd in enumerate(nodes):
-                a = nd.attr
-                if (nd.op == "conv" and (a["k"], a["stride"], a["pad"]) == (1, 1, 0) and not a["residual"]
-                        and not a.get("pre_pool") and "in_slice" not in a and nd.src != "x"
-                        and nd.src not in alias and chans[nd.src] % 8 == 0):
-                    hosts.setdefault(nd.src, (i, nd.name))
-                for t in (list(nd.src) if nd.op == "concat" else [nd.src]):
-                    first_read.setdefault(t, i)
-            riders, kept = {}, []
-            for i, nd in enumerate(nodes):
-                a = nd.attr
-                if (nd.op == "maxpool" and (a["k"], a["stride"], a["pad"]) == (3, 1, 1) and nd.dst != model.out
-                        and nd.src in hosts and hosts[nd.src][1] not in riders
-                        and hosts[nd.src][0] < first_read.get(nd.dst, len(nodes))):
-                    riders[hosts[nd.src][1]] = nd
-                    continue
-                kept.append(nd)
-            nodes = [nd._replace(attr=dict(nd.attr, pool_dst=riders[nd.name].dst)) if nd.name in riders else nd
-                     for nd in kept]
-            self.side_pools = [r.name for r in riders.values()]
-            # Independent convolutions share a launch (``groups``): a sibling that reads the same
-            # tensor is first moved next to its sibling when nothing in between stands in the way (a
-            # projection shortcut next to the first layer of its residual block), then runs of
-            # adjacent convolutions that neither read nor overwrite one another's tensors are chained.
-            def reads_of(nd):
-                r = list(nd.src) if nd.op == "concat" else [nd.src]
-                if nd.op == "conv" and nd.attr["residual"]:
-                    r.append(nd.attr["residual"])
-                return r
-
-            def shareable(nd):
-                a = nd.attr
-                return (nd.op == "conv" and a["C"] % 8 == 0 and nd.src != "x" and not a.get("pre_pool")
-                        and "dst2" not in a and "pool_dst" not in a)
-
-            def independent(p, q):
-                if p.dst in reads_of(q) or q.dst in reads_of(p):
-                    return False
-                sp, sq = storage(p.dst), storage(q.dst)
-                return sp != sq or (p.dst in alias and q.dst in alias)
-
-            def storage(t):
-                return alias[t][0] if t in alias else t
-
-            i = 0
-            while i < len(nodes):
-                if shareable(nodes[i]):
-                    for j in range(i + 2, min(i + 4, len(nodes))):
-                        between = nodes[i + 1:j]
-                        if (shareable(nodes[j]) and nodes[j].src == nodes[i].src
-                                and all(b.op != "concat" and independent(b, nodes[j]) for b in between)):
-                            nodes.insert(i + 1, nodes.pop(j))
-                            break
-                i += 1
-            self.groups, run = [], []
-            for k, nd in enumerate(nodes + [None]):
-                if nd is not None and nd.op == "concat":
-                    continue            # emits no layer: members on either side of it stay neighbours
-                if (nd is not None and shareable(nd) and len(run) < 4
-                        and all(independent(nodes[m], nd) for m in run)):
-                    run.append(k)
-                    continue
-                if len(run) >= 2:
-                    for m in run[:-1]:
-                        nodes[m] = nodes[m]._replace(attr=dict(nodes[m].attr, group_next=1))
-                    self.groups.append([nodes[m].name for m in run])
-                run = [k] if nd is not None and shareable(nd) else []
+            nodes = self._stack_siblings(nodes, chans, alias, model)
+            nodes = self._ride_pools(nodes, chans, alias, model)
+            nodes = self._chain_groups(nodes, alias)
         producers = {nd.dst: nd for nd in nodes}
         for s in alias:
             if producers[s].op != "conv":
@@ -420,6 +255,185 @@ class DeviceModel:
         self.desc = d
         self.out_fp32 = producers[model.out].op == "fc"
         self._ws = {}
+
+    def _stack_siblings(self, nodes, chans, alias, model):
+        """With ``merge_siblings`` convolutions that read the same tensor run as ONE convolution over
+        their concatenated filters where the result can be used in place:
+          * convolutions of equal geometry that store into adjacent slices of the same
+            concatenated tensor (the box and class heads of an SSD feature map): the merged
+            layer stores the combined slice;
+          * plain 1x1 convolutions that feed only other convolutions (the two reduce layers of an
+            inception block): each consumer reads its channel slice of the merged result;
+          * with those, one 1x1 convolution of the same tensor that stores into a concatenated
+            tensor (the block's 1x1 branch): its filters come first and go to the concatenated
+            tensor, the others to the second output of the same launch.
+        Every output element is the same sum in the same order, so the bits do not change;
+        ``merged`` lists the groups.
+        """
+        readers = {}
+        for nd in nodes:
+            reads = list(nd.src) if nd.op == "concat" else [nd.src]
+            if nd.op == "conv" and nd.attr["residual"]:
+                reads.append(nd.attr["residual"])
+            for t in reads:
+                readers.setdefault(t, []).append(nd)
+        index = {nd.name: i for i, nd in enumerate(nodes)}
+        sliced, stored = {}, {}
+        for nd in nodes:
+            a = nd.attr
+            if nd.op != "conv" or a["residual"] or a.get("pre_pool") or nd.src == "x" or nd.dst == model.out:
+                continue
+            rs = readers.get(nd.dst, [])
+            geom = (a["k"], a["stride"], a["pad"], bool(a["relu"]))
+            if nd.dst in alias:
+                if len(rs) == 1 and rs[0].op == "concat":
+                    stored.setdefault((nd.src, alias[nd.dst][0]) + geom, []).append(nd)
+            elif (geom[:3] == (1, 1, 0) and a["K"] % 8 == 0 and rs
+                  and all(r.op == "conv" and r.src == nd.dst and r.attr["residual"] != nd.dst for r in rs)):
+                sliced.setdefault((nd.src,) + geom, []).append(nd)
+        in_slice, first, dropped, renamed = {}, {}, set(), {}
+
+        def merge(g, lead=None):
+            parts = ([lead] if lead else []) + g
+            name = "+".join(n.name for n in g)          # the tensor that holds the outputs of g
+            attr = dict(parts[0].attr, K=sum(n.attr["K"] for n in parts), parts=[n.name for n in parts])
+            if lead:
+                attr.update(K2=sum(n.attr["K"] for n in g), dst2=name)
+                node = lead._replace(name="+".join(n.name for n in parts), attr=attr)
+            else:
+                node = g[0]._replace(name=name, dst=name, attr=attr)
+            first[min(parts, key=lambda n: index[n.name]).name] = node
+            dropped.update(n.name for n in parts)
+            chans[name] = sum(n.attr["K"] for n in g)
+            self.merged.append([n.name for n in parts])
+            return name
+
+        for g in stored.values():
+            g.sort(key=lambda n: alias[n.dst][1])
+            runs = [[g[0]]]
+            for n in g[1:]:
+                last = runs[-1][-1]
+                if alias[n.dst][1] == alias[last.dst][1] + last.attr["K"]:
+                    runs[-1].append(n)
+                else:
+                    runs.append([n])
+            for run in runs:
+                if len(run) >= 2:
+                    cat, off, total = alias[run[0].dst]
+                    name = merge(run)
+                    for n in run:
+                        del alias[n.dst]
+                        renamed[n.dst] = None
+                    renamed[run[0].dst] = name
+                    alias[name] = (cat, off, total)
+        for key, g in sliced.items():
+            lead = None
+            if chans[key[0]] % 8 == 0:
+                for k2, cand in stored.items():
+                    if k2[0] == key[0] and k2[2:] == key[1:]:
+                        for n in cand:
+                            if (n.name not in dropped and n.attr["K"] % 8 == 0 and alias[n.dst][1] % 8 == 0
+                                    and alias[n.dst][2] % 8 == 0 and lead is None):
+                                lead = n
+            if len(g) + (lead is not None) >= 2:
+                name, off = merge(g, lead), 0
+                for n in g:
+                    in_slice[n.dst] = (name, off, chans[name])
+                    off += n.attr["K"]
+        kept = []
+        for nd in nodes:
+            if nd.name in first:
+                kept.append(first[nd.name])
+            elif nd.name in dropped:
+                continue
+            elif nd.op == "conv" and nd.src in in_slice:
+                t, off, total = in_slice[nd.src]
+                if (off, total) != (0, nd.attr["C"]):
+                    nd = nd._replace(attr=dict(nd.attr, in_slice=(off, total)))
+                kept.append(nd._replace(src=t))
+            elif nd.op == "concat":
+                kept.append(nd._replace(src=[renamed.get(t, t) for t in nd.src if renamed.get(t, t) is not None]))
+            else:
+                kept.append(nd)
+        nodes = kept
+        return nodes
+
+    def _ride_pools(self, nodes, chans, alias, model):
+        # A 3x3 / stride 1 / pad 1 max pool whose input is also read by a plain 1x1 convolution
+        # (an inception block's pooling branch next to its 1x1 layers) rides along with that
+        # convolution's launch: extra workgroups of the same grid do the pooling.
+        hosts, first_read = {}, {}
+        for i, nd in enumerate(nodes):
+            a = nd.attr
+            if (nd.op == "conv" and (a["k"], a["stride"], a["pad"]) == (1, 1, 0) and not a["residual"]
+                    and not a.get("pre_pool") and "in_slice" not in a and nd.src != "x"
+                    and nd.src not in alias and chans[nd.src] % 8 == 0):
+                hosts.setdefault(nd.src, (i, nd.name))
+            for t in (list(nd.src) if nd.op == "concat" else [nd.src]):
+                first_read.setdefault(t, i)
+        riders, kept = {}, []
+        for i, nd in enumerate(nodes):
+            a = nd.attr
+            if (nd.op == "maxpool" and (a["k"], a["stride"], a["pad"]) == (3, 1, 1) and nd.dst != model.out
+                    and nd.src in hosts and hosts[nd.src][1] not in riders
+                    and hosts[nd.src][0] < first_read.get(nd.dst, len(nodes))):
+                riders[hosts[nd.src][1]] = nd
+                continue
+            kept.append(nd)
+        nodes = [nd._replace(attr=dict(nd.attr, pool_dst=riders[nd.name].dst)) if nd.name in riders else nd
+                 for nd in kept]
+        self.side_pools = [r.name for r in riders.values()]
+        return nodes
+
+    def _chain_groups(self, nodes, alias):
+        # Independent convolutions share a launch (``groups``): a sibling that reads the same
+        # tensor is first moved next to its sibling when nothing in between stands in the way (a
+        # projection shortcut next to the first layer of its residual block), then runs of
+        # adjacent convolutions that neither read nor overwrite one another's tensors are chained.
+        def reads_of(nd):
+            r = list(nd.src) if nd.op == "concat" else [nd.src]
+            if nd.op == "conv" and nd.attr["residual"]:
+                r.append(nd.attr["residual"])
+            return r
+
+        def shareable(nd):
+            a = nd.attr
+            return (nd.op == "conv" and a["C"] % 8 == 0 and nd.src != "x" and not a.get("pre_pool")
+                    and "dst2" not in a and "pool_dst" not in a)
+
+        def independent(p, q):
+            if p.dst in reads_of(q) or q.dst in reads_of(p):
+                return False
+            sp, sq = storage(p.dst), storage(q.dst)
+            return sp != sq or (p.dst in alias and q.dst in alias)
+
+        def storage(t):
+            return alias[t][0] if t in alias else t
+
+        i = 0
+        while i < len(nodes):
+            if shareable(nodes[i]):
+                for j in range(i + 2, min(i + 4, len(nodes))):
+                    between = nodes[i + 1:j]
+                    if (shareable(nodes[j]) and nodes[j].src == nodes[i].src
+                            and all(b.op != "concat" and independent(b, nodes[j]) for b in between)):
+                        nodes.insert(i + 1, nodes.pop(j))
+                        break
+            i += 1
+        self.groups, run = [], []
+        for k, nd in enumerate(nodes + [None]):
+            if nd is not None and nd.op == "concat":
+                continue            # emits no layer: members on either side of it stay neighbours
+            if (nd is not None and shareable(nd) and len(run) < 4
+                    and all(independent(nodes[m], nd) for m in run)):
+                run.append(k)
+                continue
+            if len(run) >= 2:
+                for m in run[:-1]:
+                    nodes[m] = nodes[m]._replace(attr=dict(nodes[m].attr, group_next=1))
+                self.groups.append([nodes[m].name for m in run])
+            run = [k] if nd is not None and shareable(nd) else []
+        return nodes
 
     def input_to_device(self, x_nchw):
         """Host batch (N, C, H, W) -> device NHWC bf16 with the channel padding the model expects."""
