@@ -290,20 +290,40 @@ __device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int b
     auto step = [&](int cur) {
         __syncthreads();
         const __bf16 *sA = ring + cur * STAGE, *sB = sA + BM * BK;
+        constexpr int KS = BK / 16;
+        if constexpr (MT * NT == 1) {
+            // One matrix instruction per pair of fragment reads: the wavefront would wait out the
+            // LDS latency before each of them.  All reads of the slice are issued first, and the
+            // scheduling barrier keeps them there; each matrix instruction then waits only for its
+            // own operands, and the compiler moves the next slice's barrier and reads up between
+            // this slice's last matrix instructions.  (With more accumulators per wavefront the
+            // extra fragment registers cost more than the latency: measured slower.)
+            bf16x8 fa[KS], fb[KS];
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fa[MT], fb[NT];
+            for (int ks = 0; ks < KS; ++ks) {
+                fa[ks] = *reinterpret_cast<const bf16x8 *>(&sA[lds_pos(wy * WM + frow, ks * 2 + fhalf)]);
+                fb[ks] = *reinterpret_cast<const bf16x8 *>(&sB[lds_pos(wx * WN + frow, ks * 2 + fhalf)]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8 *>(&sA[lds_pos(wy * WM + i * 32 + frow, ks * 2 + fhalf)]);
+            for (int ks = 0; ks < KS; ++ks)
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks], fb[ks], acc[0][0], 0, 0, 0);
+        } else {
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8 *>(&sB[lds_pos(wx * WN + j * 32 + frow, ks * 2 + fhalf)]);
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 fa[MT], fb[NT];
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
+                for (int i = 0; i < MT; ++i)
+                    fa[i] = *reinterpret_cast<const bf16x8 *>(&sA[lds_pos(wy * WM + i * 32 + frow, ks * 2 + fhalf)]);
 #pragma unroll
                 for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    fb[j] = *reinterpret_cast<const bf16x8 *>(&sB[lds_pos(wx * WN + j * 32 + frow, ks * 2 + fhalf)]);
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
         }
     };
     int kt = 0;
