@@ -150,10 +150,14 @@ bool stream_applicable(const ConvParams &p, bool vec) {
 
 // Chosen automatically for one depth slice (C <= 64: two workgroups per CU) and at least four tiles
 // per CU, where it measured 11 % faster than the best one-tile-per-workgroup tile (1x1 64->256 on
-// 56x56 at batch 32: 20.3 -> 18.0 us); with two slices (C = 128) it was 8 % slower.
+// 56x56 at batch 32: 20.3 -> 18.0 us).  With two slices (C up to 128) it only pays when a single
+// filter tile is walked over very many pixel tiles (128->128 on 75x75 at batch 32: 21.0 -> 17.7 us,
+// on 56x56 13.6 -> 12.9 us); with more filter tiles it measured 8-15 % slower.
 bool stream_eligible(const ConvParams &p, bool vec, int n_cu) {
-    const long long tiles = 1LL * ((p.M + STREAM_BM - 1) / STREAM_BM) * ((p.K + STREAM_BN - 1) / STREAM_BN);
-    return stream_applicable(p, vec) && p.C <= BK && tiles >= 4LL * n_cu;
+    const long long tiles_n = (p.K + STREAM_BN - 1) / STREAM_BN;
+    const long long tiles = 1LL * ((p.M + STREAM_BM - 1) / STREAM_BM) * tiles_n;
+    if (!stream_applicable(p, vec)) return false;
+    return p.C <= BK ? tiles >= 4LL * n_cu : (tiles_n == 1 && tiles >= 6LL * n_cu);
 }
 
 hipError_t launch_stream(ConvParams p, int n_cu, hipStream_t stream) {
