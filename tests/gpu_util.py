@@ -5,7 +5,10 @@ results back as float64 in the oracle's layout."""
 import numpy as np
 import torch
 
+import oracle
 from paper_2109_01611_amd import gpulet, inputs, lowering
+
+from parity_bounds import SLACK, assert_elementwise
 
 DEV = "cuda:0"
 
@@ -17,6 +20,30 @@ DEV = "cuda:0"
 # stay within 1e-2.
 LAYER_TOL = 4e-3
 MODEL_TOL = 1e-2
+
+
+def assert_close(got, ref, mag, tol=LAYER_TOL, slack=SLACK, rel=2.0 ** -8, what=""):
+    """Both parity bounds of a layer: the normwise one (whole tensor and worst image) and the
+    element-wise one of ``parity_bounds`` against the oracle's sum of absolute terms ``mag``."""
+    whole, per_img = oracle.rel_err(got, ref)
+    assert max(whole, per_img) <= tol, (what, whole, per_img)
+    assert_elementwise(got, ref, mag, slack=slack, rel=rel, what=str(what))
+
+
+def conv_mag(x, w, b, stride, pad, residual=None):
+    """The convolution of the operands' absolute values: per output element the sum of the
+    absolute values of its terms (oracle arithmetic only)."""
+    return oracle.conv2d(np.abs(x), np.abs(w), None if b is None else np.abs(b), stride, pad, False,
+                         None if residual is None else np.abs(residual))
+
+
+def assert_conv_close(got, x, w, b, stride, pad, relu, residual=None, ref=None, mag=None, tol=LAYER_TOL, what=""):
+    """``got`` (float64 NCHW) against the oracle's convolution of the same operands."""
+    if ref is None:
+        ref = oracle.conv2d(x, w, b, stride, pad, relu, residual)
+    if mag is None:
+        mag = conv_mag(x, w, b, stride, pad, residual)
+    assert_close(got, ref, mag, tol=tol, what=what)
 
 
 def conv_tensors(seed, N, C, H, W, K, R, S=None):

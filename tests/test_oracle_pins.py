@@ -502,3 +502,61 @@ def test_run_model_storage_hook_sees_every_computing_layer_once():
     first = m.nodes[0]
     assert first.op == "conv"
     assert np.array_equal(T[first.dst], 0.5 * T0[first.dst])
+
+
+# ---------------------------------------------------------------- the error metric itself
+
+def test_rel_err_hand_computed_values():
+    # ||d||_2 / ||ref||_2 on vectors whose norms are known by hand (3-4-5 triangles)
+    ref = np.array([[3.0, 4.0]])
+    got = np.array([[3.0, 4.5]])
+    whole, per = oracle.rel_err(got, ref)
+    assert whole == pytest.approx(0.1, abs=1e-15) and per == pytest.approx(0.1, abs=1e-15)
+    # the 2-norm, not the 1-norm (1/4) and not the max-norm (1)
+    whole, per = oracle.rel_err(np.array([[2.0, 1.0, 1.0, 1.0]]), np.ones((1, 4)))
+    assert whole == pytest.approx(0.5, abs=1e-15) and per == pytest.approx(0.5, abs=1e-15)
+    # divided by the norm of the reference, not of the result (that would give 1/2)
+    whole, per = oracle.rel_err(2.0 * ref, ref)
+    assert whole == pytest.approx(1.0, abs=1e-15) and per == pytest.approx(1.0, abs=1e-15)
+
+
+def test_rel_err_reports_the_worst_image_not_the_mean():
+    # two images, only the second is off by one unit: whole tensor 1/sqrt(125), images 0 and 1/10
+    ref = np.array([[3.0, 4.0], [6.0, 8.0]])
+    got = np.array([[3.0, 4.0], [6.0, 9.0]])
+    whole, per = oracle.rel_err(got, ref)
+    assert whole == pytest.approx(1.0 / np.sqrt(125.0), abs=1e-15)
+    assert per == pytest.approx(0.1, abs=1e-15)          # the mean over images would be 0.05
+    # one bad image among many good ones cannot hide in the whole-tensor figure
+    ref = np.tile(np.array([[3.0, 4.0]]), (100, 1))
+    got = ref.copy()
+    got[37] = [3.0, 9.0]
+    whole, per = oracle.rel_err(got, ref)
+    assert per == pytest.approx(1.0, abs=1e-15) and whole == pytest.approx(0.1, abs=1e-15)
+    # a small image that is entirely wrong next to a large one that is right
+    ref = np.array([[1e-3, 0.0], [30.0, 40.0]])
+    got = np.array([[0.0, 0.0], [30.0, 40.0]])
+    whole, per = oracle.rel_err(got, ref)
+    assert per == pytest.approx(1.0, abs=1e-12) and whole < 1e-4
+
+
+def test_rel_err_invariants():
+    ref = RNG.standard_normal((3, 4, 5, 6))
+    got = ref + 1e-3 * RNG.standard_normal(ref.shape)
+    assert oracle.rel_err(ref, ref) == (0.0, 0.0)
+    a = oracle.rel_err(got, ref)
+    for scale in (1e-6, 7.0, 1e9):                        # both tensors scaled alike: unchanged
+        b = oracle.rel_err(scale * got, scale * ref)
+        assert b[0] == pytest.approx(a[0], rel=1e-12) and b[1] == pytest.approx(a[1], rel=1e-12)
+    # an image is everything behind axis 0, whatever the shape: same figures on the flattened tensor
+    assert oracle.rel_err(got.reshape(3, -1), ref.reshape(3, -1)) == a
+    # the per-image figure is the largest of the images' own figures, each against its own norm
+    each = [np.linalg.norm(got[i] - ref[i]) / np.linalg.norm(ref[i]) for i in range(3)]
+    assert a[1] == pytest.approx(max(each), rel=1e-12)
+    assert a[0] == pytest.approx(np.linalg.norm(got - ref) / np.linalg.norm(ref), rel=1e-12)
+    # permuting the images changes neither figure; the per-image figure is at least the whole one
+    b = oracle.rel_err(got[::-1], ref[::-1])
+    assert b[0] == pytest.approx(a[0], rel=1e-12) and b[1] == pytest.approx(a[1], rel=1e-12)
+    # an all-zero reference raises nothing (the quotient is merely huge)
+    z = oracle.rel_err(np.ones((2, 3)), np.zeros((2, 3)))
+    assert z[0] > 1e100 and z[1] > 1e100
