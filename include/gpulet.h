@@ -343,6 +343,31 @@ gpulet_status gpulet_pool(const void *x, void *y, int N, int C, int H, int W, in
 gpulet_status gpulet_fc(const void *x, const void *w, const float *b, void *y, int N, int In,
                         int Out, int relu, int out_fp32, void *stream);
 
+/*
+ * gpulet_fc for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same result, bit for bit, as gpulet_fc on the same stream, but
+ * the partial tiles and arrival counters that long rows (In >= 8192, N <= 32)
+ * split over several workgroups need live in an array that is part of the
+ * library's device image (2 MiB of tiles + 1024 counters per GPU, held until
+ * the process ends) instead of a gpu-let's allocation.  The call allocates and
+ * frees nothing, on the host's HIP side or the device.  x, w, b, y are device
+ * pointers owned by the caller; the call is asynchronous on `stream` (a
+ * gpu-let's stream sizes the split from the gpu-let's CU count, any other
+ * stream from the device's).
+ * Limit: ceil(Out/64) * ksplit * (N <= 16 ? 4 : 8) KiB <= 2 MiB and
+ * ceil(Out/64) <= 1024, with ksplit = min(8, CUs / ceil(Out/64)) when that is
+ * at least 2; a layer beyond it returns GPULET_ENOMEM and launches nothing.
+ * Layers that need no scratch (short rows, N > 32, a single depth range) are
+ * never refused.  Other errors as gpulet_fc.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU
+ * (two streams, two threads) race and give undefined results; calls ordered on
+ * one stream do not.  The counters are cleared by a small kernel on `stream`
+ * before each use, so a call does not depend on what an earlier one left.
+ */
+gpulet_status gpulet_fc_static_scratch(const void *x, const void *w, const float *b, void *y, int N, int In,
+                                       int Out, int relu, int out_fp32, void *stream);
+
 /* ------------------------------------------------------------------------
  * Whole model on a gpu-let (Sec. 5 "Backend inference executor").
  * ------------------------------------------------------------------------ */

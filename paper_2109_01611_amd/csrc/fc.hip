@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "gpulet_internal.h"
 
@@ -302,6 +303,59 @@ gpulet_status check_fc(int N, int In, int Out) {
     return GPULET_OK;
 }
 
+namespace {
+
+// Long rows at serving batch sizes take fc_split_kernel: 64 outputs per workgroup and as many
+// depth ranges (at most 8) as fill the gpu-let.
+struct SplitPlan {
+    bool wide;       // the layer takes fc_split_kernel
+    int groups;      // output groups of 64 = one arrival counter each
+    int ksplit;      // depth ranges wanted
+    size_t need;     // bytes of partial tiles when ksplit > 1
+};
+
+SplitPlan plan_split(int N, int In, int Out, int n_cu) {
+    SplitPlan s;
+    s.wide = In >= 8192 && N <= 32;
+    s.groups = (Out + 63) / 64;
+    s.ksplit = s.wide ? std::max(1, std::min(8, (n_cu < 1 ? 1 : n_cu) / s.groups)) : 1;
+    s.need = s.ksplit > 1 ? static_cast<size_t>(s.groups) * s.ksplit * (N <= 16 ? 1 : 2) * 4 * 64 * 16 : 0;
+    return s;
+}
+
+// Scratch of the entry point that allocates nothing: partial tiles, then arrival counters.  One
+// copy per GPU, held until the process ends; every call on a GPU shares it.
+constexpr size_t kStaticTileBytes = 2u << 20;
+constexpr int kStaticCounters = 1024;
+static __device__ __align__(256) unsigned char scratch[kStaticTileBytes + kStaticCounters * sizeof(unsigned)];
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_scratch(unsigned char **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    unsigned char *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+__global__ void zero_counters_kernel(unsigned *cnt, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) cnt[i] = 0u;
+}
+
+}  // namespace
+
 hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
                      int relu, int out_fp32, const LaunchCtx &ctx, hipStream_t stream) {
     FcParams p;
@@ -313,14 +367,14 @@ hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int 
     const bool vec = (In % 8 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(w) % 16 == 0);
     const bool wide = In >= 8192;  // long rows: 16 wavefronts per workgroup
-    if (wide && N <= 32) {
-        // 64 outputs per workgroup and as many depth ranges as fill the gpu-let; the ranges need
-        // the gpu-let's scratch and one counter per output group, otherwise there is one range.
-        const int groups = (Out + 63) / 64;
+    const SplitPlan plan = plan_split(N, In, Out, ctx.n_cu);
+    if (plan.wide) {
+        // The depth ranges need scratch for the partial tiles and one counter per output group,
+        // otherwise there is one range.
+        const int groups = plan.groups;
         const int steps = (In + 31) / 32;
-        int ksplit = std::max(1, std::min(8, (ctx.n_cu < 1 ? 1 : ctx.n_cu) / groups));
-        const size_t need = static_cast<size_t>(groups) * ksplit * (N <= 16 ? 1 : 2) * 4 * 64 * 16;
-        if (!ctx.scratch || !ctx.counters || groups > ctx.n_counters || need > ctx.scratch_bytes) ksplit = 1;
+        int ksplit = plan.ksplit;
+        if (!ctx.scratch || !ctx.counters || groups > ctx.n_counters || plan.need > ctx.scratch_bytes) ksplit = 1;
         const int sps = (steps + ksplit - 1) / ksplit;
         const dim3 g(static_cast<unsigned>(groups), static_cast<unsigned>(ksplit));
 #define GPULET_FC_SPLIT(NB, V) \
@@ -343,6 +397,36 @@ hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int 
     }
 #undef GPULET_FC_LAUNCH
     return hipGetLastError();
+}
+
+// The same layer with the partial tiles and counters in the library's static device array
+// instead of a gpu-let's allocation.  Nothing is allocated here or below: the array's address
+// is looked up once per device, the counters are cleared by a small kernel on the caller's
+// stream (a caller may be capturing the stream, and the array keeps what the last call left).
+hipError_t launch_fc_static(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
+                            int relu, int out_fp32, int n_cu, hipStream_t stream, bool *too_large) {
+    *too_large = false;
+    LaunchCtx ctx;
+    ctx.n_cu = n_cu;
+    const SplitPlan plan = plan_split(N, In, Out, n_cu);
+    if (plan.wide && plan.ksplit > 1) {
+        if (plan.need > kStaticTileBytes || plan.groups > kStaticCounters) {
+            *too_large = true;
+            return hipSuccess;
+        }
+        unsigned char *base = nullptr;
+        const hipError_t e = static_scratch(&base);
+        if (e != hipSuccess) return e;
+        ctx.scratch = reinterpret_cast<float *>(base);
+        ctx.scratch_bytes = kStaticTileBytes;
+        ctx.counters = reinterpret_cast<unsigned *>(base + kStaticTileBytes);
+        ctx.n_counters = kStaticCounters;
+        hipLaunchKernelGGL(zero_counters_kernel, dim3((plan.groups + 255) / 256), dim3(256), 0, stream, ctx.counters,
+                           plan.groups);
+        const hipError_t le = hipGetLastError();
+        if (le != hipSuccess) return le;
+    }
+    return launch_fc(x, w, b, y, N, In, Out, relu, out_fp32, ctx, stream);
 }
 
 }  // namespace gpulet

@@ -109,6 +109,10 @@ hipError_t launch_pool(const void *x, void *y, int N, int C, int H, int W, int P
                        int k, int stride, int pad, hipStream_t stream);
 hipError_t launch_fc(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
                      int relu, int out_fp32, const LaunchCtx &ctx, hipStream_t stream);
+// The layer with its scratch in the library's static device array (no allocation anywhere);
+// *too_large is set, and nothing launched, when the layer needs more than the array holds.
+hipError_t launch_fc_static(const void *x, const void *w, const float *b, void *y, int N, int In, int Out,
+                            int relu, int out_fp32, int n_cu, hipStream_t stream, bool *too_large);
 hipError_t launch_dwconv(const void *x, const void *w, const float *b, void *y, int N, int C, int H, int W,
                          int R, int S, int stride, int pad, int relu, int P, int Q, hipStream_t stream);
 hipError_t launch_probe(uint32_t *out, int n_blocks, hipStream_t stream);

@@ -206,6 +206,18 @@ extern "C" gpulet_status gpulet_fc(const void *x, const void *w, const float *b,
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_fc_static_scratch(const void *x, const void *w, const float *b, void *y, int N,
+                                                  int In, int Out, int relu, int out_fp32, void *stream) {
+    if (!x || !w || !y) return GPULET_EINVAL;
+    gpulet_status st = check_fc(N, In, Out);
+    if (st != GPULET_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    bool too_large = false;
+    GPULET_HIP(launch_fc_static(x, w, b, y, N, In, Out, relu ? 1 : 0, out_fp32 ? 1 : 0, stream_ctx(s).n_cu, s,
+                                &too_large));
+    return too_large ? GPULET_ENOMEM : GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_time_conv2d(const void *x, const void *w, const float *b, void *y,
                                             int N, int C, int H, int W, int K, int R, int S,
                                             int stride, int pad, int relu, const void *residual,

@@ -113,6 +113,7 @@ def _load():
         "gpulet_maxpool3_conv1x1_fwd": ([P, P, P, P] + [I] * 8 + [P], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
+        "gpulet_fc_static_scratch": ([P, P, P, P] + [I] * 5 + [P], c_int32),
         "gpulet_set_model_lanes": ([I], c_int32),
         "gpulet_model_schedule": ([POINTER(ModelDesc), I, I, IP, IP, IP, I, IP], c_int32),
         "gpulet_model_workspace_bytes": ([POINTER(ModelDesc), I, POINTER(c_size_t)], c_int32),
@@ -291,6 +292,11 @@ def pool(x, y, N, C, H, W, mode, k=1, stride=1, pad=0, stream=None):
 def fc(x, w, b, y, N, In, Out, relu, out_fp32=False, stream=None):
     _check(lib.gpulet_fc(ptr(x), ptr(w), ptr(b), ptr(y), N, In, Out, int(relu), int(out_fp32), stream),
            "gpulet_fc")
+
+
+def fc_static_scratch(x, w, b, y, N, In, Out, relu, out_fp32=False, stream=None):
+    _check(lib.gpulet_fc_static_scratch(ptr(x), ptr(w), ptr(b), ptr(y), N, In, Out, int(relu), int(out_fp32),
+                                        stream), "gpulet_fc_static_scratch")
 
 
 def time_conv2d(x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, residual=None, y_ch_stride=0,
