@@ -23,13 +23,40 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak, all 256 CUs
 
+# The counter passes are separate profiler runs; their summary states the bytes per launch and a
+# digest of the sources the benchmark kernel is built from.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "conv3x3_n32_c256_k256_14x14_hbm_traffic.txt")
+KERNEL_SOURCES = ["conv_patch.hip", "conv_common.h", "conv.hip", "device_util.h", "gpulet_internal.h"]
+
+
+def kernel_sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2109_01611_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def recorded_traffic():
+    """Bytes per launch from the committed counter summary if it was taken on the kernel as it is now."""
+    try:
+        fields = dict(line.split(":", 1) for line in open(TRAFFIC_PROFILE) if line.startswith(("traffic_bytes", "kernel_sources")))
+        if fields["kernel_sources_sha256"].strip() == kernel_sources_digest():
+            return int(fields["traffic_bytes_per_launch"].strip())
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # a step is about 10 us: 20000 of them (0.2 s) let the clocks settle; 2000 read 3 % slower
     ap.add_argument("--steps", type=int, default=20000)
     ap.add_argument("--warmup", type=int, default=2000)
+    # a step is about 10 us and the first few thousand launches after idle run about 3 % slower while
+    # the clocks ramp up: an untimed run of this many milliseconds of launches comes before the warm-up
+    ap.add_argument("--settle-ms", type=float, default=300.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     args = ap.parse_args()
@@ -57,6 +84,11 @@ def main():
     # ---- timed region: exactly --steps forward passes on the 100% gpu-let
     with gpulet.Partition(0, 100, 0) as part:
         conv_args = (x, w, b, y, N, C, H, W, K, R, R, 1, 1, True)
+        # untimed: bring the clocks to their steady state under this load
+        settle_launches, t0 = 0, time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < args.settle_ms:
+            gpulet.time_conv2d(*conv_args, stream=part.stream, warmup=0, iters=2000)
+            settle_launches += 2000
         gpulet.time_conv2d(*conv_args, stream=part.stream, warmup=args.warmup, iters=1)
         torch.cuda.synchronize()
         part.sync()
@@ -70,12 +102,19 @@ def main():
 
     out = {
         "metric": "conv images/s + MFMA util per CU fraction (20-100%); p99 batch latency",
-        "value": N / (wall_ms * 1e-3),
+        # The steps are timed on the GPU: one HIP event pair on the gpu-let's stream around exactly
+        # --steps launches, between two host synchronisations.  The host's clock around the same call
+        # (event creation, the wake-up after the last launch) is reported next to it; with few steps
+        # of 10 us each it measures the host, not the device.
+        "value": N / (kernel_ms * 1e-3),
         "unit": "images/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": wall_ms,
+        "ms_per_step": kernel_ms,
+        "timer": "HIP events on the gpu-let's stream around the timed steps",
+        "host_wall_ms_per_step": wall_ms,
+        "settle": {"untimed_launches_before_warmup": settle_launches, "ms": args.settle_ms},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -84,17 +123,16 @@ def main():
         "config": {"workload": "single ResNet-50-style 3x3 conv layer: N=32 C=K=256 H=W=14 stride 1 pad 1 "
                                "bias+ReLU bf16 NHWC, 100% CUs (256); swept over CU masks 20/40/50/60/80/100%",
                    "flop_per_step": flops},
-        "tflops": flops / (wall_ms * 1e-3) / 1e12,
+        "tflops": flops / (kernel_ms * 1e-3) / 1e12,
         "roofline": {
             "bound": "mfma",
             "achieved": flops / (kernel_ms * 1e-3) / 1e12,
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": flops / (kernel_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            # HBM-side bytes per launch of this kernel from FETCH_SIZE + WRITE_SIZE counter passes scaled by a
-            # 64 MiB copy (profiles/conv3x3_n32_c256_k256_14x14_hbm_traffic.txt); algorithmic bytes are 7.6 MB,
-            # the excess is the weights being fetched once per die.  Reset to None when the kernel changes.
-            "traffic": 16568752,
+            # HBM-side bytes per launch from the FETCH_SIZE + WRITE_SIZE counter passes recorded in
+            # profiles/ (scaled by a 64 MiB copy); null when the kernel's sources have changed since
+            "traffic": recorded_traffic(),
             "kernel": "conv3x3_patch_kernel<64,4>",
             "avg_launch_us": kernel_ms * 1e3,
         },
@@ -108,7 +146,7 @@ def main():
         for pct in (20, 40, 50, 60, 80, 100):
             with gpulet.Partition(0, pct, 0) as part:
                 # throughput: launches back to back on the gpu-let's stream, one event pair around all of them
-                ms = gpulet.time_conv2d(*conv_args, stream=part.stream, warmup=50, iters=1000)
+                ms = gpulet.time_conv2d(*conv_args, stream=part.stream, warmup=3000, iters=2000)
                 # latency: one batch in flight at a time, each bracketed by its own event pair
                 r = profiler.measure(bound, part, warmup=50, iters=1000)
             tf = flops / (ms * 1e-3) / 1e12

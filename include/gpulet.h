@@ -283,16 +283,20 @@ gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const fl
  *      tile 1 instead)
  *  10: 128x64 walked by workgroups that keep their 64 filters' weights in
  *      registers (3x3 filters, stride 1, pad 1, exactly 64 input channels, no
- *      residual operand; other shapes run tile 1 instead),
+ *      residual operand; other shapes run tile 1 instead)
+ *  11: 224x128: a rectangle of up to 224 pixels of one image (8 x 28 on maps
+ *      56, 112 or 224 pixels wide) with its input patch resident in LDS and
+ *      the weights streamed one filter tap at a time (3x3 filters, stride 1,
+ *      pad 1, C a multiple of 64; other shapes run tile 1 instead),
  * or -1 to return to automatic selection, which picks the tile whose busiest
  * CU has the least work for the launch's shape and the stream's CU count, and
- * tile 9 wherever it applies.  Tiles 0..8 and 10 give bit-identical results; tile 9
+ * tile 9 wherever it applies.  Tiles 0..8, 10 and 11 give bit-identical results; tile 9
  * groups the same ascending sum differently (zero padding inside the depth),
- * so it agrees with them to rounding.  Tiles 7..10 need dense input pixels and
+ * so it agrees with them to rounding.  Tiles 7..11 need dense input pixels and
  * a single output: a layer that reads a channel slice or stores to two tensors
- * counts as another shape for them.  GPULET_EINVAL outside -1..10.
+ * counts as another shape for them.  GPULET_EINVAL outside -1..11.
  */
-enum { GPULET_CONV_TILES = 11 };
+enum { GPULET_CONV_TILES = 12 };
 gpulet_status gpulet_set_conv_tile(int tile);
 
 /*
@@ -525,6 +529,11 @@ gpulet_status gpulet_model_graph_destroy(gpulet_graph *g);
  * flight per gpu-let); with sync_each == 0 batches are enqueued back to back.
  * If total_ms is not NULL it receives the time from the first timed batch's
  * start to the last one's end.  Synchronises before returning.
+ * sync_each == 2 is the throughput pass for batches of a few microseconds,
+ * where an event record between two batches is itself a measurable part of the
+ * time: one event pair around all `iters` batches, nothing in between;
+ * total_ms (required) receives their time and latency_ms may be NULL (if not,
+ * every entry receives total_ms / iters).
  */
 gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int batch, gpulet_partition *p,
                                    const void *in, void *out, void *workspace,

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpulet.so")
 
 SOURCES = ["mask.cpp", "partition.cpp", "layers.cpp", "model.cpp", "sched.cpp", "interference.cpp", "conv.hip",
-           "conv_igemm.hip", "conv_patch.hip", "conv_stream.hip", "conv_stem.hip", "conv_pooled.hip", "dwconv.hip",
+           "conv_igemm.hip", "conv_patch.hip", "conv_tall.hip", "conv_stream.hip", "conv_stem.hip", "conv_pooled.hip", "dwconv.hip",
            "pool.hip", "fc.hip", "probe.hip"]
 
 # The scheduler's fp64 decisions must not depend on fused multiply-adds.

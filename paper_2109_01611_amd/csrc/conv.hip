@@ -103,7 +103,7 @@ hipError_t make_params(const ConvArgs &a, const LaunchCtx &ctx, ConvParams &p, b
     p.sps = 0;
     p.part = ctx.scratch;
     p.cnt = ctx.counters;
-    p.tw = p.n_cb = 0;
+    p.tw = p.n_cb = p.th = p.tiles_img = 0;
     p.d_pq = make_fastdiv(a.P * a.Q);
     p.d_q = make_fastdiv(a.Q);
     p.d_p = make_fastdiv(a.P);
@@ -134,7 +134,7 @@ hipError_t make_params(const ConvArgs &a, const LaunchCtx &ctx, ConvParams &p, b
 // patch kernel (column block `tw`), 8 the streaming 1x1 kernel, 9 the stem kernel, 10 the
 // resident-weight kernel (column block `tw64`).
 struct Choice {
-    int best, split, tw, tw64;
+    int best, split, tw, tw64, th11, tw11;
 };
 
 Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
@@ -179,6 +179,24 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
         best = forced;
         best_split = 1;
     }
+    // The tall tile (224 pixels of one image x 128 filters, input patch in LDS) against the best
+    // gathering tile, in the same units.  Its efficiency relative to 256x128, fitted to
+    // measurements on MI355X (3x3 layers of 128..512 channels on 28..112 pixel maps at batch 16
+    // and 32): 0.93 when every tile row is a pixel and the depth is long, less the rows that are
+    // not pixels and the first loads and the epilogue that a short depth does not amortise.
+    int th11 = 0, tw11 = 0;
+    double geo11 = 0.0;
+    const bool tall_ok = tall_eligible(p, vec, &th11, &tw11, &geo11);
+    if (forced < 0 && tall_ok && p.C >= 2 * BK) {
+        const long long tiles = tall_tiles(p, th11, tw11);
+        const double eff = 0.93 - 0.45 * (1.0 - geo11) - 0.1 / (p.C / BK);
+        const double cost = static_cast<double>((tiles + n_cu - 1) / n_cu) * 224 * 128 / eff;
+        if (cost < best_cost) {
+            best = 11;
+            best_split = 1;
+            best_cost = cost;
+        }
+    }
     int tw = 0;
     const bool patch_ok = patch_eligible(p, vec, &tw);
     if (best == 7 && !patch_ok) best = 1;  // the patch kernel does not apply: same tile shape, gathered
@@ -215,7 +233,8 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     }
     if (best == 9 && !stem_applicable(p)) best = 1;
     if (forced < 0 && stem_applicable(p)) best = 9;  // by shape alone: the same bits in every batch and gpu-let
-    return Choice{best, best_split, tw, tw64};
+    if (best == 11 && !tall_ok) best = 1;
+    return Choice{best, best_split, tw, tw64, th11, tw11};
 }
 
 }  // namespace
@@ -235,6 +254,7 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     const Choice c = choose_kernel(p, vec, ctx);
     const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
     switch (c.best) {
+        case 11: return launch_tall(p, c.th11, c.tw11, stream);
         case 10: return launch_c64(p, c.tw64, n_cu, stream);
         case 9: return launch_stem(p, n_cu, stream);
         case 8: return launch_stream(p, n_cu, stream);

@@ -59,8 +59,10 @@ struct alignas(64) ConvParams {
     FastDiv d_s, d_p;   // by S, P
     // Patch kernels only: output pixels are grouped in column blocks of `tw` pixels.
     int tw, n_cb;       // block width, blocks per output row
-    FastDiv d_tw, d_ncb, d_pwt, d_hp;               // by tw, n_cb, tw + 2, H + 2*pad
-    int pad3[2];
+    FastDiv d_tw, d_ncb, d_pwt, d_hp;               // by tw, n_cb, tw + 2, H + 2*pad (tall tiles: tiles_img)
+    // Tall-tile kernel only: a tile is a th x tw pixel rectangle of one image (n_cb = tiles per
+    // tile row, tiles_img = tiles per image).
+    int th, tiles_img;
     // ---- line 4 and on
     float *part;        // split-K scratch: [n_tiles * split_k][BM * BN] fp32 partial tiles
     unsigned *cnt;      // split-K scratch: arrival counter per tile (zero between launches)
@@ -83,6 +85,14 @@ static_assert(offsetof(ConvParams, S) == 64 && offsetof(ConvParams, x_bytes) == 
 __device__ __forceinline__ int lds_pos(int row, int chunk) {
     return row * BK + ((chunk ^ ((row >> 1) & 7)) * CHUNK);
 }
+
+// Swizzle key of position `pos` (a 128-byte row of 64 channels) of an input patch whose rows
+// are the block columns plus two halo columns, `prow` = pos / (row width): the key follows
+// q = pos - 2*prow, which steps by one from an output pixel to the next also where pos skips
+// the halo columns between two patch rows.  The skip is odd, so even and odd positions keep
+// alternating and each parity sees eight consecutive values of q >> 1: 16 consecutive pixels
+// at a tap touch 16 different 16-byte bank groups.
+__device__ __forceinline__ int patch_key(int pos, int prow) { return ((pos - 2 * prow) >> 1) & 7; }
 
 // Workgroups are dealt round-robin to the eight dies, each with its own L2.
 // Give every die a contiguous run of tiles so that tiles sharing a pixel block
@@ -115,6 +125,10 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
 // (`lds_base` is the same for the whole wavefront and travels in M0).  Issued
 // as assembly so that waiting for it stays under this kernel's control: the
 // transfers of later ring stages must remain in flight across LDS reads.
+// M0 is written here without being declared clobbered: the compiler reserves M0 (naming it in a
+// clobber list is diagnosed as undefined behaviour) and sets it itself immediately in front of
+// every instruction of its own that reads it, none of which these kernels contain (gfx9 LDS
+// instructions do not use M0).
 __device__ __forceinline__ void dma16(const i32x4 rsrc, unsigned lds_base, unsigned voff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
@@ -266,6 +280,12 @@ bool patch_eligible(const ConvParams &p, bool vec, int *tw_out);
 hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream);
 bool c64_applicable(const ConvParams &p, bool vec, int *tw_out);
 hipError_t launch_c64(ConvParams p, int tw, int n_cu, hipStream_t stream);
+
+// conv_tall.hip: tile 11 (3x3, 224 x 128 tile, input patch in LDS, one tap per ring step).
+// `eff` receives the share of tile rows that are pixels for the chosen rectangle th x tw.
+bool tall_eligible(const ConvParams &p, bool vec, int *th, int *tw, double *eff);
+long long tall_tiles(const ConvParams &p, int th, int tw);
+hipError_t launch_tall(ConvParams p, int th, int tw, hipStream_t stream);
 
 // conv_stream.hip: tile 8 (streaming 1x1).
 bool stream_applicable(const ConvParams &p, bool vec);

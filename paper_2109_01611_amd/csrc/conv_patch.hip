@@ -31,9 +31,13 @@ namespace {
 // of the block: position pos = (v - v0)*(tw+2) + u.  An output pixel with first
 // virtual row v and block column tx reads tap (r, s) at
 // pos = (v - v0 + r)*(tw+2) + tx + s = base + r*(tw+2) + s, base fixed per
-// lane.  Each position is a 128-byte row of 64 channels, XOR-swizzled like the
-// weight tiles (by the position index).  The host guarantees that no tile
-// needs more than PMAX positions.
+// lane.  Each position is a 128-byte row of 64 channels whose 16-byte chunks are
+// XOR-swizzled (patch_key) by q = pos - 2 * (patch row): along consecutive output
+// pixels pos skips the two halo columns at the end of every block row, q does
+// not, so any 16 consecutive pixels at one tap still cover all 64 LDS banks.
+// (Swizzled by pos itself, every fragment read across such a seam cost an extra
+// LDS cycle per 16 lanes.)  The host guarantees that no tile needs more than PMAX
+// positions.
 //
 // Four consumer wavefronts (one per SIMD) own 32 tile rows x 64 channels each;
 // four producers issue the transfers.  Patch buffers alternate per channel
@@ -98,10 +102,10 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 #pragma unroll
         for (int j = 0; j < POPS; ++j) {
             const int pos = (j * NPROD + pw) * 8 + (lane >> 3);
-            const int cc = (lane & 7) ^ ((pos >> 1) & 7);
+            const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
+            const int cc = (lane & 7) ^ patch_key(pos, vr);
             a_off[j] = OOB;
             if (pos < npos) {
-                const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
                 const int v = v0 + vr;
                 const int n = fdiv(v, p.d_hp);
                 const int h = v - n * Hp - p.pad, w = q0 + u - p.pad;
@@ -169,12 +173,15 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
-        // Patch position of this lane's tile row at tap (0, 0).
-        int base = 0;
+        // Patch position of this lane's tile row at tap (0, 0), and that position's patch row.
+        int base = 0, brow = 0;
         {
             const int l = l0 + wave * 32 + frow;
             const int rho = fdiv(l, p.d_tw);
-            if (rho < NP) base = (vrow(rho) - v0) * pwt + (l - rho * p.tw);
+            if (rho < NP) {
+                brow = vrow(rho) - v0;
+                base = brow * pwt + (l - rho * p.tw);
+            }
         }
         // A ring step is 12 depth steps of 16 (three taps x four).  The fragments of depth
         // step i+AHEAD are requested before the matrix instructions of step i are issued, so
@@ -193,7 +200,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
                     const int s = i / (BK / 16), ks = i % (BK / 16);
                     const int pos = base + r * pwt + s;
                     f.a = *reinterpret_cast<const bf16x8 *>(pa + pos * BK +
-                                                            (((ks * 2 + fhalf) ^ ((pos >> 1) & 7)) * CHUNK));
+                                                            (((ks * 2 + fhalf) ^ patch_key(pos, brow + r)) * CHUNK));
 #pragma unroll
                     for (int j = 0; j < NT; ++j)
                         f.b[j] = *reinterpret_cast<const bf16x8 *>(
@@ -346,10 +353,10 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
 #pragma unroll
             for (int j = 0; j < POPS; ++j) {
                 const int pos = (j * NPROD + pw) * 8 + (lane >> 3);
-                const int cc = (lane & 7) ^ ((pos >> 1) & 7);
+                const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
+                const int cc = (lane & 7) ^ patch_key(pos, vr);
                 unsigned off = OOB;
                 if (pos < tl.npos) {
-                    const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
                     const int v = tl.v0 + vr;
                     const int n = fdiv(v, p.d_hp);
                     const int h = v - n * Hp - p.pad, w = tl.q0 + u - p.pad;
@@ -393,12 +400,13 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
         for (int t = 0; t < T; ++t) {
             const Tile tl = tile_at(t);
             // Patch positions of this lane's two pixels at tap (0, 0).
-            int base[2];
+            int base[2], brow[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int l = tl.l0 + wy * 64 + i * 32 + frow;
                 const int rho = fdiv(l, p.d_tw);
-                base[i] = rho < NP ? (vrow(rho) - tl.v0) * pwt + (l - rho * p.tw) : 0;
+                brow[i] = rho < NP ? vrow(rho) - tl.v0 : 0;
+                base[i] = rho < NP ? brow[i] * pwt + (l - rho * p.tw) : 0;
             }
             f32x16 acc[2];
 #pragma unroll
@@ -419,7 +427,7 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const int pos = base[h] + r * pwt + sx;
-                    f.a[h] = *reinterpret_cast<const bf16x8 *>(pa + pos * BK + (((ks * 2 + fhalf) ^ ((pos >> 1) & 7)) * CHUNK));
+                    f.a[h] = *reinterpret_cast<const bf16x8 *>(pa + pos * BK + (((ks * 2 + fhalf) ^ patch_key(pos, brow[h] + r)) * CHUNK));
                 }
             };
             Frags f[36];

@@ -587,7 +587,8 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
                                               void *workspace, size_t workspace_bytes, int warmup,
                                               int iters, int sync_each, float *latency_ms,
                                               float *total_ms) {
-    if (!live(p) || !latency_ms || iters < 1 || warmup < 0) return GPULET_EINVAL;
+    if (!live(p) || iters < 1 || warmup < 0 || sync_each < 0 || sync_each > 2) return GPULET_EINVAL;
+    if (sync_each == 2 ? !total_ms : !latency_ms) return GPULET_EINVAL;
     Plan plan;
     gpulet_status st = build_plan(m, batch, plan);
     if (st != GPULET_OK) return st;
@@ -602,6 +603,23 @@ extern "C" gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int ba
     }
     GPULET_HIP(hipStreamSynchronize(p->stream));
 
+    if (sync_each == 2) {
+        // one event pair around all batches
+        EventPair e;
+        GPULET_HIP(e.create());
+        GPULET_HIP(hipEventRecord(e.a, p->stream));
+        for (int i = 0; i < iters; ++i) {
+            GPULET_HIP(enqueue(bd, p));
+            p->batches_run.fetch_add(1);
+            p->images_run.fetch_add(static_cast<uint64_t>(batch));
+        }
+        GPULET_HIP(hipEventRecord(e.b, p->stream));
+        GPULET_HIP(hipEventSynchronize(e.b));
+        GPULET_HIP(hipEventElapsedTime(total_ms, e.a, e.b));
+        if (latency_ms)
+            for (int i = 0; i < iters; ++i) latency_ms[i] = *total_ms / static_cast<float>(iters);
+        return GPULET_OK;
+    }
     std::vector<EventPair> ev(static_cast<size_t>(iters));
     for (EventPair &e : ev) GPULET_HIP(e.create());
     for (int i = 0; i < iters; ++i) {

@@ -382,7 +382,8 @@ class ModelGraph:
 
 def profile_model(desc, batch, partition, x, y, workspace, workspace_bytes, warmup, iters,
                   sync_each=False):
-    """-> (list of per-batch milliseconds, total milliseconds)."""
+    """-> (list of per-batch milliseconds, total milliseconds).  ``sync_each`` False / True / 2:
+    back to back / one batch in flight / back to back inside a single event pair."""
     lat = (c_float * iters)()
     total = c_float()
     _check(lib.gpulet_profile_model(byref(desc), batch, partition.handle, ptr(x), ptr(y), ptr(workspace),

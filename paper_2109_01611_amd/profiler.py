@@ -22,6 +22,8 @@ from . import gpulet, lowering, scenarios, sched, workloads
 # Dense bf16 MFMA peak of one MI355X compute unit: 2.5 PFLOP/s over 256 CUs.
 PEAK_TFLOPS_PER_CU = 2500.0 / 256.0
 
+# Models whose batch takes tens of microseconds at most: LeNet and single layers ("conv3x3_...").
+
 
 def _extent(n, k, stride, pad):
     return (n + 2 * pad - k) // stride + 1
@@ -80,9 +82,10 @@ def measure(bound, part, warmup=20, iters=200, sync_each=True):
     torch.cuda.synchronize()
     lat, _ = gpulet.profile_model(*bound.args(part), warmup=warmup, iters=iters, sync_each=sync_each)
     mean, p50, p99 = gpulet.latency_stats(lat)
-    # throughput with batches enqueued back to back (no host wait in between)
-    n_tp = max(10, iters // 4)
-    _, total = gpulet.profile_model(*bound.args(part), warmup=2, iters=n_tp, sync_each=False)
+    # throughput: batches enqueued back to back inside one event pair (an event record between two
+    # batches of a few microseconds would be part of what is measured), at least 100 of them
+    n_tp = max(100, iters // 4)
+    _, total = gpulet.profile_model(*bound.args(part), warmup=10, iters=n_tp, sync_each=2)
     conv, fc = model_flops(bound.dm.model)
     flops = (conv + fc) * bound.batch
     tp_ms = total / n_tp
@@ -98,7 +101,11 @@ def measure(bound, part, warmup=20, iters=200, sync_each=True):
 
 def sweep(model, batches, pcts, seed=0, warmup=20, iters=200, device="cuda:0", log=None):
     """L(b, p) rows of one model over batch sizes and gpu-let sizes (one
-    gpu-let per size, every batch size measured on it)."""
+    gpu-let per size, every batch size measured on it).  Models whose batch takes
+    microseconds (LeNet, the single layer) get at least 1000 timed batches per row, so
+    that the 99th percentile rests on more than a handful of samples."""
+    if model.name == "lenet5" or model.name.startswith("conv"):
+        iters = max(iters, 1000)
     dm = lowering.DeviceModel(model, workloads.parameters(model, seed), device)
     bounds = [Bound(dm, b, seed) for b in batches]
     rows = {}

@@ -49,7 +49,7 @@ def test_conv_parity_every_tile(part, case):
     ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
     mag = conv_mag(x, w, b, stride, pad)
     first = None
-    for tile in range(-1, 11):
+    for tile in range(-1, 12):
         got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
         assert_close(got, ref, mag, what=tile)
         if tile < 0 or (tile == 9 and C <= 4):
@@ -85,6 +85,38 @@ def test_conv_patch_kernel_parity(part, case):
     ct = K + 16
     got, _ = gpu_conv(part, x, w, b, 1, 1, False, ch_total=ct, ch_offset=8, tile=7)
     assert_conv_close(got[:, 8:8 + K], x, w, b, 1, 1, False)
+    assert np.all(got[:, :8] == -512.0) and np.all(got[:, 8 + K:] == -512.0)
+
+
+# N, C, H, W, K: 3x3, stride 1, pad 1, C a multiple of 64 -> the tall tile (a pixel rectangle of one image
+# with its input patch in LDS, weights streamed tap by tap; tile 11)
+TALL_CASES = [
+    (2, 64, 56, 56, 128),      # 8 x 28 rectangles, one channel block
+    (1, 128, 28, 28, 136),     # 28-pixel rows do not divide into 8: ragged last rectangle; ragged second filter tile
+    (3, 64, 14, 14, 64),       # the whole image is one tile (196 of 224 rows)
+    (2, 192, 9, 33, 72),       # odd sizes, three channel blocks
+    (1, 64, 5, 3, 8),          # smaller than anything
+    (2, 256, 16, 16, 64),      # four channel blocks
+    (1, 64, 112, 112, 128),    # 56 rectangles per image
+    (2, 128, 30, 60, 264),     # rectangles ragged in both directions, three filter tiles
+    (5, 320, 7, 7, 40),        # five channel blocks, tiny maps: most rows of a tile are not pixels
+]
+
+
+@pytest.mark.parametrize("case", TALL_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_tall_tile_kernel_parity(part, case):
+    N, C, H, W, K = case
+    x, w, b = conv_tensors(27, N, C, H, W, K, 3)
+    res = inputs.tensor(27, "res_tall", (N, K, H, W), "normal")
+    got, raw = gpu_conv(part, x, w, b, 1, 1, True, residual=res, tile=11)
+    assert_conv_close(got, x, w, b, 1, 1, True, residual=res)
+    _, gathered = gpu_conv(part, x, w, b, 1, 1, True, residual=res, tile=1)
+    assert torch.equal(raw, gathered)          # same summation order as the gathering kernel
+    _, again = gpu_conv(part, x, w, b, 1, 1, True, residual=res, tile=11)
+    assert torch.equal(raw, again)
+    ct = K + 16
+    got, _ = gpu_conv(part, x, w, None, 1, 1, False, ch_total=ct, ch_offset=8, tile=11)
+    assert_conv_close(got[:, 8:8 + K], x, w, None, 1, 1, False)
     assert np.all(got[:, :8] == -512.0) and np.all(got[:, 8 + K:] == -512.0)
 
 
@@ -165,7 +197,7 @@ def test_conv_reading_a_channel_slice(part, case):
     wd = lowering.kcrs_to_krsc(w, DEV)
     bd = torch.from_numpy(b).to(DEV)
     ct, co = K + 16, 8
-    for tile in range(-1, 11):
+    for tile in range(-1, 12):
         yd = torch.full((N, P, Q, ct), -512.0, dtype=torch.bfloat16, device=DEV)
         torch.cuda.synchronize()
         gpulet.set_conv_tile(tile)
@@ -221,7 +253,7 @@ def test_1x1_conv_with_two_outputs(part, case):
     xd = lowering.nchw_to_nhwc(wide, DEV)
     wd = lowering.kcrs_to_krsc(w, DEV)
     bd = torch.from_numpy(b).to(DEV)
-    for tile in range(-1, 11):
+    for tile in range(-1, 12):
         y1 = torch.full((N, P, Q, ldy or k2), -512.0, dtype=torch.bfloat16, device=DEV)
         y2 = torch.full((N, P, Q, ldy2 or K - k2), -512.0, dtype=torch.bfloat16, device=DEV)
         torch.cuda.synchronize()
@@ -278,7 +310,7 @@ def test_1x1_conv_carrying_the_max_pool_of_its_input(part, case):
     xd = lowering.nchw_to_nhwc(x, DEV)
     wd = lowering.kcrs_to_krsc(w, DEV)
     bd = torch.from_numpy(b).to(DEV)
-    for tile in range(-1, 11):
+    for tile in range(-1, 12):
         y1 = torch.full((N, H, W, k2 or K), -512.0, dtype=torch.bfloat16, device=DEV)
         y2 = torch.full((N, H, W, K - k2), -512.0, dtype=torch.bfloat16, device=DEV) if k2 else None
         pool = torch.full((N, H, W, C), -512.0, dtype=torch.bfloat16, device=DEV)
@@ -359,7 +391,7 @@ def test_independent_convs_in_one_launch(part, case):
                           x_ch_stride=wide_c, x_ch_offset=xo))
         outs.append((P, Q, K, off))
         off += K
-    for tile in range(-1, 11):
+    for tile in range(-1, 12):
         if same_size:       # slices of one concatenated tensor
             cat = torch.full((N, outs[0][0], outs[0][1], total), -512.0, dtype=torch.bfloat16, device=DEV)
             ys = [cat] * len(members)
@@ -758,6 +790,6 @@ def test_conv_random_shapes_through_every_kernel_family(part, case):
     relu = bool((N + K) % 2)
     ref = oracle.conv2d(x, w, b, stride, pad, relu)
     mag = conv_mag(x, w, b, stride, pad)
-    for tile in (-1, 7, 8, 9, 10, 3):
+    for tile in (-1, 7, 8, 9, 10, 11, 3):
         got, _ = gpu_conv(part, x, w, b, stride, pad, relu, tile=tile)
         assert_close(got, ref, mag, what=tile)
