@@ -156,6 +156,49 @@ gpulet_status gpulet_interference_predict(const double *coef, const double *feat
 gpulet_status gpulet_interference_error(const double *coef, const double *features, const double *factor, int n,
                                         const double *q, int n_q, double *error_at_q);
 
+/*
+ * The two features of one solo run (Sec. 4.4: L2 utilisation and DRAM bandwidth
+ * utilisation "measured in the solo run" of a model at a batch size on a gpu-let):
+ *   l2_util  = l2_requests / seconds / l2_peak_requests_per_s
+ *   mem_util = (fetch_bytes + write_bytes) / seconds / mem_peak_bytes_per_s
+ * with seconds = solo_ms / 1000: the counters of the whole run over the latency
+ * of that run, relative to what the whole GPU can do (the shared L2 and memory
+ * are not partitioned, so the peaks are the GPU's, not the gpu-let's share).
+ * Counter totals must be >= 0, solo_ms and the peaks > 0, everything finite.
+ */
+gpulet_status gpulet_interference_utilisation(double l2_requests, double fetch_bytes, double write_bytes,
+                                              double solo_ms, double l2_peak_requests_per_s,
+                                              double mem_peak_bytes_per_s, double *l2_util, double *mem_util);
+
+/* factor[i] = corun_ms[i] / solo_ms[i] (both > 0): how much slower the victim ran next to its neighbour. */
+gpulet_status gpulet_interference_factor(const double *corun_ms, const double *solo_ms, int n, double *factor);
+
+/*
+ * Training / validation split of n samples (Sec. 4.4: 1,750 of 2,500 samples
+ * for training, 750 for validation, i.e. 70 / 30): the samples are ordered by
+ * the caller's keys key[0..n) (one seeded uniform draw per sample; equal keys
+ * keep their index order), the first *n_train = floor(7 n / 10) of that order
+ * train, the rest validate.  order receives the n sample indices in that order.
+ */
+gpulet_status gpulet_interference_split(const double *key, int n, int *order, int *n_train);
+
+/*
+ * Entry of the scheduler's slowdown matrix for one (victim, aggressor) pair of
+ * models: the largest predicted factor over the n feature rows given (every
+ * profiled pair of batch sizes and every split), minus one, not below zero.
+ */
+gpulet_status gpulet_interference_worst_slowdown(const double *coef, const double *features, int n,
+                                                 double *slowdown);
+
+/*
+ * Distribution of the measured overhead factor - 1 over n co-runs (Fig. 6):
+ * its value at the percentiles q[0..n_q) (nearest rank, as everywhere in this
+ * library) and the share of samples strictly below `threshold` (the paper
+ * quotes 18 %).  share_below may be NULL.
+ */
+gpulet_status gpulet_interference_overhead(const double *factor, int n, const double *q, int n_q,
+                                           double *overhead_at_q, double threshold, double *share_below);
+
 #ifdef __cplusplus
 }
 #endif

@@ -52,3 +52,36 @@ def percentile(values, q):
     """Nearest-rank percentile (q in (0, 100])."""
     v = sorted(float(e) for e in values)
     return v[max(0, int(math.ceil(q / 100.0 * len(v))) - 1)]
+
+
+def utilisation(l2_requests, fetch_bytes, write_bytes, solo_ms, l2_peak_requests_per_s, mem_peak_bytes_per_s):
+    """The two features of one solo run (Sec. 4.4): counter totals of the run over its latency,
+    relative to the whole GPU's L2 request rate and memory bandwidth -> (l2, mem)."""
+    seconds = solo_ms / 1000.0
+    l2_rate = l2_requests / seconds
+    mem_rate = (fetch_bytes + write_bytes) / seconds
+    return l2_rate / l2_peak_requests_per_s, mem_rate / mem_peak_bytes_per_s
+
+
+def factors(corun_ms, solo_ms):
+    """Co-run latency over solo latency of the victim, per sample."""
+    return [c / s for c, s in zip(corun_ms, solo_ms)]
+
+
+def split(keys):
+    """70 / 30 split (Sec. 4.4: 1,750 of 2,500 samples train, 750 validate): samples in the order
+    of their keys (ties by index), the first floor(0.7 n) train -> (train indices, validation indices)."""
+    order = sorted(range(len(keys)), key=lambda i: (keys[i], i))
+    n_train = (7 * len(keys)) // 10
+    return order[:n_train], order[n_train:]
+
+
+def worst_slowdown(c, features):
+    """Largest predicted factor over the rows, minus one, not below zero."""
+    return max(0.0, max(float(v) for v in predict(c, features)) - 1.0)
+
+
+def overhead(factor_values, qs, threshold):
+    """Overhead factor - 1 at the percentiles qs (nearest rank) and the share strictly below threshold."""
+    over = [f - 1.0 for f in factor_values]
+    return [percentile(over, q) for q in qs], sum(1 for o in over if o < threshold) / len(over)

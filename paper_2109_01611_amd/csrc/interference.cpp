@@ -100,4 +100,64 @@ gpulet_status gpulet_interference_error(const double *coef, const double *featur
     return GPULET_OK;
 }
 
+gpulet_status gpulet_interference_utilisation(double l2_requests, double fetch_bytes, double write_bytes,
+                                              double solo_ms, double l2_peak_requests_per_s,
+                                              double mem_peak_bytes_per_s, double *l2_util, double *mem_util) {
+    if (!l2_util || !mem_util) return GPULET_EINVAL;
+    const double v[6] = {l2_requests, fetch_bytes, write_bytes, solo_ms, l2_peak_requests_per_s, mem_peak_bytes_per_s};
+    if (!finite_all(v, 6)) return GPULET_EINVAL;
+    if (l2_requests < 0.0 || fetch_bytes < 0.0 || write_bytes < 0.0 || !(solo_ms > 0.0) ||
+        !(l2_peak_requests_per_s > 0.0) || !(mem_peak_bytes_per_s > 0.0))
+        return GPULET_EINVAL;
+    const double seconds = solo_ms * 1e-3;
+    *l2_util = l2_requests / seconds / l2_peak_requests_per_s;
+    *mem_util = (fetch_bytes + write_bytes) / seconds / mem_peak_bytes_per_s;
+    return GPULET_OK;
+}
+
+gpulet_status gpulet_interference_factor(const double *corun_ms, const double *solo_ms, int n, double *factor) {
+    if (!factor || n < 1 || !finite_all(corun_ms, n) || !finite_all(solo_ms, n)) return GPULET_EINVAL;
+    for (int i = 0; i < n; ++i)
+        if (!(corun_ms[i] > 0.0) || !(solo_ms[i] > 0.0)) return GPULET_EINVAL;
+    for (int i = 0; i < n; ++i) factor[i] = corun_ms[i] / solo_ms[i];
+    return GPULET_OK;
+}
+
+gpulet_status gpulet_interference_split(const double *key, int n, int *order, int *n_train) {
+    if (!order || !n_train || n < 1 || !finite_all(key, n)) return GPULET_EINVAL;
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order, order + n, [key](int a, int b) { return key[a] < key[b]; });
+    *n_train = static_cast<int>((7LL * n) / 10);
+    return GPULET_OK;
+}
+
+gpulet_status gpulet_interference_worst_slowdown(const double *coef, const double *features, int n,
+                                                 double *slowdown) {
+    if (!slowdown || n < 1 || !finite_all(coef, NC) || !finite_all(features, 4LL * n)) return GPULET_EINVAL;
+    double worst = model(coef, features);
+    for (int i = 1; i < n; ++i) worst = std::max(worst, model(coef, features + 4LL * i));
+    *slowdown = std::max(0.0, worst - 1.0);
+    return GPULET_OK;
+}
+
+gpulet_status gpulet_interference_overhead(const double *factor, int n, const double *q, int n_q,
+                                           double *overhead_at_q, double threshold, double *share_below) {
+    if (!overhead_at_q || !q || n < 1 || n_q < 1 || !finite_all(factor, n) || !std::isfinite(threshold))
+        return GPULET_EINVAL;
+    std::vector<double> over(factor, factor + n);
+    for (double &o : over) o -= 1.0;
+    std::sort(over.begin(), over.end());
+    for (int k = 0; k < n_q; ++k) {
+        if (!(q[k] > 0.0) || !(q[k] <= 100.0)) return GPULET_EINVAL;
+        const int rank = static_cast<int>(std::ceil(q[k] / 100.0 * n));
+        overhead_at_q[k] = over[std::max(0, rank - 1)];
+    }
+    if (share_below) {
+        long long below = 0;
+        for (double o : over) below += o < threshold ? 1 : 0;
+        *share_below = static_cast<double>(below) / static_cast<double>(n);
+    }
+    return GPULET_OK;
+}
+
 }  // extern "C"

@@ -134,6 +134,11 @@ def _load():
         "gpulet_interference_fit": ([DP, DP, I, DP], c_int32),
         "gpulet_interference_predict": ([DP, DP, I, DP], c_int32),
         "gpulet_interference_error": ([DP, DP, DP, I, DP, I, DP], c_int32),
+        "gpulet_interference_utilisation": ([c_double] * 6 + [DP, DP], c_int32),
+        "gpulet_interference_factor": ([DP, DP, I, DP], c_int32),
+        "gpulet_interference_split": ([DP, I, IP, IP], c_int32),
+        "gpulet_interference_worst_slowdown": ([DP, DP, I, DP], c_int32),
+        "gpulet_interference_overhead": ([DP, I, DP, I, DP, c_double, DP], c_int32),
     }
     for name, (argtypes, restype) in sig.items():
         fn = getattr(L, name)

@@ -1,8 +1,10 @@
 """Interference between two gpu-lets sharing a GPU (paper Sec. 3.2 / Fig. 6) and
 the linear model that predicts it (Sec. 4.4 / Fig. 9), measured on one MI355X.
 
-Three measurement steps and two analysis steps; all arithmetic of the model
-(fit, prediction, error percentiles) runs in ``libgpulet.so``:
+Three measurement steps and two analysis steps; all arithmetic of the method
+(utilisation features, co-run factor, training / validation split, fit,
+prediction, error and overhead percentiles, slowdown matrix) runs in
+``libgpulet.so``; this module reads counter files, marshals and prints:
 
 1. ``solo`` (run under the profiler, once per counter set): every model at every
    batch size on every gpu-let size, alone, so that the per-dispatch counters
@@ -46,8 +48,6 @@ MODELS = ("lenet5", "googlenet", "resnet50", "ssd_mobilenet", "vgg16")
 BATCHES = (2, 4, 8, 16, 32)
 SPLITS = (20, 40, 50, 60, 80)       # size of the first gpu-let; the second takes the rest
 COPY_BYTES = 64 << 20
-L2_PEAK_REQ_PER_S = 128 * 2.4e9     # 16 L2 channels on each of 8 dies, one request per clock at 2.4 GHz
-HBM_PEAK_BYTES_PER_S = 8e12
 
 
 def _lowered(names):
@@ -164,31 +164,30 @@ def sweep(out_path, window_ms=120.0, alone_iters=30):
 
 
 def utilisation(feat, side):
-    """(L2 utilisation, memory-bandwidth utilisation) of one solo run."""
+    """(L2 utilisation, memory-bandwidth utilisation) of one solo run, from its counter totals."""
+    from paper_2109_01611_amd import sched
     f = feat["%s/%d/%d" % (side["model"], side["batch"], side["pct"])]
-    seconds = side["alone_ms"] * 1e-3
-    l2 = f["TCC_REQ_sum"] / seconds / L2_PEAK_REQ_PER_S
-    mem = (f["FETCH_SIZE_bytes"] + f["WRITE_SIZE_bytes"]) / seconds / HBM_PEAK_BYTES_PER_S
-    return l2, mem
+    return sched.interference_utilisation(f["TCC_REQ_sum"], f["FETCH_SIZE_bytes"], f["WRITE_SIZE_bytes"],
+                                          side["alone_ms"])
 
 
 def fit(features_path, samples_path, report_path, seed=0):
     import numpy as np
     from paper_2109_01611_amd import inputs, sched
     feat = json.load(open(features_path))
-    rows, factors, tags = [], [], []
+    rows, corun, alone, tags = [], [], [], []
     for s in json.load(open(samples_path)):
         for victim, aggressor in ((s["a"], s["b"]), (s["b"], s["a"])):
             l2v, memv = utilisation(feat, victim)
             l2a, mema = utilisation(feat, aggressor)
             rows.append([l2v, l2a, memv, mema])
-            factors.append(victim["corun_ms"] / victim["alone_ms"])
+            corun.append(victim["corun_ms"])
+            alone.append(victim["alone_ms"])
             tags.append("%s b%d %d%% next to %s b%d" % (victim["model"], victim["batch"], victim["pct"],
                                                          aggressor["model"], aggressor["batch"]))
+    factors = sched.interference_factor(corun, alone)
     n = len(factors)
-    order = np.argsort(inputs.uniform(seed, "interference/split", n), kind="stable")
-    n_train = (n * 7) // 10
-    tr, va = order[:n_train], order[n_train:]
+    tr, va = sched.interference_split(list(inputs.uniform(seed, "interference/split", n)))
     pick = lambda idx, seq: [seq[i] for i in idx]
     coef = sched.interference_fit(pick(tr, rows), pick(tr, factors))
     qs = (50.0, 90.0, 95.0, 100.0)
@@ -196,15 +195,15 @@ def fit(features_path, samples_path, report_path, seed=0):
     err_train = sched.interference_error(coef, pick(tr, rows), pick(tr, factors), qs)
     const = [0.0, 0.0, 0.0, 0.0, sum(pick(tr, factors)) / len(tr)]       # no-feature baseline: the mean factor
     err_const = sched.interference_error(const, pick(va, rows), pick(va, factors), qs)
-    over = sorted(f - 1.0 for f in factors)
+    (o50, o90, o99, omax), below18 = sched.interference_overhead(factors, (50.0, 90.0, 99.0, 100.0), 0.18)
     report = {
         "samples": n, "train": int(len(tr)), "validate": int(len(va)),
         "coefficients_c1_c5": coef,
         "validation_error_at_percentile": dict(zip(map(str, qs), err_val)),
         "training_error_at_percentile": dict(zip(map(str, qs), err_train)),
         "mean_factor_baseline_error_at_percentile": dict(zip(map(str, qs), err_const)),
-        "overhead_distribution": {"median": over[n // 2], "p90": over[int(0.9 * n)], "p99": over[int(0.99 * n)],
-                                  "max": over[-1], "share_below_18_percent": sum(o < 0.18 for o in over) / n},
+        "overhead_distribution": {"median": o50, "p90": o90, "p99": o99, "max": omax,
+                                  "share_below_18_percent": below18},
         "feature_ranges": {"l2": [min(r[0] for r in rows), max(r[0] for r in rows)],
                            "mem": [min(r[2] for r in rows), max(r[2] for r in rows)]},
         "worst_cases": [tags[i] + ": x%.3f" % factors[i] for i in np.argsort(factors)[::-1][:8]],
@@ -232,7 +231,7 @@ def slowdown_matrix(feat, coef, latency_ms, names):
                         l2v, memv = utilisation(feat, sv)
                         l2a, mema = utilisation(feat, sa)
                         rows.append([l2v, l2a, memv, mema])
-            row.append(max(0.0, max(sched.interference_predict(coef, rows)) - 1.0))
+            row.append(sched.interference_worst_slowdown(coef, rows))
         F.append(row)
     return F
 

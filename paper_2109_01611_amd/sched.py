@@ -105,5 +105,53 @@ def interference_error(coef, features, factors, percentiles=(90.0, 95.0)):
     return list(out)
 
 
+# The whole GPU's L2 request rate (16 channels on each of 8 dies, one request per clock at 2.4 GHz) and
+# HBM bandwidth: what solo-run counter totals are put in relation to.
+L2_PEAK_REQ_PER_S = 128 * 2.4e9
+HBM_PEAK_BYTES_PER_S = 8e12
+
+
+def interference_utilisation(l2_requests, fetch_bytes, write_bytes, solo_ms, l2_peak=L2_PEAK_REQ_PER_S,
+                             mem_peak=HBM_PEAK_BYTES_PER_S):
+    """-> (L2 utilisation, memory-bandwidth utilisation) of one solo run from its counter totals."""
+    l2, mem = c_double(), c_double()
+    _check(lib.gpulet_interference_utilisation(l2_requests, fetch_bytes, write_bytes, solo_ms, l2_peak, mem_peak,
+                                               byref(l2), byref(mem)), "gpulet_interference_utilisation")
+    return l2.value, mem.value
+
+
+def interference_factor(corun_ms, solo_ms):
+    n = len(corun_ms)
+    out = (c_double * n)()
+    _check(lib.gpulet_interference_factor(_doubles(corun_ms), _doubles(solo_ms), n, out),
+           "gpulet_interference_factor")
+    return list(out)
+
+
+def interference_split(keys):
+    """-> (training indices, validation indices): 70 / 30 in the order of the seeded keys."""
+    n = len(keys)
+    order, n_train = (c_int * n)(), c_int()
+    _check(lib.gpulet_interference_split(_doubles(keys), n, order, byref(n_train)), "gpulet_interference_split")
+    return list(order[:n_train.value]), list(order[n_train.value:])
+
+
+def interference_worst_slowdown(coef, features):
+    out = c_double()
+    _check(lib.gpulet_interference_worst_slowdown(_doubles(coef), _flat(features), len(features), byref(out)),
+           "gpulet_interference_worst_slowdown")
+    return out.value
+
+
+def interference_overhead(factors, percentiles=(50.0, 90.0, 99.0, 100.0), threshold=0.18):
+    """-> (overhead = factor - 1 at the percentiles (nearest rank), share of samples below ``threshold``)."""
+    out, share = (c_double * len(percentiles))(), c_double()
+    _check(lib.gpulet_interference_overhead(_doubles(factors), len(factors), _doubles(percentiles), len(percentiles),
+                                            out, threshold, byref(share)), "gpulet_interference_overhead")
+    return list(out), share.value
+
+
 __all__ = ["affordable_rate", "rate_curve", "max_efficient_partition", "min_required_partition",
-           "elastic_partitioning", "interference_fit", "interference_predict", "interference_error", "gpulet"]
+           "elastic_partitioning", "interference_fit", "interference_predict", "interference_error",
+           "interference_utilisation", "interference_factor", "interference_split", "interference_worst_slowdown",
+           "interference_overhead", "gpulet"]

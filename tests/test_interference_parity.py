@@ -66,3 +66,48 @@ def test_argument_errors():
         sched.interference_error([0, 0, 0, 0, 1.0], f.tolist(), (-np.abs(y)).tolist(), (90.0,))
     with pytest.raises(gpulet.GpuletError):
         sched.interference_error([0, 0, 0, 0, 1.0], f.tolist(), np.abs(y).tolist(), (0.0,))
+
+
+def test_features_factor_split_slowdown_and_overhead_match():
+    n = 600
+    cnt = inputs.uniform(8, "intf/counters", 4 * n).reshape(n, 4)
+    l2_peak, mem_peak = sched.L2_PEAK_REQ_PER_S, sched.HBM_PEAK_BYTES_PER_S
+    feats = []
+    for r in cnt:
+        args = (r[0] * 3e8, r[1] * 2e9, r[2] * 1e9, 0.05 + 3.0 * r[3])
+        got = sched.interference_utilisation(*args)
+        want = I.utilisation(*args, l2_peak, mem_peak)
+        assert got == pytest.approx(want, rel=1e-13)
+        feats.append(got)
+    corun = (1.0 + cnt[:, 0]).tolist()
+    solo = (0.5 + cnt[:, 1]).tolist()
+    fac = sched.interference_factor(corun, solo)
+    assert fac == pytest.approx(I.factors(corun, solo), rel=1e-15)
+    keys = list(inputs.uniform(8, "intf/keys", n))
+    keys[17] = keys[3]                                    # a tie
+    assert sched.interference_split(keys) == I.split(keys)
+    assert sched.interference_split(list(inputs.uniform(8, "intf/keys2500", 2500))) == \
+        I.split(list(inputs.uniform(8, "intf/keys2500", 2500)))
+    c = [0.31, -0.07, 0.52, 0.11, 0.95]
+    rows = [[a[0], b[0], a[1], b[1]] for a, b in zip(feats[::2], feats[1::2])]
+    assert sched.interference_worst_slowdown(c, rows) == pytest.approx(I.worst_slowdown(c, rows), rel=1e-12)
+    assert sched.interference_worst_slowdown([0, 0, 0, 0, 0.5], rows) == 0.0
+    qs = (1.0, 50.0, 90.0, 99.0, 100.0)
+    at, share = sched.interference_overhead(fac, qs, 0.18)
+    want_at, want_share = I.overhead(fac, qs, 0.18)
+    assert at == pytest.approx(want_at, rel=1e-13, abs=1e-15) and share == want_share
+
+
+def test_new_entry_points_refuse_bad_arguments():
+    with pytest.raises(gpulet.GpuletError):
+        sched.interference_utilisation(1.0, 1.0, 1.0, 0.0)               # no latency
+    with pytest.raises(gpulet.GpuletError):
+        sched.interference_utilisation(-1.0, 1.0, 1.0, 1.0)
+    with pytest.raises(gpulet.GpuletError):
+        sched.interference_factor([1.0, 2.0], [1.0, 0.0])
+    with pytest.raises(gpulet.GpuletError):
+        sched.interference_split([0.1, float("nan")])
+    with pytest.raises(gpulet.GpuletError):
+        sched.interference_overhead([1.1, 1.2], (0.0,), 0.18)
+    with pytest.raises(gpulet.GpuletError):
+        sched.interference_worst_slowdown([0, 0, 0, 0, float("inf")], [[0, 0, 0, 0]])
