@@ -287,16 +287,19 @@ gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const fl
  *  11: 224x128: a rectangle of up to 224 pixels of one image (8 x 28 on maps
  *      56, 112 or 224 pixels wide) with its input patch resident in LDS and
  *      the weights streamed one filter tap at a time (3x3 filters, stride 1,
- *      pad 1, C a multiple of 64; other shapes run tile 1 instead),
+ *      pad 1, C a multiple of 64; other shapes run tile 1 instead)
+ *  12: 192x128  13: 96x128 (gathering tiles with three 32-pixel row tiles per
+ *      wavefront, for layers whose 128-pixel tiles just miss a whole number of
+ *      rounds on a gpu-let),
  * or -1 to return to automatic selection, which picks the tile whose busiest
  * CU has the least work for the launch's shape and the stream's CU count, and
- * tile 9 wherever it applies.  Tiles 0..8, 10 and 11 give bit-identical results; tile 9
+ * tile 9 wherever it applies.  All tiles but 9 give bit-identical results; tile 9
  * groups the same ascending sum differently (zero padding inside the depth),
  * so it agrees with them to rounding.  Tiles 7..11 need dense input pixels and
  * a single output: a layer that reads a channel slice or stores to two tensors
- * counts as another shape for them.  GPULET_EINVAL outside -1..11.
+ * counts as another shape for them.  GPULET_EINVAL outside -1..13.
  */
-enum { GPULET_CONV_TILES = 12 };
+enum { GPULET_CONV_TILES = 14 };
 gpulet_status gpulet_set_conv_tile(int tile);
 
 /*
@@ -545,7 +548,10 @@ gpulet_status gpulet_profile_model(const gpulet_model_desc *m, int batch, gpulet
  * are driven by two host threads, each dispatching one batch at a time (timed
  * by its own event pair, waited for before the next) until `window_ms` of wall
  * time has passed after `warmup` untimed batches each; the timed windows of
- * the two threads start together.  lat_a/lat_b (capacity cap_a/cap_b)
+ * the two threads start together.  The side whose window ends first stops;
+ * the other stops after the batch it is running then, and that batch, which ran
+ * partly alone, is not reported (it still counts in the gpu-let's counters), so
+ * every reported latency is a co-run latency.  lat_a/lat_b (capacity cap_a/cap_b)
  * receive the per-batch latencies, *n_a and *n_b how many were recorded (batches
  * beyond the capacity still run but are not recorded).  pa and pb must be
  * different live gpu-lets of one device.

@@ -22,14 +22,20 @@ std::atomic<int> g_max_split_k{1};
 std::atomic<int> g_tile_override{-1};
 
 struct TileChoice {
-    int bm, bn;
+    int id, bm, bn;
     float eff;  // relative MFMA efficiency of the tile shape (bigger tiles reuse LDS reads more)
 };
 
-// The gathering tiles (index = tile id) and the order in which they are tried.
-const TileChoice kTiles[] = {{128, 128, 0.90f}, {128, 64, 0.72f}, {64, 128, 0.72f}, {64, 64, 0.58f},
-                             {128, 32, 0.30f},  {32, 128, 0.40f}, {256, 128, 1.00f}};
-const int kOrder[] = {6, 0, 2, 1, 3, 5, 4};
+// The gathering tiles in the order in which they are tried (on a tie the earlier one wins).
+// 192x128 and 96x128 exist for the layers whose 128-pixel tiles just miss a whole number of
+// rounds on a gpu-let (98 tiles on 96 CUs, 196 on 192): three row tiles per wavefront instead
+// of two or four change the tile count enough to save a round.
+const TileChoice kTiles[] = {{6, 256, 128, 1.00f}, {12, 192, 128, 0.93f}, {0, 128, 128, 0.90f}, {13, 96, 128, 0.80f},
+                             {2, 64, 128, 0.72f},  {1, 128, 64, 0.72f},   {3, 64, 64, 0.58f},   {5, 32, 128, 0.40f},
+                             {4, 128, 32, 0.30f}};
+constexpr int kNumTiles = static_cast<int>(sizeof(kTiles) / sizeof(kTiles[0]));
+
+bool is_gathering_tile(int id) { return (id >= 0 && id <= 6) || id == 12 || id == 13; }
 
 
 }  // namespace
@@ -149,9 +155,9 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     int best = 0, best_split = 1;
     double best_cost = 0.0;
     const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
-    for (int o = 0; o < static_cast<int>(sizeof(kOrder) / sizeof(kOrder[0])); ++o) {
-        const int i = kOrder[o];
-        const TileChoice &t = kTiles[i];
+    for (int o = 0; o < kNumTiles; ++o) {
+        const TileChoice &t = kTiles[o];
+        const int i = t.id;
         const long long tiles = 1LL * ((p.M + t.bm - 1) / t.bm) * ((p.K + t.bn - 1) / t.bn);
         for (int sk = 1; sk <= max_split; ++sk) {
             if (sk > 1) {
@@ -282,7 +288,7 @@ hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hip
             break;
         }
         const Choice c = choose_kernel(p[j], vec, ctx);
-        if (c.best > 6 || c.split > 1) together = false;
+        if (!is_gathering_tile(c.best) || c.split > 1) together = false;
     }
     if (launches) *launches = together ? 1 : n;
     if (!together) {
@@ -301,21 +307,21 @@ hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hip
     }
     int best = 0;
     double best_cost = 0.0;
-    for (int o = 0; o < static_cast<int>(sizeof(kOrder) / sizeof(kOrder[0])); ++o) {
-        const TileChoice &t = kTiles[kOrder[o]];
+    for (int o = 0; o < kNumTiles; ++o) {
+        const TileChoice &t = kTiles[o];
         long long tiles = 0;
         for (int j = 0; j < n; ++j) tiles += 1LL * ((p[j].M + t.bm - 1) / t.bm) * ((p[j].K + t.bn - 1) / t.bn);
         double eff = t.eff;
         // the same bonus as in a single launch for 128x128 with two workgroups per CU, at the
         // members' mean depth (inception 3a's group at batch 32: 18.0 -> 15.8 us)
-        if (kOrder[o] == 0 && tiles128 > n_cu) eff = std::min(1.2, 0.90 + 3.0 * tiles128 / slices128);
+        if (t.id == 0 && tiles128 > n_cu) eff = std::min(1.2, 0.90 + 3.0 * tiles128 / slices128);
         const double cost = static_cast<double>((tiles + n_cu - 1) / n_cu) * t.bm * t.bn / eff;
         if (o == 0 || cost < best_cost) {
-            best = kOrder[o];
+            best = t.id;
             best_cost = cost;
         }
     }
-    if (forced >= 0 && forced <= 6) best = forced;
+    if (is_gathering_tile(forced)) best = forced;
     return launch_igemm_group(p, n, best, tiles128 > n_cu, stream);
 }
 

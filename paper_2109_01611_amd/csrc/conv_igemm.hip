@@ -669,6 +669,8 @@ hipError_t launch_igemm_group(const ConvParams *p, int n, int tile, bool two_sta
         case 3: return launch_group_tile<64, 64, 2, 2, 2, 3>(p, n, stream);
         case 4: return launch_group_tile<128, 32, 4, 1, 2, 3>(p, n, stream);
         case 5: return launch_group_tile<32, 128, 1, 4, 2, 3>(p, n, stream);
+        case 12: return launch_group_tile<192, 128, 2, 4, 4, 3>(p, n, stream);
+        case 13: return launch_group_tile<96, 128, 1, 4, 4, 3>(p, n, stream);
         default: return launch_group_tile<256, 128, 4, 2, 4, 3>(p, n, stream);
     }
 }
@@ -685,6 +687,14 @@ hipError_t launch_igemm(const ConvParams &p, bool vec, int tile, int split_k, bo
         case 3: return launch_tile<64, 64, 2, 2, 2, 3, 2, 2>(p, vec, split_k, stream);
         case 4: return launch_tile<128, 32, 4, 1, 2, 3, 4, 1>(p, vec, split_k, stream);
         case 5: return launch_tile<32, 128, 1, 4, 2, 3, 1, 4>(p, vec, split_k, stream);
+        // three row tiles per consumer (96 pixels x 32 filters); the scalar-gather variant has no such
+        // instance and takes the nearest shape
+        case 12:
+            if (!vec) return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, split_k, stream);
+            return launch_tile<192, 128, 2, 4, 4, 3, 2, 2>(p, vec, split_k, stream);
+        case 13:
+            if (!vec) return launch_tile<128, 128, 4, 2, 4, 3, 2, 2>(p, vec, split_k, stream);
+            return launch_tile<96, 128, 1, 4, 4, 3, 2, 2>(p, vec, split_k, stream);
         default: return launch_tile<256, 128, 4, 2, 4, 3, 2, 2>(p, vec, split_k, stream);
     }
 }

@@ -762,7 +762,11 @@ struct CorunSide {
     int hip_error = 0;
 };
 
-void corun_thread(CorunSide *s, std::atomic<int> *ready, double window_ms) {
+// `done` / `other_done`: a side raises its flag when it leaves the window.  The batch a side is
+// running when its neighbour leaves ran partly alone, so it is not reported (it still counts as a
+// batch run on the gpu-let), and the side stops there: both sides' samples are co-run samples only.
+void corun_thread(CorunSide *s, std::atomic<int> *ready, double window_ms, std::atomic<int> *done,
+                  const std::atomic<int> *other_done) {
     auto fail = [&](hipError_t e) {
         s->status = GPULET_EHIP;
         s->hip_error = static_cast<int>(e);
@@ -780,6 +784,7 @@ void corun_thread(CorunSide *s, std::atomic<int> *ready, double window_ms) {
     while (ready->load() < 2) std::this_thread::yield();
     if (e != hipSuccess) {
         fail(e);
+        done->store(1);
         return;
     }
     const auto t0 = std::chrono::steady_clock::now();
@@ -788,13 +793,15 @@ void corun_thread(CorunSide *s, std::atomic<int> *ready, double window_ms) {
         e = timed_batch(s->bd, s->p, s->batch, ev, &ms);
         if (e != hipSuccess) {
             fail(e);
-            return;
+            break;
         }
+        if (other_done->load()) break;      // the neighbour left while this batch ran: not a co-run sample
         if (s->n < s->cap) s->lat[s->n] = ms;
         ++s->n;
         const double el = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
         if (el >= window_ms) break;
     }
+    done->store(1);
 }
 
 }  // namespace
@@ -819,9 +826,9 @@ extern "C" gpulet_status gpulet_profile_corun(
 
     CorunSide sa{&plan_a, Bound{&plan_a, in_a, out_a, static_cast<char *>(ws_a)}, pa, batch_a, warmup, cap_a, lat_a};
     CorunSide sb{&plan_b, Bound{&plan_b, in_b, out_b, static_cast<char *>(ws_b)}, pb, batch_b, warmup, cap_b, lat_b};
-    std::atomic<int> ready{0};
-    std::thread ta(corun_thread, &sa, &ready, window_ms);
-    std::thread tb(corun_thread, &sb, &ready, window_ms);
+    std::atomic<int> ready{0}, done_a{0}, done_b{0};
+    std::thread ta(corun_thread, &sa, &ready, window_ms, &done_a, &done_b);
+    std::thread tb(corun_thread, &sb, &ready, window_ms, &done_b, &done_a);
     ta.join();
     tb.join();
     *n_a = std::min(sa.n, cap_a);

@@ -381,8 +381,10 @@ def test_corun_two_gpulets_gives_same_results_and_counts():
         la, lb = gpulet.profile_corun((da.desc, 4, p0, xad, ya, wsa, na), (db.desc, 6, p1, xbd, yb, wsb, nb),
                                       warmup=2, window_ms=200.0)
         assert len(la) >= 1 and len(lb) >= 1 and min(la) > 0 and min(lb) > 0
-        assert p0.counters() == (2 + len(la), 4 * (2 + len(la)))
-        assert p1.counters() == (2 + len(lb), 6 * (2 + len(lb)))
+        # the side that was still running when the other left ran one more batch, which is not reported
+        extra = [p0.counters()[0] - 2 - len(la), p1.counters()[0] - 2 - len(lb)]
+        assert sorted(extra) in ([0, 0], [0, 1])
+        assert p0.counters()[1] == 4 * p0.counters()[0] and p1.counters()[1] == 6 * p1.counters()[0]
         with pytest.raises(gpulet.GpuletError):
             gpulet.profile_corun((da.desc, 4, p0, xad, ya, wsa, na), (db.desc, 6, p0, xbd, yb, wsb, nb), 1, 10.0)
     _assert_close(ya.cpu().numpy().astype(np.float64).reshape(4, -1), oracle.run_model(ma, pa_, xa))
