@@ -79,6 +79,23 @@ static_assert(offsetof(ConvParams, S) == 64 && offsetof(ConvParams, x_bytes) == 
               "ConvParams: fields grouped by 64-byte line");
 
 
+// Brings the first four lines of the argument block into registers at once.  Left to itself the
+// compiler loads a field where it is first needed, which for a kernel that decodes its tile,
+// leaves early when it has none, and then sets up addresses makes three or four dependent round
+// trips to memory (the argument block is not cached from one launch to the next), each a few
+// hundred nanoseconds in front of the first transfer.  Call first thing in a kernel.
+__device__ __forceinline__ void fetch_params(const ConvParams &p) {
+    asm volatile("" ::"s"(p.x), "s"(p.w), "s"(p.b), "s"(p.y), "s"(p.res), "s"(p.N), "s"(p.C), "s"(p.H), "s"(p.W), "s"(p.K),
+                 "s"(p.R), "s"(p.S), "s"(p.stride), "s"(p.pad), "s"(p.relu), "s"(p.P), "s"(p.Q), "s"(p.M), "s"(p.Kg),
+                 "s"(p.ldy), "s"(p.y_off), "s"(p.ldx), "s"(p.k2), "s"(p.tiles_n), "s"(p.n_tiles), "s"(p.tiles_per_xcd),
+                 "s"(p.x_bytes), "s"(p.w_bytes), "s"(p.vec_store));
+    asm volatile("" ::"s"(p.d_pq.mul), "s"(p.d_pq.shift), "s"(p.d_q.mul), "s"(p.d_q.shift), "s"(p.d_tiles_n.mul),
+                 "s"(p.d_tiles_n.shift), "s"(p.d_c.mul), "s"(p.d_c.shift), "s"(p.d_s.mul), "s"(p.d_s.shift),
+                 "s"(p.d_p.mul), "s"(p.d_p.shift), "s"(p.tw), "s"(p.n_cb), "s"(p.d_tw.mul), "s"(p.d_tw.shift),
+                 "s"(p.d_ncb.mul), "s"(p.d_ncb.shift), "s"(p.d_pwt.mul), "s"(p.d_pwt.shift), "s"(p.d_hp.mul),
+                 "s"(p.d_hp.shift), "s"(p.th), "s"(p.tiles_img), "s"(p.tap_inner), "s"(p.split_k), "s"(p.sps));
+}
+
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
 // Rows are 128 bytes; XOR-ing the chunk index with bits 1..3 of the row spreads
 // 16 consecutive rows at one logical chunk over all 64 banks.

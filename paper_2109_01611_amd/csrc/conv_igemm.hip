@@ -109,6 +109,7 @@ __device__ __forceinline__ void conv_igemm_body(const ConvParams &p, const int b
     // input, which would otherwise be a launch of its own with nothing but fixed cost to it.
     // They are told apart inside the early exit that idle workgroups take anyway, so that a
     // workgroup with a tile does not wait for one more field of the argument block first.
+    fetch_params(p);
     const int item = tile_of_block(p, bid);
     if (item >= p.n_tiles * p.split_k || bid >= p.tiles_per_xcd * 8) {
         if (EXTRA && bid >= p.tiles_per_xcd * 8 && p.side_blocks > 0) {

@@ -61,9 +61,17 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     constexpr int MAIN = 2 * PATCH + NS * BSTAGE;
     constexpr int LDS_ELEMS = MAIN > BM * LDT * 2 ? MAIN : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 lds[LDS_ELEMS];
+    // Per patch position: byte offset in x of its first channel (block 0), or OOB, with the
+    // position's swizzle key in the three low bits.  Locating a position costs two divisions;
+    // the 256 consumer threads compute one position each while the producers already fetch
+    // weights, instead of every producer lane locating eight (which kept the first patch
+    // transfer waiting for 0.9 us on a 10 us kernel).
+    __shared__ unsigned ptab[PMAX];
+    static_assert(PMAX == NCONS * 64, "one table entry per consumer thread");
     __bf16 *const patch = lds;
     __bf16 *const wring = lds + 2 * PATCH;
 
+    fetch_params(p);
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
@@ -96,23 +104,6 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
         const i32x4 rx = make_rsrc(p.x, p.x_bytes);
         const i32x4 rw = make_rsrc(p.w, p.w_bytes);
 
-        // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8;
-        // this lane fills physical chunk lane&7 of one of them.
-        unsigned a_off[POPS];
-#pragma unroll
-        for (int j = 0; j < POPS; ++j) {
-            const int pos = (j * NPROD + pw) * 8 + (lane >> 3);
-            const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
-            const int cc = (lane & 7) ^ patch_key(pos, vr);
-            a_off[j] = OOB;
-            if (pos < npos) {
-                const int v = v0 + vr;
-                const int n = fdiv(v, p.d_hp);
-                const int h = v - n * Hp - p.pad, w = q0 + u - p.pad;
-                if (n < p.N && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
-                    a_off[j] = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C + cc * CHUNK) * 2);
-            }
-        }
         // Weight transfer i fills rows rg*8 .. +8 of tap s of the stage, q = i*NPROD + pw = s*RG + rg.
         unsigned b_off[BOPS];
 #pragma unroll
@@ -124,6 +115,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             b_off[i] = k < p.K ? static_cast<unsigned>(((k * 9 + s) * p.C + cc * CHUNK) * 2) : OOB;
         }
 
+        unsigned a_off[POPS];
         auto issue_patch = [&](int blk, int half) {
             const unsigned base = lds_addr(patch + (blk & 1) * PATCH) + pw * 1024;
             const unsigned add = static_cast<unsigned>(blk * BK * 2);
@@ -144,10 +136,19 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             }
         };
 
+        issue_weights(0, 0, 0);
+        __syncthreads();   // the consumers have filled the position table
+        // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8;
+        // this lane fills physical chunk lane&7 of one of them.
+#pragma unroll
+        for (int j = 0; j < POPS; ++j) {
+            const unsigned e = ptab[(j * NPROD + pw) * 8 + (lane >> 3)];
+            const unsigned cc = (lane & 7u) ^ (e & 7u);
+            a_off[j] = (e & OOB) ? OOB : (e & ~7u) + cc * (CHUNK * 2);
+        }
         issue_patch(0, 0);
         issue_patch(0, 1);
-        issue_weights(0, 0, 0);
-        issue_weights(0, 1, 1);
+        issue_weights(0, 1, 1);   // not needed by the first step: behind the patch
         for (int blk = 0; blk < nblk; ++blk) {
             // step 3*blk: its weights were followed by those of step 3*blk+1 only
             __builtin_amdgcn_s_waitcnt(vmcnt_imm(BOPS));
@@ -168,6 +169,21 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     } else {
         // ------------------------------------------------------------ consumer
         const int frow = lane & 31, fhalf = lane >> 5;
+        {
+            // this thread's entry of the position table
+            const int pos = wave * 64 + lane;
+            const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
+            unsigned e = OOB;
+            if (pos < npos) {
+                const int v = v0 + vr;
+                const int n = fdiv(v, p.d_hp);
+                const int h = v - n * Hp - p.pad, w = q0 + u - p.pad;
+                if (n < p.N && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+                    e = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C) * 2);
+            }
+            ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr));
+        }
+        __syncthreads();   // the table is complete (the producers wait here too)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll

@@ -147,6 +147,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     __bf16 *const wring = lds;
     __bf16 *const patch = lds + NS * WSTAGE;
 
+    fetch_params(p);
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
     // tile -> (image, tile row, tile column, filter tile); filter tiles of one pixel tile are neighbours
