@@ -144,6 +144,11 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     constexpr int MAIN = NS * WSTAGE + 2 * PATCH;
     constexpr int LDS_ELEMS = MAIN > BM * LDT * 2 ? MAIN : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 lds[LDS_ELEMS];
+    // Per patch position: byte offset in x of its first channel (block 0), or OOB, with the
+    // position's swizzle key in the three low bits; filled by the consumer threads (one position
+    // each) while the producers already fetch weights.
+    __shared__ unsigned ptab[PMAX];
+    static_assert(PMAX <= NCONS * 64, "one table entry per consumer thread");
     __bf16 *const wring = lds;
     __bf16 *const patch = lds + NS * WSTAGE;
 
@@ -172,21 +177,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
         const i32x4 rx = make_rsrc(p.x, p.x_bytes);
         const i32x4 rw = make_rsrc(p.w, p.w_bytes);
 
-        // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8; this lane
-        // fills physical chunk lane&7 of one of them.
         unsigned a_off[POPS];
-#pragma unroll
-        for (int j = 0; j < POPS; ++j) {
-            const int pos = (j * NPROD + pw) * 8 + (lane >> 3);
-            const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
-            const int cc = (lane & 7) ^ patch_key(pos, vr);
-            a_off[j] = OOB;
-            if (pos < npos) {
-                const int h = ty0 + vr - 1, w = tx0 + u - 1;
-                if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
-                    a_off[j] = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C + cc * CHUNK) * 2);
-            }
-        }
         // Weight transfer i fills rows (i*NPROD + pw)*8 .. +8 of the stage.
         unsigned b_off[WOPS];
 #pragma unroll
@@ -218,9 +209,18 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
             }
         };
 
-        issue_patch(0, 0, POPS);
         issue_weights(0, 0, 0);
         issue_weights(0, 1, 1);
+        __syncthreads();   // the consumers have filled the position table
+        // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8; this lane
+        // fills physical chunk lane&7 of one of them.
+#pragma unroll
+        for (int j = 0; j < POPS; ++j) {
+            const unsigned e = ptab[(j * NPROD + pw) * 8 + (lane >> 3)];
+            const unsigned cc = (lane & 7u) ^ (e & 7u);
+            a_off[j] = (e & OOB) ? OOB : (e & ~7u) + cc * (CHUNK * 2);
+        }
+        issue_patch(0, 0, POPS);
         issue_weights(0, 2, 2);
         int g = 0;
         for (int blk = 0; blk < nblk; ++blk) {
@@ -247,6 +247,21 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
         const int frow = lane & 31, fhalf = lane >> 5;
         const int fg = wave & 3, hi = wave >> 2;   // filter group; row tiles 0..3 or 4..6
         const int rt0 = hi * 4;
+        {
+            // this thread's entry of the position table
+            const int pos = wave * 64 + lane;
+            if (pos < PMAX) {
+                const int vr = fdiv(pos, p.d_pwt), u = pos - vr * pwt;
+                unsigned e = OOB;
+                if (pos < npos) {
+                    const int h = ty0 + vr - 1, w = tx0 + u - 1;
+                    if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
+                        e = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C) * 2);
+                }
+                ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr));
+            }
+        }
+        __syncthreads();   // the table is complete (the producers wait here too)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
