@@ -195,7 +195,7 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     const bool tall_ok = tall_eligible(p, vec, &th11, &tw11, &geo11);
     if (forced < 0 && tall_ok && p.C >= 2 * BK) {
         const long long tiles = tall_tiles(p, th11, tw11);
-        const double eff = 0.93 - 0.45 * (1.0 - geo11) - 0.1 / (p.C / BK);
+        const double eff = 0.93 - 0.45 * (1.0 - geo11) - 0.06 / (p.C / BK);
         const double cost = static_cast<double>((tiles + n_cu - 1) / n_cu) * 224 * 128 / eff;
         if (cost < best_cost) {
             best = 11;
@@ -207,10 +207,10 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     const bool patch_ok = patch_eligible(p, vec, &tw);
     if (best == 7 && !patch_ok) best = 1;  // the patch kernel does not apply: same tile shape, gathered
     // The patch kernel runs one workgroup per CU.  Measured on MI355X it beats the gathering
-    // tiles when all of its workgroups are resident at once (a second round doubles its time)
-    // and the depth is long enough (four or more channel blocks) to amortise loading the
-    // first patch.
-    if (forced < 0 && patch_ok && p.C >= 4 * BK) {
+    // tiles whenever all of its workgroups are resident at once (a second round doubles its
+    // time), from a single block of 64 channels on: 3x3 64 -> 64 on 56x56 at batch 8 5.5 against
+    // 6.2 us, 128 -> 256 on 14x14 at batch 32 6.9 against 7.8, 192 -> 384 on 7x7 7.9 against 10.0.
+    if (forced < 0 && patch_ok) {
         const int n_cb = (p.Q + tw - 1) / tw;
         const long long lin = 1LL * p.N * p.P * tw;
         const long long tiles = ((lin + PATCH_BM - 1) / PATCH_BM) * n_cb * ((p.K + 63) / 64);
