@@ -172,7 +172,8 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
             // 128x128 runs two workgroups per CU when there are more tiles than CUs (see the
             // launch below); the overlap of one's loads with the other's epilogue weighs more
             // the shorter the depth (measured against 256x128 at 9 .. 72 slices).
-            if (i == 0 && sk == 1 && tiles > n_cu) eff = std::min(1.2, 0.90 + 3.0 / nk);
+            // (filters larger than 1x1 gain less: 0.92-0.95 measured at 18 and 36 slices)
+            if (i == 0 && sk == 1 && tiles > n_cu) eff = std::min(1.2, 0.90 + (p.R * p.S == 1 ? 3.0 : 0.6) / nk);
             const double cost = static_cast<double>(per_cu) * t.bm * t.bn * share / eff;
             if ((o == 0 && sk == 1) || cost < best_cost) {
                 best = i;
@@ -188,14 +189,14 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     // The tall tile (224 pixels of one image x 128 filters, input patch in LDS) against the best
     // gathering tile, in the same units.  Its efficiency relative to 256x128, fitted to
     // measurements on MI355X (3x3 layers of 128..512 channels on 28..112 pixel maps at batch 16
-    // and 32): 0.93 when every tile row is a pixel and the depth is long, less the rows that are
+    // and 32): 0.95 when every tile row is a pixel and the depth is long, less the rows that are
     // not pixels and the first loads and the epilogue that a short depth does not amortise.
     int th11 = 0, tw11 = 0;
     double geo11 = 0.0;
     const bool tall_ok = tall_eligible(p, vec, &th11, &tw11, &geo11);
     if (forced < 0 && tall_ok && p.C >= 2 * BK) {
         const long long tiles = tall_tiles(p, th11, tw11);
-        const double eff = 0.93 - 0.45 * (1.0 - geo11) - 0.06 / (p.C / BK);
+        const double eff = 0.95 - 0.7 * (1.0 - geo11) - 0.04 / (p.C / BK);
         const double cost = static_cast<double>((tiles + n_cu - 1) / n_cu) * 224 * 128 / eff;
         if (cost < best_cost) {
             best = 11;

@@ -290,6 +290,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, const int wgs_per_col, const int tiles_m,
                                                           const int die_aware) {
+    fetch_params(p);
     constexpr int BM = PATCH_BM, BN = 64, NPROD = 4, PMAX = PATCH_PMAX, NB = 2;  // NB patch buffers
     constexpr int PATCH = PMAX * BK;           // elements per patch buffer
     constexpr int POPS = PMAX / 8 / NPROD;     // patch transfers per producer lane and tile

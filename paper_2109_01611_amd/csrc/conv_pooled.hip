@@ -31,6 +31,7 @@ constexpr int PC_BM = 32, PC_BN = 64;
 // slice, and the raw loads of slices j+1 and j+2 are in flight while slice j is multiplied.
 // Only two of the four wavefronts issue matrix instructions (32 x 32 each); all four load.
 __global__ __launch_bounds__(256) void pooled_conv1x1_kernel(const ConvParams p) {
+    fetch_params(p);
     constexpr int BM = PC_BM, BN = PC_BN, LDT = BN + 8;
     constexpr int STAGE = (BM + BN) * BK;  // elements per LDS stage: pixel rows, then filter rows
     constexpr int LDS_ELEMS = 2 * STAGE > BM * LDT * 2 ? 2 * STAGE : BM * LDT * 2;

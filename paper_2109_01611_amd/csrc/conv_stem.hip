@@ -53,6 +53,7 @@ constexpr int STEM_PXT = STEM_PX / 256;    // ... per thread
 template <int R, int KROW, int NT>
 __global__ __launch_bounds__(256) void conv_stem_kernel(const ConvParams p, const int wgs_per_col, const int tiles_m,
                                                         const int tiles_q, const int tiles_pq) {
+    fetch_params(p);
     constexpr int BN = NT * 32, KS = KROW / 16;
     constexpr int WELEMS = BN * R * KROW;  // padded weights, staged once on their way to registers
     constexpr int TROW = BN * 2 + 16;      // bytes per pixel row of the epilogue's transposition (padded)

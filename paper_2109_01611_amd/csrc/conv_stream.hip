@@ -38,6 +38,7 @@ constexpr int STREAM_BM = 64, STREAM_BN = 128;
 template <int NK>
 __global__ __launch_bounds__(12 * 64) void conv1x1_stream_kernel(const ConvParams p, const int wgs_per_col,
                                                                  const int tiles_m) {
+    fetch_params(p);
     constexpr int BM = STREAM_BM, BN = STREAM_BN, NCONS = 8, NPROD = 4, NA = 3;
     constexpr int CWN = 4, WM = 32, WN = 32;                 // consumers: 2 x 4 wavefronts of 32 x 32
     constexpr int PROWS = NPROD * 8;                          // 32 tile rows per round of producer instructions

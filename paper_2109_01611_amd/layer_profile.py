@@ -15,7 +15,8 @@ library chose, its duration, TFLOP/s, the fraction of the bf16 MFMA peak, and
         python3 /root/repo/paper_2109_01611_amd/layer_profile.py run --plan OUT2/plan.json
     python3 paper_2109_01611_amd/layer_profile.py parse OUT OUT2
 
-``run`` takes ``--models name:batch,...`` (default: the four ImageNet-size
+``load --shape N,C,H,W,K,R,stride,pad --data normal|relu|zeros --seconds S`` keeps one layer
+running so that clocks and power can be read meanwhile.  ``run`` takes ``--models name:batch,...`` (default: the four ImageNet-size
 models at their configurations' batch sizes plus the benchmark layer) and
 ``--shapes "N,C,H,W,K,R,stride,pad;..."`` for extra layers.  Inputs are dense
 N(0,1) values (no zeros), the most power-hungry case for the matrix pipelines;
@@ -109,6 +110,39 @@ def run(args):
     print("ran %d shapes x %d launches; plan written to %s" % (len(plan), args.reps, args.plan))
 
 
+def load(args):
+    """Keeps one layer running back to back for ``--seconds`` and prints its rate once a second, so
+    that the engine clock and power can be sampled from another shell while it runs
+    (``rocm-smi --showclocks --showpower``).  ``--data zeros`` runs the same instructions on
+    all-zero operands: the matrix pipelines then draw far less power and the clock stays up."""
+    import time
+    import torch
+    from paper_2109_01611_amd import gpulet
+    dev = torch.device("cuda:0")
+    N, C, H, W, K, R, stride, pad = (int(v) for v in args.shape.split(","))
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    gen = torch.Generator(device=dev).manual_seed(0)
+    x = torch.randn((N, H, W, C), device=dev, generator=gen).to(torch.bfloat16)
+    w = (torch.randn((K, R, R, C), device=dev, generator=gen) * (2.0 / (C * R * R)) ** 0.5).to(torch.bfloat16)
+    if args.data == "zeros":
+        x.zero_()
+        w.zero_()
+    elif args.data == "relu":
+        x = torch.relu(x)
+    b = torch.zeros(K, device=dev)
+    y = torch.empty((N, P, Q, K), dtype=torch.bfloat16, device=dev)
+    flop = 2.0 * N * P * Q * K * C * R * R
+    torch.cuda.synchronize()
+    with gpulet.Partition(0, 100, 0) as part:
+        t_end = time.perf_counter() + args.seconds
+        iters = max(50, int(2e11 / flop))
+        while time.perf_counter() < t_end:
+            ms = gpulet.time_conv2d(x, w, b, y, N, C, H, W, K, R, R, stride, pad, True, stream=part.stream, warmup=0,
+                                    iters=iters)
+            print("%s data: %.2f us per launch, %.0f TFLOP/s" % (args.data, ms * 1e3, flop / ms / 1e9), flush=True)
+            iters = max(50, int(1000.0 / ms))
+
+
 def _conv_dispatches(path, want):
     """Rows of a profiler csv that are convolution kernels of this library, in dispatch order."""
     rows = [r for r in csv.DictReader(open(path)) if "gpulet::conv::" in r["Kernel_Name"] and want(r)]
@@ -172,12 +206,18 @@ def main():
     r.add_argument("--models", default=DEFAULT_MODELS)
     r.add_argument("--shapes", default="")
     r.add_argument("--reps", type=int, default=20)
+    l = sub.add_parser("load")
+    l.add_argument("--shape", default="16,512,28,28,512,3,1,1", help="N,C,H,W,K,R,stride,pad")
+    l.add_argument("--data", default="normal", choices=["normal", "relu", "zeros"])
+    l.add_argument("--seconds", type=float, default=5.0)
     p = sub.add_parser("parse")
     p.add_argument("trace_dir")
     p.add_argument("pmc_dir", nargs="?")
     args = ap.parse_args()
     if args.cmd == "run":
         run(args)
+    elif args.cmd == "load":
+        load(args)
     else:
         parse(args.trace_dir, args.pmc_dir)
 
