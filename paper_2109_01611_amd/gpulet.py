@@ -24,6 +24,7 @@ LIB_PATH = os.path.join(_HERE, "libgpulet.so")
 OK, EINVAL, EOVERSUB, EHIP, ENOMEM = 0, -1, -2, -3, -4
 POOL_MAX, POOL_AVG, POOL_GLOBAL_AVG = 0, 1, 2
 OP_CONV, OP_POOL, OP_FC, OP_DWCONV = 0, 1, 2, 3
+CONV_TILES = 14  # GPULET_CONV_TILES: set_conv_tile takes -1 .. CONV_TILES - 1
 
 
 class GpuletError(RuntimeError):

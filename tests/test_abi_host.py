@@ -291,3 +291,10 @@ def test_model_description_errors():
     # residual of the wrong shape
     bad([_layer(op=gpulet.OP_CONV, in_buf=0, out_buf=2, C=3, K=8, R=3, S=3, stride=2, pad=1, w=W),
          _layer(op=gpulet.OP_CONV, in_buf=0, out_buf=1, C=3, K=8, R=3, S=3, stride=1, pad=1, w=W, res_buf=2)])
+
+
+def test_binding_mirrors_the_header_tile_count():
+    import re
+    header = open(os.path.join(os.path.dirname(__file__), "..", "include", "gpulet.h")).read()
+    m = re.search(r"enum\s*\{\s*GPULET_CONV_TILES\s*=\s*(\d+)\s*\}", header)
+    assert m and int(m.group(1)) == gpulet.CONV_TILES

@@ -49,7 +49,7 @@ def test_conv_parity_every_tile(part, case):
     ref = oracle.conv2d(x, w, b, stride, pad, relu=True)
     mag = conv_mag(x, w, b, stride, pad)
     first = None
-    for tile in range(-1, 14):
+    for tile in range(-1, gpulet.CONV_TILES):
         got, raw = gpu_conv(part, x, w, b, stride, pad, True, tile=tile)
         assert_close(got, ref, mag, what=tile)
         if tile < 0 or (tile == 9 and C <= 4):
@@ -197,7 +197,7 @@ def test_conv_reading_a_channel_slice(part, case):
     wd = lowering.kcrs_to_krsc(w, DEV)
     bd = torch.from_numpy(b).to(DEV)
     ct, co = K + 16, 8
-    for tile in range(-1, 14):
+    for tile in range(-1, gpulet.CONV_TILES):
         yd = torch.full((N, P, Q, ct), -512.0, dtype=torch.bfloat16, device=DEV)
         torch.cuda.synchronize()
         gpulet.set_conv_tile(tile)
@@ -253,7 +253,7 @@ def test_1x1_conv_with_two_outputs(part, case):
     xd = lowering.nchw_to_nhwc(wide, DEV)
     wd = lowering.kcrs_to_krsc(w, DEV)
     bd = torch.from_numpy(b).to(DEV)
-    for tile in range(-1, 14):
+    for tile in range(-1, gpulet.CONV_TILES):
         y1 = torch.full((N, P, Q, ldy or k2), -512.0, dtype=torch.bfloat16, device=DEV)
         y2 = torch.full((N, P, Q, ldy2 or K - k2), -512.0, dtype=torch.bfloat16, device=DEV)
         torch.cuda.synchronize()
@@ -310,7 +310,7 @@ def test_1x1_conv_carrying_the_max_pool_of_its_input(part, case):
     xd = lowering.nchw_to_nhwc(x, DEV)
     wd = lowering.kcrs_to_krsc(w, DEV)
     bd = torch.from_numpy(b).to(DEV)
-    for tile in range(-1, 14):
+    for tile in range(-1, gpulet.CONV_TILES):
         y1 = torch.full((N, H, W, k2 or K), -512.0, dtype=torch.bfloat16, device=DEV)
         y2 = torch.full((N, H, W, K - k2), -512.0, dtype=torch.bfloat16, device=DEV) if k2 else None
         pool = torch.full((N, H, W, C), -512.0, dtype=torch.bfloat16, device=DEV)
@@ -391,7 +391,7 @@ def test_independent_convs_in_one_launch(part, case):
                           x_ch_stride=wide_c, x_ch_offset=xo))
         outs.append((P, Q, K, off))
         off += K
-    for tile in range(-1, 14):
+    for tile in range(-1, gpulet.CONV_TILES):
         if same_size:       # slices of one concatenated tensor
             cat = torch.full((N, outs[0][0], outs[0][1], total), -512.0, dtype=torch.bfloat16, device=DEV)
             ys = [cat] * len(members)
