@@ -141,6 +141,22 @@ gpulet_status gpulet_partition_sync(gpulet_partition *p);
  */
 gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_blocks);
 
+/*
+ * Measurement aid for the roofline of the convolution kernels (the matrix-core
+ * utilisation asked of the per-partition profile, paper Sec. 3.1): runs one
+ * workgroup of waves_per_cu (4 or 8) wavefronts per CU of the gpu-let, each
+ * issuing 64 * iters 32x32x16 bf16 matrix instructions on register operands and
+ * nothing else, `launches` times back to back between one event pair (after
+ * one untimed launch).  dense != 0: pseudo-random operands in (-1, 1);
+ * dense == 0: all-zero operands.  *avg_ms = milliseconds per launch,
+ * *tflops = the rate.  The difference between the two patterns is the engine
+ * clock the power limit allows.  Uses the gpu-let's scratch for the kernel's
+ * (meaningless) output.  Synchronises.  GPULET_EINVAL for other wave counts or
+ * counts below 1.
+ */
+gpulet_status gpulet_partition_mfma_rate(gpulet_partition *p, int dense, int waves_per_cu, int iters,
+                                         int launches, float *avg_ms, double *tflops);
+
 /* The same probe, launched through a captured HIP graph when via_graph != 0:
  * checks that graph replays on a gpu-let's stream honour its CU mask too. */
 gpulet_status gpulet_partition_probe_ex(gpulet_partition *p, uint32_t *out, int n_blocks,

@@ -116,6 +116,9 @@ hipError_t launch_fc_static(const void *x, const void *w, const float *b, void *
 hipError_t launch_dwconv(const void *x, const void *w, const float *b, void *y, int N, int C, int H, int W,
                          int R, int S, int stride, int pad, int relu, int P, int Q, hipStream_t stream);
 hipError_t launch_probe(uint32_t *out, int n_blocks, hipStream_t stream);
+// blocks x waves wavefronts of nothing but 32x32x16 bf16 matrix instructions, 64 * iters each; out: one float
+// per thread.  dense: pseudo-random operands in (-1, 1) instead of zeros.
+hipError_t launch_mfma_rate(float *out, int blocks, int waves, int iters, int dense, hipStream_t stream);
 
 // Argument checks shared by the single-layer entry points and the model runner.
 gpulet_status check_conv(const ConvArgs &a);

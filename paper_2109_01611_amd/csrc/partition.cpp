@@ -266,6 +266,37 @@ extern "C" gpulet_status gpulet_partition_probe_ex(gpulet_partition *p, uint32_t
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_partition_mfma_rate(gpulet_partition *p, int dense, int waves_per_cu, int iters,
+                                                    int launches, float *avg_ms, double *tflops) {
+    if (!live(p) || !avg_ms || !tflops || iters < 1 || launches < 1) return GPULET_EINVAL;
+    if (waves_per_cu != 4 && waves_per_cu != 8) return GPULET_EINVAL;
+    const int blocks = p->n_cu;
+    if (static_cast<size_t>(blocks) * waves_per_cu * 64 * sizeof(float) > p->scratch_bytes) return GPULET_ENOMEM;
+    float *out = static_cast<float *>(p->scratch);
+    GPULET_HIP(launch_mfma_rate(out, blocks, waves_per_cu, iters, dense, p->stream));  // warm-up
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    GPULET_HIP(hipEventCreate(&e0));
+    hipError_t e = hipEventCreate(&e1);
+    if (e != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return hip_fail(e);
+    }
+    e = hipEventRecord(e0, p->stream);
+    for (int i = 0; i < launches && e == hipSuccess; ++i)
+        e = launch_mfma_rate(out, blocks, waves_per_cu, iters, dense, p->stream);
+    if (e == hipSuccess) e = hipEventRecord(e1, p->stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(e);
+    *avg_ms = ms / static_cast<float>(launches);
+    const double flop = 2.0 * 32 * 32 * 16 * 64.0 * iters * waves_per_cu * blocks;  // per launch
+    *tflops = flop / (static_cast<double>(*avg_ms) * 1e-3) * 1e-12;
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_partition_probe(gpulet_partition *p, uint32_t *out, int n_blocks) {
     return gpulet_partition_probe_ex(p, out, n_blocks, 0);
 }

@@ -98,6 +98,7 @@ def _load():
         "gpulet_partition_sync": ([P], c_int32),
         "gpulet_partition_probe": ([P, P, I], c_int32),
         "gpulet_partition_probe_ex": ([P, P, I, I], c_int32),
+        "gpulet_partition_mfma_rate": ([P, I, I, I, I, FP, DP], c_int32),
         "gpulet_model_graph_create": ([POINTER(ModelDesc), I, P, P, P, P, c_size_t, POINTER(P)], c_int32),
         "gpulet_model_graph_launch": ([P, FP], c_int32),
         "gpulet_model_graph_profile": ([P, I, I, FP, FP], c_int32),
@@ -217,6 +218,13 @@ class Partition:
     def probe(self, out, n_blocks, via_graph=False):
         _check(lib.gpulet_partition_probe_ex(self.handle, ptr(out), n_blocks, int(via_graph)),
                "gpulet_partition_probe_ex")
+
+    def mfma_rate(self, dense, waves_per_cu=8, iters=2000, launches=20):
+        """(milliseconds per launch, TFLOP/s) of the matrix-instruction-only probe on this gpu-let."""
+        ms, tf = c_float(), c_double()
+        _check(lib.gpulet_partition_mfma_rate(self.handle, int(bool(dense)), waves_per_cu, iters, launches,
+                                              ctypes.byref(ms), ctypes.byref(tf)), "gpulet_partition_mfma_rate")
+        return ms.value, tf.value
 
     def destroy(self):
         if self.handle is not None:

@@ -16,7 +16,9 @@ library chose, its duration, TFLOP/s, the fraction of the bf16 MFMA peak, and
     python3 paper_2109_01611_amd/layer_profile.py parse OUT OUT2
 
 ``load --shape N,C,H,W,K,R,stride,pad --data normal|relu|zeros --seconds S`` keeps one layer
-running so that clocks and power can be read meanwhile.  ``run`` takes ``--models name:batch,...`` (default: the four ImageNet-size
+running so that clocks and power can be read meanwhile; ``mfma --data both|dense|zeros --waves 4|8 --seconds S``
+does the same with a probe that issues matrix instructions on register operands and nothing else (the ceiling of
+the matrix pipelines for an operand pattern).  ``run`` takes ``--models name:batch,...`` (default: the four ImageNet-size
 models at their configurations' batch sizes plus the benchmark layer) and
 ``--shapes "N,C,H,W,K,R,stride,pad;..."`` for extra layers.  Inputs are dense
 N(0,1) values (no zeros), the most power-hungry case for the matrix pipelines;
@@ -143,6 +145,22 @@ def load(args):
             iters = max(50, int(1000.0 / ms))
 
 
+def mfma(args):
+    """Runs the matrix-instruction-only probe (no memory traffic at all) for ``--seconds`` per operand
+    pattern and prints its rate once a second: the ceiling of any kernel's matrix throughput at the
+    clock the power limit allows for that pattern."""
+    import time
+    import torch  # noqa: F401  (the binding needs torch's HIP runtime loaded first)
+    from paper_2109_01611_amd import gpulet
+    with gpulet.Partition(0, 100, 0) as part:
+        for dense in ([1] if args.data == "dense" else [0] if args.data == "zeros" else [0, 1]):
+            t_end = time.perf_counter() + args.seconds
+            while time.perf_counter() < t_end:
+                ms, tf = part.mfma_rate(dense, waves_per_cu=args.waves, iters=4000, launches=400)
+                print("%s operands, %d wavefronts per CU: %.1f us per launch, %.0f TFLOP/s (%.3f of 2500)"
+                      % ("dense" if dense else "zero", args.waves, ms * 1e3, tf, tf / PEAK_TFLOPS), flush=True)
+
+
 def _conv_dispatches(path, want):
     """Rows of a profiler csv that are convolution kernels of this library, in dispatch order."""
     rows = [r for r in csv.DictReader(open(path)) if "gpulet::conv::" in r["Kernel_Name"] and want(r)]
@@ -206,6 +224,10 @@ def main():
     r.add_argument("--models", default=DEFAULT_MODELS)
     r.add_argument("--shapes", default="")
     r.add_argument("--reps", type=int, default=20)
+    m = sub.add_parser("mfma")
+    m.add_argument("--data", default="both", choices=["both", "dense", "zeros"])
+    m.add_argument("--waves", type=int, default=8, choices=[4, 8])
+    m.add_argument("--seconds", type=float, default=3.0)
     l = sub.add_parser("load")
     l.add_argument("--shape", default="16,512,28,28,512,3,1,1", help="N,C,H,W,K,R,stride,pad")
     l.add_argument("--data", default="normal", choices=["normal", "relu", "zeros"])
@@ -218,6 +240,8 @@ def main():
         run(args)
     elif args.cmd == "load":
         load(args)
+    elif args.cmd == "mfma":
+        mfma(args)
     else:
         parse(args.trace_dir, args.pmc_dir)
 

@@ -105,3 +105,22 @@ def test_request_counters_are_exact():
             gpulet.run_model(dm.desc, 4, p, x, y, ws, n - 1)
         assert e.value.status == gpulet.ENOMEM
         assert p.counters() == (17, total + 52)
+
+
+def test_mfma_rate_probe_scales_with_the_gpulet_and_checks_its_arguments():
+    # The matrix-instruction-only probe: a rate below the 2.5 PFLOP/s peak, about half of it on half
+    # of the CUs, and no faster on dense operands than on zeros (the power limit works the other way).
+    with gpulet.Partition(0, 100, 0) as p:
+        p.mfma_rate(0, iters=500, launches=20)                   # clocks up
+        _, full_zero = p.mfma_rate(0, iters=500, launches=40)
+        _, full_dense = p.mfma_rate(1, iters=500, launches=40)
+        for bad in ((0, 3, 10, 1), (0, 8, 0, 1), (0, 8, 10, 0)):
+            ms, tf = gpulet.c_float(), gpulet.c_double()
+            assert gpulet.lib.gpulet_partition_mfma_rate(p.handle, *bad, gpulet.byref(ms), gpulet.byref(tf)) == gpulet.EINVAL
+    with gpulet.Partition(0, 50, 0) as p:
+        p.mfma_rate(0, iters=500, launches=20)
+        _, half_zero = p.mfma_rate(0, iters=500, launches=40)
+    print("mfma probe: %.0f TFLOP/s zeros, %.0f dense, %.0f zeros on 128 CUs" % (full_zero, full_dense, half_zero), flush=True)
+    assert 1000.0 < full_zero < 2600.0
+    assert 500.0 < full_dense <= 1.02 * full_zero
+    assert 0.4 * full_zero < half_zero < 0.6 * full_zero
