@@ -270,6 +270,36 @@ gpulet_status gpulet_conv1x1_maxpool3_fwd(const void *x, const void *w, const fl
                                           int y2_ch_offset, void *stream);
 
 /*
+ * A 3x3 / stride 1 / pad 1 convolution with ReLU and the 2x2 / stride 2 max pool
+ * behind it (the end of every VGG-16 group, Table 4) in one kernel:
+ *   y = maxpool2x2(relu(b + conv3x3(x, w)))
+ * The layer's own output is never written: the kernel's epilogue takes the
+ * maximum of each 2x2 window of a tile's fp32 sums, then adds the bias, applies
+ * the ReLU and rounds once (rounding and ReLU do not decrease, so the result
+ * has the bits of gpulet_conv2d_fwd_ex followed by gpulet_pool).  x: N*H*W*C
+ * bf16, w: K*3*3*C bf16, b: K fp32 or NULL, y: N*(H/2)*(W/2) pixels of
+ * y_ch_stride channels (0 = K), filter k stored at channel y_ch_offset + k.
+ * Device pointers owned by the caller; asynchronous on `stream`.
+ * GPULET_EINVAL unless H and W are even, C is a multiple of 64, K, y_ch_stride
+ * and y_ch_offset are multiples of 8 and x, w, b, y are 16-byte aligned; other
+ * errors as gpulet_conv2d_fwd_ex.
+ */
+gpulet_status gpulet_conv3x3_maxpool2_fwd(const void *x, const void *w, const float *b, void *y, int N, int C,
+                                          int H, int W, int K, int y_ch_stride, int y_ch_offset, void *stream);
+
+/*
+ * Whether gpulet_run_model and its relatives (profile, co-run, graph capture) may
+ * run a convolution and the 2x2 / stride 2 max pool that follows it as one launch
+ * (1, the default) or always as two kernels (0).  When allowed, a pair is fused
+ * per launch if the pool is the only reader of the layer's output, the layer
+ * qualifies for gpulet_conv3x3_maxpool2_fwd with at least 128 input channels and
+ * the kernel with the pooled epilogue costs the layer at most 15 % more than
+ * the kernel it would run otherwise; the layer's own output buffer is then left
+ * unwritten.  Results are bit-identical either way.  Process-wide.
+ */
+gpulet_status gpulet_set_conv_pool_fusion(int on);
+
+/*
  * Pooling branch of an inception block (GoogLeNet of Table 4) in one kernel:
  *   y = act(b + conv1x1(maxpool(x, window 3x3, stride 1, pad 1), w))
  * with the pool's maximum taken over in-image taps only, as in gpulet_pool.

@@ -18,6 +18,7 @@ namespace {
 // Off by default: the partial tiles cross dies through memory, which costs about 8 us per
 // launch on MI355X and only pays for layers with very few tiles and a very long depth.
 std::atomic<int> g_max_split_k{1};
+std::atomic<int> g_pool_fusion{1};
 
 std::atomic<int> g_tile_override{-1};
 
@@ -56,6 +57,8 @@ gpulet_status check_conv(const ConvArgs &a) {
     if (a.pool_y && (a.R != 1 || a.S != 1 || a.pad != 0 || a.pre_pool || a.C % 8 != 0 ||
                      (a.x_ch_stride != 0 && a.x_ch_stride != a.C)))
         return GPULET_EINVAL;
+    if (a.post_pool2 != 0 && (a.post_pool2 != 2 || a.P % 2 != 0 || a.Q % 2 != 0 || a.residual || a.y2 || a.pool_y || a.pre_pool))
+        return GPULET_EINVAL;
     if (a.pre_pool != 0 && (a.pre_pool != 3 || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % 8 != 0))
         return GPULET_EINVAL;
     const int ldx = a.x_ch_stride ? a.x_ch_stride : a.C;
@@ -93,6 +96,7 @@ hipError_t make_params(const ConvArgs &a, const LaunchCtx &ctx, ConvParams &p, b
     p.k2 = a.y2 ? a.k2 : a.K;
     p.ldy2 = a.y2_ch_stride;
     p.y2_off = a.y2_ch_offset;
+    p.pool2 = p.pad4 = 0;
     p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
     // up to the last channel the layer reads of the last pixel
     p.x_bytes = static_cast<unsigned>(2LL * ((1LL * a.N * a.H * a.W - 1) * p.ldx + a.C));
@@ -141,6 +145,7 @@ hipError_t make_params(const ConvArgs &a, const LaunchCtx &ctx, ConvParams &p, b
 // resident-weight kernel (column block `tw64`).
 struct Choice {
     int best, split, tw, tw64, th11, tw11;
+    double cost;   // of `best` in the cost model's units when it is a gathering tile or the tall tile, else 0
 };
 
 Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
@@ -241,7 +246,7 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     if (best == 9 && !stem_applicable(p)) best = 1;
     if (forced < 0 && stem_applicable(p)) best = 9;  // by shape alone: the same bits in every batch and gpu-let
     if (best == 11 && !tall_ok) best = 1;
-    return Choice{best, best_split, tw, tw64, th11, tw11};
+    return Choice{best, best_split, tw, tw64, th11, tw11, (is_gathering_tile(best) || best == 11) ? best_cost : 0.0};
 }
 
 }  // namespace
@@ -258,10 +263,16 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
         return launch_pooled_conv(p, stream);
     }
 
+    if (a.post_pool2) {
+        int th = 0, tw = 0;
+        double geo = 0.0;
+        if (a.post_pool2 != 2 || a.y2 || a.pool_y || !tall_eligible(p, vec, &th, &tw, &geo, true)) return hipErrorInvalidValue;
+        return launch_tall(p, th, tw, true, stream);
+    }
     const Choice c = choose_kernel(p, vec, ctx);
     const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
     switch (c.best) {
-        case 11: return launch_tall(p, c.th11, c.tw11, stream);
+        case 11: return launch_tall(p, c.th11, c.tw11, false, stream);
         case 10: return launch_c64(p, c.tw64, n_cu, stream);
         case 9: return launch_stem(p, n_cu, stream);
         case 8: return launch_stream(p, n_cu, stream);
@@ -271,6 +282,27 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
             return launch_igemm(p, vec, c.best, c.split, tiles128 > n_cu, stream);
         }
     }
+}
+
+// The pooled epilogue saves the layer's full-size store and the pool kernel's pass over it (at
+// least a sixth of the pair's time on the layers it applies to), so the tall tile may cost up to
+// 15 % more than the kernel the layer would get by itself.  Layers that a specialised kernel takes
+// (all workgroups of the patch kernel resident, 64 input channels) keep it and their pool kernel.
+bool conv_pool2_fusable(const ConvArgs &a, const LaunchCtx &ctx) {
+    if (!g_pool_fusion.load() || g_tile_override.load() >= 0) return false;
+    if (a.pre_pool || a.y2 || a.pool_y || a.residual || !a.relu) return false;
+    ConvParams p;
+    bool vec = false;
+    if (make_params(a, ctx, p, vec) != hipSuccess) return false;
+    int th = 0, tw = 0;
+    double geo = 0.0;
+    if (p.C < 2 * BK || !tall_eligible(p, vec, &th, &tw, &geo, true)) return false;
+    const Choice c = choose_kernel(p, vec, ctx);
+    if (c.cost <= 0.0) return false;
+    const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
+    const double eff = 0.95 - 0.7 * (1.0 - geo) - 0.04 / (p.C / BK);
+    const double cost = static_cast<double>((tall_tiles(p, th, tw) + n_cu - 1) / n_cu) * 224 * 128 / eff;
+    return cost <= 1.15 * c.cost;
 }
 
 // Independent layers in one launch.  Every member must be a layer the gathering kernel would
@@ -327,6 +359,8 @@ hipError_t launch_conv_group(const ConvArgs *a, int n, const LaunchCtx &ctx, hip
 }
 
 void set_conv_split_k(int max_split) { g_max_split_k.store(max_split); }
+
+void set_conv_pool_fusion(int on) { g_pool_fusion.store(on ? 1 : 0); }
 
 void set_conv_tile(int tile) { g_tile_override.store(tile); }
 

@@ -70,6 +70,9 @@ struct alignas(64) ConvParams {
     // y2[m * ldy2 + y2_off + k - k2] instead.
     __bf16 *y2;
     int ldy2, y2_off;
+    // Tall-tile kernel only: 2 = a 2x2 / stride 2 max pool follows the layer and only the pooled
+    // tensor (N, P/2, Q/2 pixels of ldy channels) is stored to y; 0 = the layer's own output.
+    int pool2, pad4;
     // Side job (1x1 gathering kernels only): the side_blocks extra workgroups compute the
     // 3x3 / stride 1 / pad 1 max pool side_pool of the layer's (dense) input.
     PoolParams side_pool;
@@ -300,9 +303,9 @@ hipError_t launch_c64(ConvParams p, int tw, int n_cu, hipStream_t stream);
 
 // conv_tall.hip: tile 11 (3x3, 224 x 128 tile, input patch in LDS, one tap per ring step).
 // `eff` receives the share of tile rows that are pixels for the chosen rectangle th x tw.
-bool tall_eligible(const ConvParams &p, bool vec, int *th, int *tw, double *eff);
+bool tall_eligible(const ConvParams &p, bool vec, int *th, int *tw, double *eff, bool pool2 = false);
 long long tall_tiles(const ConvParams &p, int th, int tw);
-hipError_t launch_tall(ConvParams p, int th, int tw, hipStream_t stream);
+hipError_t launch_tall(ConvParams p, int th, int tw, bool pool2, hipStream_t stream);
 
 // conv_stream.hip: tile 8 (streaming 1x1).
 bool stream_applicable(const ConvParams &p, bool vec);

@@ -132,6 +132,48 @@ __device__ __forceinline__ void tall_consume(const __bf16 *lds, const unsigned (
     }
 }
 
+// Epilogue of a tile whose layer is followed by a 2x2 / stride 2 max pool: the fp32 tile parked in
+// LDS (rows = the th x tw pixels of the tile, th, tw and the tile's origin even) is reduced over
+// each 2x2 window, then bias, ReLU and the rounding to bf16 are applied once and only the pooled
+// pixel is stored.  x -> round(relu(x + bias)) does not decrease, so the maximum can be taken
+// first: the bits equal those of the layer's output pooled by the pool kernel.
+template <int BN, int NTHR>
+__device__ __forceinline__ void finish_tile_pool2(const ConvParams &p, const float *stg, int n0, const BiasRegs &br,
+                                                  int n, int ty0, int tx0) {
+    constexpr int LDT = BN + 8, VPR = BN / 8, PSTEP = NTHR / VPR;
+    const int cv = threadIdx.x % VPR, k = n0 + cv * 8;
+    if (k >= p.K) return;
+    const float bias[8] = {br.lo.x, br.lo.y, br.lo.z, br.lo.w, br.hi.x, br.hi.y, br.hi.z, br.hi.w};
+    const unsigned limit = relu_limit(p.relu);
+    const int tw2 = p.tw >> 1, n_pooled = (p.th >> 1) * tw2;
+    const int P2 = p.P >> 1, Q2 = p.Q >> 1;
+    __bf16 *yb = p.y + p.y_off + k;
+    for (int pi = threadIdx.x / VPR; pi < n_pooled; pi += PSTEP) {
+        const int py = pi / tw2, px = pi - py * tw2;
+        const int hh = ty0 + 2 * py, ww = tx0 + 2 * px;     // top left pixel of the window
+        if (hh >= p.P || ww >= p.Q) continue;               // P, Q, hh, ww even: the window is inside or outside as a whole
+        const int row = 2 * py * p.tw + 2 * px;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = -__builtin_inff();
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float *src = &stg[(row + (t >> 1) * p.tw + (t & 1)) * LDT + cv * 8];
+            const float4 lo = *reinterpret_cast<const float4 *>(src);
+            const float4 hi = *reinterpret_cast<const float4 *>(src + 4);
+            const float u[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = u[e] > v[e] ? u[e] : v[e];
+        }
+        unsigned pk[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            pk[e] = relu_or_pass(pack_bf16(v[2 * e] + bias[2 * e], v[2 * e + 1] + bias[2 * e + 1]), limit);
+        const int m = (n * P2 + (hh >> 1)) * Q2 + (ww >> 1);
+        *reinterpret_cast<uint4 *>(yb + m * p.ldy) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    }
+}
+
 __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     constexpr int BM = TALL_BM, BN = TALL_BN, NCONS = 8, NPROD = 4, NS = 4, PMAX = TALL_PMAX;
     constexpr int WSTAGE = BN * BK;                // elements per weight stage: one tap
@@ -153,6 +195,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     __bf16 *const patch = lds + NS * WSTAGE;
 
     fetch_params(p);
+    asm volatile("" ::"s"(p.pool2));   // requested with the rest of the argument block
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
     // tile -> (image, tile row, tile column, filter tile); filter tiles of one pixel tile are neighbours
@@ -306,6 +349,10 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
         }
     }
     __syncthreads();
+    if (p.pool2) {
+        finish_tile_pool2<BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, n, ty0, tx0);
+        return;
+    }
     finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, [&](int row) {
         if (row >= npix) return -1;
         const int ty = fdiv(row, p.d_tw), tx = row - ty * p.tw;
@@ -316,12 +363,13 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
 
 // The pixel rectangle th x tw (th*tw <= 224, patch within TALL_PMAX positions) that wastes the
 // fewest tile rows on a P x Q map; on a tie the wider one (longer contiguous runs per transfer).
-bool tall_geometry(int P, int Q, int *th_out, int *tw_out, double *eff_out) {
+bool tall_geometry(int P, int Q, bool even, int *th_out, int *tw_out, double *eff_out) {
     double best = 0.0;
     int bth = 0, btw = 0;
-    for (int tw = 1; tw <= std::min(Q, TALL_BM); ++tw) {
+    const int step = even ? 2 : 1;     // tiles of whole 2x2 windows for a fused pool
+    for (int tw = step; tw <= std::min(Q, TALL_BM); tw += step) {
         const int th_max = std::min(P, TALL_BM / tw);
-        for (int th = 1; th <= th_max; ++th) {
+        for (int th = step; th <= th_max; th += step) {
             if ((th + 2) * (tw + 2) > TALL_PMAX) break;
             const long long tiles = 1LL * ((P + th - 1) / th) * ((Q + tw - 1) / tw);
             const double eff = static_cast<double>(P) * Q / (static_cast<double>(tiles) * TALL_BM);
@@ -341,16 +389,19 @@ bool tall_geometry(int P, int Q, int *th_out, int *tw_out, double *eff_out) {
 
 }  // namespace
 
-bool tall_eligible(const ConvParams &p, bool vec, int *th, int *tw, double *eff) {
+bool tall_eligible(const ConvParams &p, bool vec, int *th, int *tw, double *eff, bool pool2) {
+    if (pool2 && (p.P % 2 != 0 || p.Q % 2 != 0 || p.res || !p.relu || !p.vec_store || p.K % 8 != 0)) return false;
     return vec && p.ldx == p.C && p.R == 3 && p.S == 3 && p.stride == 1 && p.pad == 1 && p.C % BK == 0 && p.P == p.H &&
-           p.Q == p.W && tall_geometry(p.P, p.Q, th, tw, eff);
+           p.Q == p.W && tall_geometry(p.P, p.Q, pool2, th, tw, eff);
 }
 
 long long tall_tiles(const ConvParams &p, int th, int tw) {
     return 1LL * p.N * ((p.P + th - 1) / th) * ((p.Q + tw - 1) / tw) * ((p.K + TALL_BN - 1) / TALL_BN);
 }
 
-hipError_t launch_tall(ConvParams p, int th, int tw, hipStream_t stream) {
+hipError_t launch_tall(ConvParams p, int th, int tw, bool pool2, hipStream_t stream) {
+    if (pool2 && (th % 2 != 0 || tw % 2 != 0)) return hipErrorInvalidValue;
+    p.pool2 = pool2 ? 2 : 0;
     p.th = th;
     p.tw = tw;
     p.n_cb = (p.Q + tw - 1) / tw;                       // tiles per tile row

@@ -96,8 +96,19 @@ struct ConvArgs {
     // Side job (1x1 filters, dense input, C % 8 == 0): when set, the launch also writes the
     // 3x3 / stride 1 / pad 1 max pool of x (N*H*W*C bf16) to pool_y.
     void *pool_y = nullptr;
+    // 2: a 2x2 / stride 2 max pool follows and y receives only the pooled tensor (N, P/2, Q/2 pixels
+    // of y_ch_stride channels); P and Q stay the layer's own output size.  Only layers for which
+    // conv_pool2_fusable() holds.
+    int post_pool2 = 0;
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
+// Whether the layer followed by a 2x2 / stride 2 max pool should run as one launch on this
+// stream: a kernel that can pool in its epilogue applies (3x3, stride 1, pad 1, ReLU, no residual,
+// C a multiple of 64 from 128 on, even output size, aligned dense operands) and is at most a few
+// percent slower on the layer alone than the kernel that would run it otherwise.  `a.y` is the
+// pooled destination.
+bool conv_pool2_fusable(const ConvArgs &a, const LaunchCtx &ctx);
+void set_conv_pool_fusion(int on);
 // n independent layers (no member reads or overwrites what another writes), in one launch where
 // the kernels allow it.
 // *launches (if not null) receives the number of kernel launches made: 1 or n.

@@ -155,6 +155,29 @@ extern "C" gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *
     return GPULET_OK;
 }
 
+extern "C" gpulet_status gpulet_conv3x3_maxpool2_fwd(const void *x, const void *w, const float *b, void *y, int N,
+                                                     int C, int H, int W, int K, int y_ch_stride, int y_ch_offset,
+                                                     void *stream) {
+    ConvArgs a;
+    a.post_pool2 = 2;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, 3, 3, 1, 1, 1, nullptr, y_ch_stride, y_ch_offset);
+    if (st != GPULET_OK) return st;
+    // what the kernel with the pooled epilogue needs: whole 64-channel blocks, 16-byte stores
+    if (C % 64 != 0 || K % 8 != 0 || a.y_ch_stride % 8 != 0 || a.y_ch_offset % 8 != 0 ||
+        reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(y) % 16 != 0 || reinterpret_cast<uintptr_t>(b) % 16 != 0)
+        return GPULET_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GPULET_HIP(launch_conv(a, stream_ctx(s), s));
+    return GPULET_OK;
+}
+
+extern "C" gpulet_status gpulet_set_conv_pool_fusion(int on) {
+    if (on != 0 && on != 1) return GPULET_EINVAL;
+    set_conv_pool_fusion(on);
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const float *b, void *y,
                                            int N, int C, int H, int W, int K, int R, int S,
                                            int stride, int pad, int relu, void *stream) {

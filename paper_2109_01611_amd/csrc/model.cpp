@@ -41,6 +41,8 @@ struct Step {
     int lane;               // stream of the gpu-let this layer runs on
     std::vector<int> wait;  // earlier layers on other lanes this one must wait for
     bool record;            // a later layer on another lane waits for this one
+    bool pool_next;         // CONV: the next layer is a 2x2 / stride 2 max pool that is the only reader of
+                            // this layer's output; the pair may run as one launch (conv_pool2_fusable)
 };
 
 struct Plan {
@@ -178,6 +180,7 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         s.slice = false;
         s.lane = 0;
         s.record = false;
+        s.pool_next = false;
         int oc = 0, oh = 0, ow = 0, oelem = 2;
         if (L.op == GPULET_OP_CONV) {
             // in_ch_total > 0: the layer reads L.C channels from in_ch_offset on of wider pixels
@@ -309,6 +312,27 @@ gpulet_status build_plan(const gpulet_model_desc *m, int batch, Plan &plan) {
         }
         i += len;
     }
+    // Convolution + 2x2 / stride 2 max pool pairs whose intermediate tensor nobody else reads: the
+    // convolution may store the pooled tensor directly (decided per launch, see enqueue).  The
+    // intermediate buffer keeps its place in the workspace for the launches that run the pair as
+    // two kernels.
+    for (int i = 0; i + 1 < m->n_layers; ++i) {
+        Step &c = plan.steps[static_cast<size_t>(i)];
+        const Step &q = plan.steps[static_cast<size_t>(i + 1)];
+        if (c.op != GPULET_OP_CONV || c.group_len != 1 || c.slice || c.out2_buf >= 0 || c.pool_buf >= 0 || c.res_buf >= 0 ||
+            c.conv.pre_pool || !c.conv.relu || c.out_buf == m->out_buf)
+            continue;
+        if (q.op != GPULET_OP_POOL || q.group_len != 1 || q.in_buf != c.out_buf || q.mode != GPULET_POOL_MAX || q.k != 2 ||
+            q.stride != 2 || q.pad != 0 || c.conv.P % 2 != 0 || c.conv.Q % 2 != 0 || q.out_buf == c.in_buf)
+            continue;
+        bool only_reader = true;
+        for (int j = i + 2; j < m->n_layers && only_reader; ++j) {
+            const Step &t = plan.steps[static_cast<size_t>(j)];
+            if (t.in_buf == c.out_buf || t.res_buf == c.out_buf) only_reader = false;
+            if (t.out_buf == c.out_buf && !t.slice) break;   // overwritten as a whole: later readers see that tensor
+        }
+        c.pool_next = only_reader;
+    }
     assign_lanes(plan, m->n_bufs, g_model_lanes.load());
 
     plan.offset.assign(static_cast<size_t>(m->n_bufs), static_cast<size_t>(-1));
@@ -417,6 +441,29 @@ hipError_t enqueue(const Bound &bd, gpulet_partition *p) {
             }
             i += len - 1;
             continue;
+        }
+        if (s.op == GPULET_OP_CONV && s.pool_next && !s.record && steps[i + 1].lane == s.lane && steps[i + 1].wait.empty()) {
+            // the layer and the max pool behind it as one launch, when a kernel with a pooled
+            // epilogue applies and does not cost the layer more than the pool kernel saves
+            ConvArgs a = s.conv;
+            a.x = bd.ptr(s.in_buf);
+            a.y = bd.ptr(steps[i + 1].out_buf);
+            a.y_ch_stride = a.K;
+            a.y_ch_offset = 0;
+            if (conv_pool2_fusable(a, ctx)) {
+                a.post_pool2 = 2;
+                e = launch_conv(a, ctx, stream);
+                if (e != hipSuccess) return e;
+                p->kernels_enqueued.fetch_add(1);
+                ++i;   // the pool is done
+                if (steps[i].record) {
+                    hipEvent_t ev;
+                    e = pool_event(p, kMaxLanes + i, &ev);
+                    if (e == hipSuccess) e = hipEventRecord(ev, stream);
+                    if (e != hipSuccess) return e;
+                }
+                continue;
+            }
         }
         if (s.op == GPULET_OP_CONV) {
             ConvArgs a = s.conv;

@@ -113,6 +113,8 @@ def _load():
         "gpulet_set_conv_split_k": ([I], c_int32),
         "gpulet_depthwise_conv2d_fwd": ([P, P, P, P] + [I] * 9 + [P], c_int32),
         "gpulet_maxpool3_conv1x1_fwd": ([P, P, P, P] + [I] * 8 + [P], c_int32),
+        "gpulet_conv3x3_maxpool2_fwd": ([P, P, P, P] + [I] * 7 + [P], c_int32),
+        "gpulet_set_conv_pool_fusion": ([I], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
         "gpulet_fc_static_scratch": ([P, P, P, P] + [I] * 5 + [P], c_int32),
@@ -297,6 +299,15 @@ def depthwise_conv2d_fwd(x, w, b, y, N, C, H, W, R, S, stride, pad, relu, stream
 def maxpool3_conv1x1_fwd(x, w, b, y, N, C, H, W, K, relu, ch_total=0, ch_offset=0, stream=None):
     _check(lib.gpulet_maxpool3_conv1x1_fwd(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, K, int(relu), ch_total,
                                            ch_offset, stream), "gpulet_maxpool3_conv1x1_fwd")
+
+
+def conv3x3_maxpool2_fwd(x, w, b, y, N, C, H, W, K, ch_total=0, ch_offset=0, stream=None):
+    _check(lib.gpulet_conv3x3_maxpool2_fwd(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, K, ch_total, ch_offset,
+                                           stream), "gpulet_conv3x3_maxpool2_fwd")
+
+
+def set_conv_pool_fusion(on):
+    _check(lib.gpulet_set_conv_pool_fusion(int(bool(on))), "gpulet_set_conv_pool_fusion")
 
 
 def pool(x, y, N, C, H, W, mode, k=1, stride=1, pad=0, stream=None):

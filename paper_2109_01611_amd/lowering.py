@@ -145,6 +145,12 @@ class DeviceModel:
                 reads.append(nd.attr["residual"])
             for t in reads:
                 last_use[storage(t)] = i
+            # A 2x2 / stride 2 max pool right behind a convolution may be computed by that convolution's
+            # launch (the library decides per launch), which then writes the pool's buffer while it
+            # still reads its own input: that input stays allocated until the pool is done.
+            if (nd.op == "maxpool" and (nd.attr["k"], nd.attr["stride"], nd.attr["pad"]) == (2, 2, 0) and i > 0
+                    and nodes[i - 1].op == "conv" and nodes[i - 1].dst == nd.src):
+                last_use[storage(nodes[i - 1].src)] = max(last_use.get(storage(nodes[i - 1].src), 0), i)
         last_use[storage(model.out)] = len(nodes)
 
         buf_of = {"x": 0, storage(model.out): 1}

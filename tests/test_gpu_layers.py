@@ -690,6 +690,67 @@ def test_pool_parity(part, case):
         assert oracle.rel_err(got, ref)[1] <= LAYER_TOL
 
 
+# N, C, H, W, K, destination channels (0: K), first channel written
+POOLED_CONV_CASES = [
+    (2, 128, 56, 56, 128, 0, 0),      # VGG conv2_2-like: 8 x 28 tiles, two per row
+    (3, 64, 28, 28, 192, 0, 0),       # one channel block, ragged filter tile, tile rows 8+8+8+4
+    (1, 256, 14, 14, 256, 0, 0),      # whole map in one tile
+    (2, 128, 12, 20, 64, 0, 0),       # 10 x 20 + 2 x 20 tiles, half a filter tile
+    (2, 192, 6, 34, 136, 0, 0),       # one 6 x 34 tile per image, K a multiple of 8 only (second filter tile: 8 filters)
+    (1, 64, 10, 58, 64, 0, 0),        # column tiles of 20, 20 and 18 pixels
+    (1, 64, 2, 2, 8, 0, 0),           # one window
+    (2, 128, 16, 16, 72, 200, 64),    # stored as a channel slice of wider pixels
+]
+
+
+@pytest.mark.parametrize("case", POOLED_CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv3x3_maxpool2_fused_parity(part, case):
+    N, C, H, W, K, ct, co = case
+    x, w, b = conv_tensors(23, N, C, H, W, K, 3)
+    full = oracle.conv2d(x, w, b, 1, 1, relu=True)
+    ref = oracle.maxpool(full, 2, 2, 0)
+    mag = oracle.maxpool(conv_mag(x, w, b, 1, 1), 2, 2, 0)       # the largest bound of a window covers its maximum
+    xd, wd = lowering.nchw_to_nhwc(x, DEV), lowering.kcrs_to_krsc(w, DEV)
+    bd = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(DEV)
+    ctot = ct if ct else K
+    yd = torch.full((N, H // 2, W // 2, ctot), -512.0, dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    gpulet.conv3x3_maxpool2_fwd(xd, wd, bd, yd, N, C, H, W, K, ct, co, part.stream)
+    part.sync()
+    got = lowering.nhwc_to_nchw(yd[..., co:co + K])
+    assert_close(got, ref, mag, what=case)
+    if ct:                                                        # channels outside the slice are untouched
+        rest = torch.cat([yd[..., :co], yd[..., co + K:]], dim=-1)
+        assert bool((rest == -512.0).all())
+    # the same bits as the layer followed by the pool kernel, whatever tile runs the layer
+    for tile in (-1, 11, 1):
+        _, raw = gpu_conv(part, x, w, b, 1, 1, True, tile=tile)
+        pd = torch.empty((N, H // 2, W // 2, K), dtype=torch.bfloat16, device=DEV)
+        gpulet.pool(raw, pd, N, K, H, W, gpulet.POOL_MAX, 2, 2, 0, part.stream)
+        part.sync()
+        assert torch.equal(pd, yd[..., co:co + K]), tile
+
+
+def test_conv3x3_maxpool2_argument_errors(part):
+    def call(N, C, H, W, K, ct=0, co=0, shift=0):
+        x = torch.zeros(N * H * W * C + 8, dtype=torch.bfloat16, device=DEV)[shift:]
+        w = torch.zeros(K * 9 * C, dtype=torch.bfloat16, device=DEV)
+        b = torch.zeros(K, device=DEV)
+        y = torch.zeros(N * (H // 2) * (W // 2) * (ct if ct else K) + 8, dtype=torch.bfloat16, device=DEV)
+        return gpulet.lib.gpulet_conv3x3_maxpool2_fwd(gpulet.ptr(x), gpulet.ptr(w), gpulet.ptr(b), gpulet.ptr(y), N, C, H, W,
+                                                      K, ct, co, part.stream)
+    assert call(1, 64, 8, 8, 64) == gpulet.OK
+    assert call(1, 64, 7, 8, 64) == gpulet.EINVAL        # odd height: windows would hang over the edge
+    assert call(1, 64, 8, 9, 64) == gpulet.EINVAL
+    assert call(1, 96, 8, 8, 64) == gpulet.EINVAL        # not whole 64-channel blocks
+    assert call(1, 64, 8, 8, 60) == gpulet.EINVAL        # 16-byte stores need K % 8 == 0
+    assert call(1, 64, 8, 8, 64, 100, 0) == gpulet.EINVAL
+    assert call(1, 64, 8, 8, 64, 128, 4) == gpulet.EINVAL
+    assert call(1, 64, 8, 8, 64, 96, 40) == gpulet.EINVAL  # slice past the pixel
+    assert call(1, 64, 8, 8, 64, shift=4) == gpulet.EINVAL # misaligned x
+    part.sync()
+
+
 # N, In, Out
 FC_CASES = [(32, 400, 120), (32, 120, 84), (32, 84, 10), (1, 2048, 1000), (8, 1024, 1000),
             (33, 72, 17), (5, 8, 3), (40, 4096, 1000), (16, 25088, 64), (2, 100, 7),

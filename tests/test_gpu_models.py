@@ -259,6 +259,38 @@ def test_inception_1x1_layers_of_a_block_run_as_one_convolution(width_div, in_hw
     _assert_close(a.to(torch.float32).cpu().numpy().astype(np.float64).reshape(2, -1), ref)
 
 
+@pytest.mark.parametrize("model,batch,fused_pairs", [
+    (workloads.vgg16(), 16, 3),                                 # the pools after 128, 256 and 512 channels on 112, 56 and 28 pixel maps
+    (workloads.vgg16(width_div=2, in_hw=64, n_class=20), 16, None),
+], ids=["full", "half_width_64"])
+def test_vgg_pools_ride_in_the_convolutions_epilogue(model, batch, fused_pairs):
+    # A convolution followed by a 2x2 / stride 2 max pool may run as one launch; same bits, fewer launches.
+    params = workloads.parameters(model, 4)
+    x = workloads.batch_input(model, batch, 4)
+    dm = lowering.DeviceModel(model, params, DEV)
+    with gpulet.Partition(0, 100, 0) as p:
+        xd = dm.input_to_device(x)
+        try:
+            gpulet.set_conv_pool_fusion(False)
+            a, _ = dm.run(p, xd)
+            a = a.clone()
+            n_plain = p.kernel_launches()
+        finally:
+            gpulet.set_conv_pool_fusion(True)
+        b, _ = dm.run(p, xd)
+        n_fused = p.kernel_launches() - n_plain
+    assert torch.equal(a, b)
+    assert n_plain == dm.desc.n_layers
+    print("%s batch %d: %d launches, %d with pools fused" % (model.name, batch, n_plain, n_fused), flush=True)
+    if fused_pairs is not None:
+        assert n_fused == n_plain - fused_pairs
+    else:
+        assert n_fused <= n_plain
+    sel = [0, batch - 1]
+    ref = oracle.run_model(model, params, x[sel]).reshape(2, -1)
+    _assert_close(b.to(torch.float32).cpu().numpy().astype(np.float64).reshape(batch, -1)[sel], ref)
+
+
 def test_ssd_box_and_class_heads_run_as_one_convolution():
     model = workloads.ssd_mobilenet(width_div=4, in_hw=128, n_class=5)
     params = workloads.parameters(model, 12)
