@@ -292,10 +292,13 @@ gpulet_status gpulet_conv3x3_maxpool2_fwd(const void *x, const void *w, const fl
  * run a convolution and the 2x2 / stride 2 max pool that follows it as one launch
  * (1, the default) or always as two kernels (0).  When allowed, a pair is fused
  * per launch if the pool is the only reader of the layer's output, the layer
- * qualifies for gpulet_conv3x3_maxpool2_fwd with at least 128 input channels and
- * the kernel with the pooled epilogue costs the layer at most 15 % more than
- * the kernel it would run otherwise; the layer's own output buffer is then left
- * unwritten.  Results are bit-identical either way.  Process-wide.
+ * qualifies for gpulet_conv3x3_maxpool2_fwd and either runs the kernel that
+ * keeps the weights of 64 input channels in registers anyway (that kernel pools
+ * in its epilogue when its column blocks are a power of two wide) or has at
+ * least 128 input channels and the tall-tile kernel, which pools in its
+ * epilogue, costs the layer at most 15 % more than the kernel it would run
+ * otherwise; the layer's own output buffer is then left unwritten.  Results are
+ * bit-identical either way.  Process-wide.
  */
 gpulet_status gpulet_set_conv_pool_fusion(int on);
 

@@ -264,16 +264,19 @@ hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stre
     }
 
     if (a.post_pool2) {
+        // the two kernels with a pooled epilogue: weights in registers for 64 input channels, else the tall tile
         int th = 0, tw = 0;
         double geo = 0.0;
-        if (a.post_pool2 != 2 || a.y2 || a.pool_y || !tall_eligible(p, vec, &th, &tw, &geo, true)) return hipErrorInvalidValue;
+        if (a.post_pool2 != 2 || a.y2 || a.pool_y) return hipErrorInvalidValue;
+        if (c64_applicable(p, vec, &tw, true)) return launch_c64(p, tw, ctx.n_cu < 1 ? 1 : ctx.n_cu, true, stream);
+        if (!tall_eligible(p, vec, &th, &tw, &geo, true)) return hipErrorInvalidValue;
         return launch_tall(p, th, tw, true, stream);
     }
     const Choice c = choose_kernel(p, vec, ctx);
     const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
     switch (c.best) {
         case 11: return launch_tall(p, c.th11, c.tw11, false, stream);
-        case 10: return launch_c64(p, c.tw64, n_cu, stream);
+        case 10: return launch_c64(p, c.tw64, n_cu, false, stream);
         case 9: return launch_stem(p, n_cu, stream);
         case 8: return launch_stream(p, n_cu, stream);
         case 7: return launch_patch(p, c.tw, stream);
@@ -296,8 +299,9 @@ bool conv_pool2_fusable(const ConvArgs &a, const LaunchCtx &ctx) {
     if (make_params(a, ctx, p, vec) != hipSuccess) return false;
     int th = 0, tw = 0;
     double geo = 0.0;
-    if (p.C < 2 * BK || !tall_eligible(p, vec, &th, &tw, &geo, true)) return false;
     const Choice c = choose_kernel(p, vec, ctx);
+    if (c.best == 10) return c64_applicable(p, vec, &tw, true);   // the same kernel with another epilogue
+    if (p.C < 2 * BK || !tall_eligible(p, vec, &th, &tw, &geo, true)) return false;
     if (c.cost <= 0.0) return false;
     const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
     const double eff = 0.95 - 0.7 * (1.0 - geo) - 0.04 / (p.C / BK);

@@ -298,8 +298,8 @@ hipError_t launch_igemm_group(const ConvParams *p, int n, int tile, bool two_sta
 // conv_patch.hip: tile 7 (input patch in LDS) and tile 10 (64 input channels, weights in registers).
 bool patch_eligible(const ConvParams &p, bool vec, int *tw_out);
 hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream);
-bool c64_applicable(const ConvParams &p, bool vec, int *tw_out);
-hipError_t launch_c64(ConvParams p, int tw, int n_cu, hipStream_t stream);
+bool c64_applicable(const ConvParams &p, bool vec, int *tw_out, bool pool2 = false);
+hipError_t launch_c64(ConvParams p, int tw, int n_cu, bool pool2, hipStream_t stream);
 
 // conv_tall.hip: tile 11 (3x3, 224 x 128 tile, input patch in LDS, one tap per ring step).
 // `eff` receives the share of tile rows that are pixels for the chosen rectangle th x tw.

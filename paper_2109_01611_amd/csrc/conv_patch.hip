@@ -291,6 +291,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, const int wgs_per_col, const int tiles_m,
                                                           const int die_aware) {
     fetch_params(p);
+    asm volatile("" ::"s"(p.pool2));   // requested with the rest of the argument block
     constexpr int BM = PATCH_BM, BN = 64, NPROD = 4, PMAX = PATCH_PMAX, NB = 2;  // NB patch buffers
     constexpr int PATCH = PMAX * BK;           // elements per patch buffer
     constexpr int POPS = PMAX / 8 / NPROD;     // patch transfers per producer lane and tile
@@ -473,6 +474,30 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            if (p.pool2) {
+                // A 2x2 / stride 2 max pool follows: the wavefront's 64 pixels are 64/tw whole rows of
+                // the tile (an even number, starting at an even row and column), i.e. 16 windows;
+                // lane -> window lane/4, its 8 filters.  The maximum is taken on the rounded values,
+                // as the pool kernel would, and only the pooled pixel is stored.  p.th = log2(tw/2).
+                const int pp = lane >> 2, py = pp >> p.th, px = pp - (py << p.th);
+                const int lw = 2 * py * p.tw + 2 * px;            // window's top left pixel among the 64
+                unsigned k[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(tr + (lw + (i >> 1) * p.tw + (i & 1)) * TROW + (lane & 3) * 16);
+                    const unsigned kv[4] = {bf16_pair_order_key(v.x), bf16_pair_order_key(v.y), bf16_pair_order_key(v.z),
+                                            bf16_pair_order_key(v.w)};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) k[e] = i == 0 ? kv[e] : max_keys(k[e], kv[e]);
+                }
+                const int l = tl.l0 + wy * 64 + lw;
+                const int rho = fdiv(l, p.d_tw);
+                const int q = tl.q0 + (l - rho * p.tw);
+                if (rho < NP && q < p.Q && kst < p.K)   // rho = n*P + row with P even: the pooled row is rho/2
+                    *reinterpret_cast<uint4 *>(p.y + (((rho >> 1) * (p.Q >> 1) + (q >> 1)) * p.ldy + p.y_off + kst)) =
+                        make_uint4(bf16_pair_order_key(k[0]), bf16_pair_order_key(k[1]), bf16_pair_order_key(k[2]),
+                                   bf16_pair_order_key(k[3]));
+            } else {
             uint4 out[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -484,6 +509,7 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
                 const int q = tl.q0 + (l - rho * p.tw);
                 if (rho < NP && q < p.Q && kst < p.K)
                     *reinterpret_cast<uint4 *>(p.y + ((rho * p.Q + q) * p.ldy + p.y_off + kst)) = out[i];
+            }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -543,11 +569,17 @@ hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream) {
 
 // The 3x3 kernel with register-resident weights: what the patch kernel needs, exactly 64 input
 // channels, no residual operand, aligned 16-byte stores.
-bool c64_applicable(const ConvParams &p, bool vec, int *tw_out) {
-    return patch_eligible(p, vec, tw_out) && p.C == BK && !p.res && p.vec_store && p.K % 8 == 0;
+bool c64_applicable(const ConvParams &p, bool vec, int *tw_out, bool pool2) {
+    if (!(patch_eligible(p, vec, tw_out) && p.C == BK && !p.res && p.vec_store && p.K % 8 == 0)) return false;
+    // a fused 2x2 pool: every wavefront's 64 pixels must be an even number of whole, even-aligned tile rows
+    const int tw = *tw_out;
+    return !pool2 || (p.relu && p.P % 2 == 0 && p.Q % 2 == 0 && tw >= 2 && tw <= 32 && (tw & (tw - 1)) == 0);
 }
 
-hipError_t launch_c64(ConvParams p, int tw, int n_cu, hipStream_t stream) {
+hipError_t launch_c64(ConvParams p, int tw, int n_cu, bool pool2, hipStream_t stream) {
+    p.pool2 = pool2 ? 2 : 0;
+    p.th = 0;
+    while (pool2 && (2 << p.th) < tw) ++p.th;   // log2(tw / 2)
     p.tw = tw;
     p.n_cb = (p.Q + tw - 1) / tw;
     const long long lin = 1LL * p.N * p.P * tw;

@@ -104,9 +104,9 @@ struct ConvArgs {
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 // Whether the layer followed by a 2x2 / stride 2 max pool should run as one launch on this
 // stream: a kernel that can pool in its epilogue applies (3x3, stride 1, pad 1, ReLU, no residual,
-// C a multiple of 64 from 128 on, even output size, aligned dense operands) and is at most a few
-// percent slower on the layer alone than the kernel that would run it otherwise.  `a.y` is the
-// pooled destination.
+// C a multiple of 64, even output size, aligned dense operands) and is the kernel the layer would
+// run anyway (64 input channels, weights in registers) or at most a few percent slower on the
+// layer alone (the tall tile, from 128 channels on).  `a.y` is the pooled destination.
 bool conv_pool2_fusable(const ConvArgs &a, const LaunchCtx &ctx);
 void set_conv_pool_fusion(int on);
 // n independent layers (no member reads or overwrites what another writes), in one launch where

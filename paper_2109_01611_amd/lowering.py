@@ -475,7 +475,10 @@ class DeviceModel:
 
     def read_tensor(self, name, batch):
         """Copy of a named intermediate tensor (NHWC) from the workspace after a run.
-        Only meaningful for tensors whose buffer was not reused later."""
+        Only meaningful for tensors whose buffer was not reused later, and, for the output of a
+        convolution that feeds nothing but a 2x2 / stride 2 max pool, only with
+        ``gpulet.set_conv_pool_fusion(False)`` (the pair may otherwise run as one launch that never
+        writes it)."""
         buf = self.tensor_buf[name]
         ws, _ = self.workspace(batch)
         C, H, W, e, off = gpulet.model_buffer_info(self.desc, batch, buf)

@@ -697,8 +697,13 @@ POOLED_CONV_CASES = [
     (1, 256, 14, 14, 256, 0, 0),      # whole map in one tile
     (2, 128, 12, 20, 64, 0, 0),       # 10 x 20 + 2 x 20 tiles, half a filter tile
     (2, 192, 6, 34, 136, 0, 0),       # one 6 x 34 tile per image, K a multiple of 8 only (second filter tile: 8 filters)
-    (1, 64, 10, 58, 64, 0, 0),        # column tiles of 20, 20 and 18 pixels
+    (1, 128, 10, 58, 64, 0, 0),       # column tiles of 20, 20 and 18 pixels
     (1, 64, 2, 2, 8, 0, 0),           # one window
+    # 64 input channels and column blocks of a power of two: the resident-weight kernel's pooled epilogue
+    (2, 64, 32, 32, 64, 0, 0),        # 8 x 16 tiles, two column blocks
+    (1, 64, 64, 48, 128, 0, 0),       # two filter tiles, three column blocks
+    (3, 64, 8, 8, 72, 0, 0),          # 8-pixel rows: tiles span two images; ragged filter tile
+    (2, 64, 10, 58, 64, 96, 32),      # ragged last column block, rows of two images in one tile, channel slice
     (2, 128, 16, 16, 72, 200, 64),    # stored as a channel slice of wider pixels
 ]
 

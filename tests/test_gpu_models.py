@@ -260,7 +260,7 @@ def test_inception_1x1_layers_of_a_block_run_as_one_convolution(width_div, in_hw
 
 
 @pytest.mark.parametrize("model,batch,fused_pairs", [
-    (workloads.vgg16(), 16, 3),                                 # the pools after 128, 256 and 512 channels on 112, 56 and 28 pixel maps
+    (workloads.vgg16(), 16, 4),                                 # all pools but the last (14 x 14 maps: the patch kernel keeps that layer)
     (workloads.vgg16(width_div=2, in_hw=64, n_class=20), 16, None),
 ], ids=["full", "half_width_64"])
 def test_vgg_pools_ride_in_the_convolutions_epilogue(model, batch, fused_pairs):
