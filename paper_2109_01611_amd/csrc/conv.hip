@@ -148,6 +148,18 @@ struct Choice {
     double cost;   // of `best` in the cost model's units when it is a gathering tile or the tall tile, else 0
 };
 
+// Cost of a layer on the tall tile in the units of choose_kernel: rounds on the busiest CU x tile
+// area / efficiency relative to the 256x128 gathering tile.  The efficiency is fitted to
+// measurements on MI355X (3x3 layers of 128..512 channels on 14..112 pixel maps at batch 16 and
+// 32, on 64, 128 and 256 CUs): 0.95 when every tile row is a pixel and the depth is long, less a
+// share of the rows that are not pixels (they are already in the tile count; what remains is that
+// the epilogue and the patch do not shrink with them) and the first loads and the epilogue that
+// a short depth does not amortise.
+double tall_cost(const ConvParams &p, int th, int tw, double geo, int n_cu) {
+    const double eff = 0.95 - 0.35 * (1.0 - geo) - 0.04 / (p.C / BK);
+    return static_cast<double>((tall_tiles(p, th, tw) + n_cu - 1) / n_cu) * 224 * 128 / eff;
+}
+
 Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
     // Pick the tile and the split of the depth that minimise
     //   (work items on the busiest CU) x (tile area) x (share of the depth + fixed cost of a split) / efficiency.
@@ -192,17 +204,12 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
         best_split = 1;
     }
     // The tall tile (224 pixels of one image x 128 filters, input patch in LDS) against the best
-    // gathering tile, in the same units.  Its efficiency relative to 256x128, fitted to
-    // measurements on MI355X (3x3 layers of 128..512 channels on 28..112 pixel maps at batch 16
-    // and 32): 0.95 when every tile row is a pixel and the depth is long, less the rows that are
-    // not pixels and the first loads and the epilogue that a short depth does not amortise.
+    // gathering tile, in the same units (tall_cost).
     int th11 = 0, tw11 = 0;
     double geo11 = 0.0;
     const bool tall_ok = tall_eligible(p, vec, &th11, &tw11, &geo11);
     if (forced < 0 && tall_ok && p.C >= 2 * BK) {
-        const long long tiles = tall_tiles(p, th11, tw11);
-        const double eff = 0.95 - 0.7 * (1.0 - geo11) - 0.04 / (p.C / BK);
-        const double cost = static_cast<double>((tiles + n_cu - 1) / n_cu) * 224 * 128 / eff;
+        const double cost = tall_cost(p, th11, tw11, geo11, n_cu);
         if (cost < best_cost) {
             best = 11;
             best_split = 1;
@@ -303,10 +310,7 @@ bool conv_pool2_fusable(const ConvArgs &a, const LaunchCtx &ctx) {
     if (c.best == 10) return c64_applicable(p, vec, &tw, true);   // the same kernel with another epilogue
     if (p.C < 2 * BK || !tall_eligible(p, vec, &th, &tw, &geo, true)) return false;
     if (c.cost <= 0.0) return false;
-    const int n_cu = ctx.n_cu < 1 ? 1 : ctx.n_cu;
-    const double eff = 0.95 - 0.7 * (1.0 - geo) - 0.04 / (p.C / BK);
-    const double cost = static_cast<double>((tall_tiles(p, th, tw) + n_cu - 1) / n_cu) * 224 * 128 / eff;
-    return cost <= 1.15 * c.cost;
+    return tall_cost(p, th, tw, geo, ctx.n_cu < 1 ? 1 : ctx.n_cu) <= 1.15 * c.cost;
 }
 
 // Independent layers in one launch.  Every member must be a layer the gathering kernel would
