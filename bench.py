@@ -133,7 +133,7 @@ def main():
             # HBM-side bytes per launch from the FETCH_SIZE + WRITE_SIZE counter passes recorded in
             # profiles/ (scaled by a 64 MiB copy); null when the kernel's sources have changed since
             "traffic": recorded_traffic(),
-            "kernel": "conv3x3_patch_kernel<64,4>",
+            "kernel": "conv3x3_patch_kernel<64,4,false>",
             "avg_launch_us": kernel_ms * 1e3,
         },
     }

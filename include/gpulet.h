@@ -317,6 +317,28 @@ gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const fl
                                           int y_ch_offset, void *stream);
 
 /*
+ * Measurement aid for the time decomposition of a convolution launch (the
+ * per-partition latency profile of Sec. 3.1 is made of such launches): runs the
+ * layer `warmup` times as gpulet_conv2d_fwd would, then once more with the
+ * kernel's first workgroups (at most 8) recording the device's wall clock (a
+ * constant 100 MHz counter shared by the whole GPU: 10 ns units) at these
+ * points of their life:
+ *   0 first instruction            1 argument block fetched, tile decoded
+ *   2 position table complete      3 first input patch and weights in LDS
+ *   4 end of the main loop         5 fp32 tile staged in LDS
+ *   6 output stores issued         7 unused (0)
+ * stamps: HOST array of 8 x 8 int64, row = workgroup; *workgroups = how many
+ * rows were filled: 0 when the kernel that runs this layer records no stamps
+ * (only the kernels that keep the input patch in LDS, tiles 7 and 11 of
+ * gpulet_set_conv_tile, do).  Allocates and frees a 512-byte device buffer;
+ * synchronises.  Errors as gpulet_conv2d_fwd; GPULET_EINVAL for NULL stamps or
+ * workgroups or a negative warmup.
+ */
+gpulet_status gpulet_conv2d_timeline(const void *x, const void *w, const float *b, void *y, int N, int C,
+                                     int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                                     void *stream, int warmup, int64_t *stamps, int *workgroups);
+
+/*
  * Tuning and testing knob: force every later convolution launch of the
  * process onto one workgroup tile (pixels x channels):
  *   0: 128x128  1: 128x64  2: 64x128  3: 64x64  4: 128x32  5: 32x128  6: 256x128

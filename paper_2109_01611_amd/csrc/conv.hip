@@ -97,6 +97,7 @@ hipError_t make_params(const ConvArgs &a, const LaunchCtx &ctx, ConvParams &p, b
     p.ldy2 = a.y2_ch_stride;
     p.y2_off = a.y2_ch_offset;
     p.pool2 = p.pad4 = 0;
+    p.stamps = static_cast<long long *>(a.stamps);
     p.tiles_n = p.n_tiles = p.tiles_per_xcd = 0;
     // up to the last channel the layer reads of the last pixel
     p.x_bytes = static_cast<unsigned>(2LL * ((1LL * a.N * a.H * a.W - 1) * p.ldx + a.C));

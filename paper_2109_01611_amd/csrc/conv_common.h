@@ -73,6 +73,9 @@ struct alignas(64) ConvParams {
     // Tall-tile kernel only: 2 = a 2x2 / stride 2 max pool follows the layer and only the pooled
     // tensor (N, P/2, Q/2 pixels of ldy channels) is stored to y; 0 = the layer's own output.
     int pool2, pad4;
+    // Patch and tall-tile kernels only: when not null, the first kStampWgs workgroups record the
+    // wall clock (10 ns units) at kStampPoints points of their life here (gpulet_conv2d_timeline).
+    long long *stamps;
     // Side job (1x1 gathering kernels only): the side_blocks extra workgroups compute the
     // 3x3 / stride 1 / pad 1 max pool side_pool of the layer's (dense) input.
     PoolParams side_pool;
@@ -98,6 +101,35 @@ __device__ __forceinline__ void fetch_params(const ConvParams &p) {
                  "s"(p.d_ncb.mul), "s"(p.d_ncb.shift), "s"(p.d_pwt.mul), "s"(p.d_pwt.shift), "s"(p.d_hp.mul),
                  "s"(p.d_hp.shift), "s"(p.th), "s"(p.tiles_img), "s"(p.tap_inner), "s"(p.split_k), "s"(p.sps));
 }
+
+// Wall-clock stamps of a workgroup for the timeline entry point: taken by the first wavefront of
+// the first kStampWgs workgroups and stored at once by its first lane.  Only the kernel instances
+// compiled with ON record anything (a branch per point cost the ordinary launches 1-4 %); in the
+// others every member is empty.
+constexpr int kStampWgs = 8, kStampPoints = 8;
+template <bool ON>
+struct Stamps {
+    long long *slot = nullptr;   // this workgroup's row, or null
+    __device__ __forceinline__ Stamps(const ConvParams &p, int wave) {
+        if constexpr (ON) {
+            if (p.stamps != nullptr && blockIdx.x < kStampWgs && wave == 0) slot = p.stamps + blockIdx.x * kStampPoints;
+        }
+    }
+    __device__ __forceinline__ void at(int i) {
+        if constexpr (ON) {
+            if (slot) {
+                const long long t = wall_clock64();
+                if (threadIdx.x == 0) slot[i] = t;
+            }
+        }
+    }
+    // a stamp taken before this object could be made (before the argument block was there)
+    __device__ __forceinline__ void put(int i, long long t) {
+        if constexpr (ON) {
+            if (slot && threadIdx.x == 0) slot[i] = t;
+        }
+    }
+};
 
 // LDS position (in elements) of chunk `chunk` of row `row` in a [rows][BK] tile.
 // Rows are 128 bytes; XOR-ing the chunk index with bits 1..3 of the row spreads

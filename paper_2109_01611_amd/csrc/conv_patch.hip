@@ -46,7 +46,8 @@ namespace {
 // the next patch are issued before the weights of step t+2, so waiting for the
 // weights of step t also covers every patch piece issued earlier.
 // ---------------------------------------------------------------------------
-template <int BN, int NPROD>
+// STAMP: the instance that records wall-clock stamps of its first workgroups (gpulet_conv2d_timeline).
+template <int BN, int NPROD, bool STAMP = false>
 __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const ConvParams p) {
     constexpr int BM = PATCH_BM, NCONS = 4, NS = 3, PMAX = PATCH_PMAX;
     constexpr int NT = BN / 32;                    // MFMA tiles per consumer (one row of them)
@@ -71,9 +72,14 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     __bf16 *const patch = lds;
     __bf16 *const wring = lds + 2 * PATCH;
 
+    long long t_start = 0;
+    if constexpr (STAMP) t_start = wall_clock64();
     fetch_params(p);
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
+    Stamps<STAMP> st(p, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+    st.put(0, t_start);
+    st.at(1);   // the argument block is there
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int tl = fdiv(tm, p.d_ncb), cb = tm - tl * p.n_cb;
     const int l0 = tl * BM, n0 = tn * BN, q0 = cb * p.tw;
@@ -184,6 +190,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr));
         }
         __syncthreads();   // the table is complete (the producers wait here too)
+        st.at(2);
 #pragma unroll
         for (int j = 0; j < NT; ++j)
 #pragma unroll
@@ -211,6 +218,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
                 __syncthreads();
+                if (r == 0 && blk == 0) st.at(3);   // the first patch and weights have landed
                 const __bf16 *wb = wring + r * BSTAGE;
                 auto load = [&](Frags &f, int i) {
                     const int s = i / (BK / 16), ks = i % (BK / 16);
@@ -240,6 +248,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 
     // Epilogue through LDS, as in the kernel above.
     float *stg = reinterpret_cast<float *>(lds);
+    st.at(4);          // end of the main loop
     __syncthreads();
     if (wave < NCONS) {
         const int frow = lane & 31, fhalf = lane >> 5;
@@ -252,12 +261,14 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             }
     }
     __syncthreads();
+    st.at(5);          // the tile is staged
     finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, [&](int row) {
         const int l = l0 + row;
         const int rho = fdiv(l, p.d_tw);
         const int q = q0 + (l - rho * p.tw);
         return (rho < NP && q < p.Q) ? rho * p.Q + q : -1;
     });
+    st.at(6);          // the output stores are issued
 }
 
 // ---------------------------------------------------------------------------
@@ -562,8 +573,12 @@ hipError_t launch_patch(ConvParams p, int tw, hipStream_t stream) {
     p.d_ncb = make_fastdiv(p.n_cb);
     p.d_pwt = make_fastdiv(tw + 2);
     p.d_hp = make_fastdiv(p.H + 2 * p.pad);
-    hipLaunchKernelGGL((conv3x3_patch_kernel<BN, 4>), dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)),
-                       dim3(8 * 64), 0, stream, p);
+    if (p.stamps)
+        hipLaunchKernelGGL((conv3x3_patch_kernel<BN, 4, true>), dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)),
+                           dim3(8 * 64), 0, stream, p);
+    else
+        hipLaunchKernelGGL((conv3x3_patch_kernel<BN, 4>), dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)),
+                           dim3(8 * 64), 0, stream, p);
     return hipGetLastError();
 }
 

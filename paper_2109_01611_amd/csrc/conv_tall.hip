@@ -72,10 +72,10 @@ __device__ __forceinline__ bf16x8 lds_frag(const __bf16 *lds, unsigned byte_off)
 // One consumer wavefront: MTW row tiles starting at row tile rt0, filters fg*32 .. +32.
 // a_addr[i][tap]: byte offset of this lane's fragment of depth step 0 at tap `tap` for its row
 // of row tile i, inside patch buffer 0; depth step ks is at a_addr ^ (ks << 5).
-template <int MTW>
+template <int MTW, bool STAMP>
 __device__ __forceinline__ void tall_consume(const __bf16 *lds, const unsigned (&a_addr)[4][9], const unsigned b_addr,
                                              const int nblk, const unsigned wring_off, const unsigned stage_bytes,
-                                             const unsigned patch_bytes, f32x16 (&acc)[4]) {
+                                             const unsigned patch_bytes, f32x16 (&acc)[4], Stamps<STAMP> &st) {
     TallFrags f0, f1;
     // Zero, but re-made opaque to the compiler in every block: the offsets of the four depth
     // steps of every (row tile, tap) are loop invariants, and hoisting them out of the block
@@ -95,6 +95,7 @@ __device__ __forceinline__ void tall_consume(const __bf16 *lds, const unsigned (
     unsigned pb = 0;                       // byte offset of the current block's patch buffer
     int g = 0;                             // tap counter over all blocks: its weights sit in stage g % 4
     __syncthreads();                       // barrier 0
+    st.at(3);                              // the first patch and weights have landed
     load(f0, 0, 0, 0u, wring_off);
     for (int blk = 0; blk < nblk; ++blk) {
         const unsigned pb_next = pb ^ patch_bytes;   // pb is only ever 0 or patch_bytes
@@ -174,6 +175,8 @@ __device__ __forceinline__ void finish_tile_pool2(const ConvParams &p, const flo
     }
 }
 
+// STAMP: the instance that records wall-clock stamps of its first workgroups (gpulet_conv2d_timeline).
+template <bool STAMP>
 __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     constexpr int BM = TALL_BM, BN = TALL_BN, NCONS = 8, NPROD = 4, NS = 4, PMAX = TALL_PMAX;
     constexpr int WSTAGE = BN * BK;                // elements per weight stage: one tap
@@ -194,10 +197,15 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     __bf16 *const wring = lds;
     __bf16 *const patch = lds + NS * WSTAGE;
 
+    long long t_start = 0;
+    if constexpr (STAMP) t_start = wall_clock64();
     fetch_params(p);
     asm volatile("" ::"s"(p.pool2));   // requested with the rest of the argument block
     const int tile = tile_of_block(p);
     if (tile >= p.n_tiles) return;
+    Stamps<STAMP> st(p, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
+    st.put(0, t_start);
+    st.at(1);   // the argument block is there
     // tile -> (image, tile row, tile column, filter tile); filter tiles of one pixel tile are neighbours
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int n = fdiv(tm, p.d_hp), ti = tm - n * p.tiles_img;
@@ -305,6 +313,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
             }
         }
         __syncthreads();   // the table is complete (the producers wait here too)
+        st.at(2);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -327,13 +336,14 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
         const int brow = fg * 32 + frow;
         const unsigned b_addr = static_cast<unsigned>(brow * (BK * 2) + ((((brow >> 1) & 7) ^ fhalf) << 4));
         if (hi == 0)
-            tall_consume<4>(lds, a_addr, b_addr, nblk, 0u, WSTAGE * 2, PATCH * 2, acc);
+            tall_consume<4, STAMP>(lds, a_addr, b_addr, nblk, 0u, WSTAGE * 2, PATCH * 2, acc, st);
         else
-            tall_consume<3>(lds, a_addr, b_addr, nblk, 0u, WSTAGE * 2, PATCH * 2, acc);
+            tall_consume<3, STAMP>(lds, a_addr, b_addr, nblk, 0u, WSTAGE * 2, PATCH * 2, acc, st);
     }
 
     // Epilogue through LDS, as in the other kernels.
     float *stg = reinterpret_cast<float *>(lds);
+    st.at(4);          // end of the main loop
     __syncthreads();   // all LDS reads of the main loop are done, all transfers have landed
     if (wave < NCONS) {
         const int frow = lane & 31, fhalf = lane >> 5;
@@ -349,16 +359,18 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
         }
     }
     __syncthreads();
+    st.at(5);          // the tile is staged
     if (p.pool2) {
         finish_tile_pool2<BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, n, ty0, tx0);
-        return;
+    } else {
+        finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, [&](int row) {
+            if (row >= npix) return -1;
+            const int ty = fdiv(row, p.d_tw), tx = row - ty * p.tw;
+            const int hh = ty0 + ty, ww = tx0 + tx;
+            return (hh < p.P && ww < p.Q) ? (n * p.P + hh) * p.Q + ww : -1;
+        });
     }
-    finish_tile<BM, BN, (NCONS + NPROD) * 64>(p, stg, n0, bias_regs, [&](int row) {
-        if (row >= npix) return -1;
-        const int ty = fdiv(row, p.d_tw), tx = row - ty * p.tw;
-        const int hh = ty0 + ty, ww = tx0 + tx;
-        return (hh < p.P && ww < p.Q) ? (n * p.P + hh) * p.Q + ww : -1;
-    });
+    st.at(6);          // the output stores are issued
 }
 
 // The pixel rectangle th x tw (th*tw <= 224, patch within TALL_PMAX positions) that wastes the
@@ -415,7 +427,10 @@ hipError_t launch_tall(ConvParams p, int th, int tw, bool pool2, hipStream_t str
     p.d_ncb = make_fastdiv(p.n_cb);
     p.d_pwt = make_fastdiv(tw + 2);
     p.d_hp = make_fastdiv(p.tiles_img);
-    hipLaunchKernelGGL(conv3x3_tall_kernel, dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)), dim3(12 * 64), 0, stream, p);
+    if (p.stamps)
+        hipLaunchKernelGGL(conv3x3_tall_kernel<true>, dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)), dim3(12 * 64), 0, stream, p);
+    else
+        hipLaunchKernelGGL(conv3x3_tall_kernel<false>, dim3(static_cast<unsigned>(p.tiles_per_xcd * 8)), dim3(12 * 64), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -100,6 +100,9 @@ struct ConvArgs {
     // of y_ch_stride channels); P and Q stay the layer's own output size.  Only layers for which
     // conv_pool2_fusable() holds.
     int post_pool2 = 0;
+    // Measurement (gpulet_conv2d_timeline): device array of 8 x 8 int64 that the kernel's first
+    // workgroups fill with wall-clock stamps, if the kernel that runs the layer records them.
+    void *stamps = nullptr;
 };
 hipError_t launch_conv(const ConvArgs &a, const LaunchCtx &ctx, hipStream_t stream);
 // Whether the layer followed by a 2x2 / stride 2 max pool should run as one launch on this

@@ -185,6 +185,32 @@ extern "C" gpulet_status gpulet_conv2d_fwd(const void *x, const void *w, const f
                                 stream);
 }
 
+extern "C" gpulet_status gpulet_conv2d_timeline(const void *x, const void *w, const float *b, void *y, int N, int C,
+                                                int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                                                void *stream, int warmup, int64_t *stamps, int *workgroups) {
+    if (!stamps || !workgroups || warmup < 0) return GPULET_EINVAL;
+    ConvArgs a;
+    gpulet_status st = make_conv_args(a, x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, nullptr, 0, 0);
+    if (st != GPULET_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const LaunchCtx ctx = stream_ctx(s);
+    constexpr size_t kBytes = 8 * 8 * sizeof(int64_t);
+    void *dev = nullptr;
+    GPULET_HIP(hipMalloc(&dev, kBytes));
+    hipError_t e = hipMemsetAsync(dev, 0, kBytes, s);
+    for (int i = 0; i < warmup && e == hipSuccess; ++i) e = launch_conv(a, ctx, s);
+    a.stamps = dev;
+    if (e == hipSuccess) e = launch_conv(a, ctx, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(stamps, dev, kBytes, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(dev);
+    if (e != hipSuccess) return hip_fail(e);
+    int n = 0;
+    while (n < 8 && stamps[n * 8] != 0) ++n;
+    *workgroups = n;
+    return GPULET_OK;
+}
+
 extern "C" gpulet_status gpulet_set_conv_tile(int tile) {
     if (tile < -1 || tile >= GPULET_CONV_TILES) return GPULET_EINVAL;
     set_conv_tile(tile);

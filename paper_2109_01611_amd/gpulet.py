@@ -115,6 +115,7 @@ def _load():
         "gpulet_maxpool3_conv1x1_fwd": ([P, P, P, P] + [I] * 8 + [P], c_int32),
         "gpulet_conv3x3_maxpool2_fwd": ([P, P, P, P] + [I] * 7 + [P], c_int32),
         "gpulet_set_conv_pool_fusion": ([I], c_int32),
+        "gpulet_conv2d_timeline": ([P, P, P, P] + [I] * 10 + [P, I, POINTER(ctypes.c_int64), IP], c_int32),
         "gpulet_pool": ([P, P] + [I] * 8 + [P], c_int32),
         "gpulet_fc": ([P, P, P, P] + [I] * 5 + [P], c_int32),
         "gpulet_fc_static_scratch": ([P, P, P, P] + [I] * 5 + [P], c_int32),
@@ -304,6 +305,16 @@ def maxpool3_conv1x1_fwd(x, w, b, y, N, C, H, W, K, relu, ch_total=0, ch_offset=
 def conv3x3_maxpool2_fwd(x, w, b, y, N, C, H, W, K, ch_total=0, ch_offset=0, stream=None):
     _check(lib.gpulet_conv3x3_maxpool2_fwd(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, K, ch_total, ch_offset,
                                            stream), "gpulet_conv3x3_maxpool2_fwd")
+
+
+def conv2d_timeline(x, w, b, y, N, C, H, W, K, R, S, stride, pad, relu, stream=None, warmup=100):
+    """Wall-clock stamps (10 ns units) of the first workgroups of one launch: list of rows of 8 integers,
+    empty when the kernel that runs the layer records none."""
+    buf = (ctypes.c_int64 * 64)()
+    n = c_int()
+    _check(lib.gpulet_conv2d_timeline(ptr(x), ptr(w), ptr(b), ptr(y), N, C, H, W, K, R, S, stride, pad, int(relu), stream,
+                                      warmup, buf, byref(n)), "gpulet_conv2d_timeline")
+    return [list(buf[i * 8:i * 8 + 8]) for i in range(n.value)]
 
 
 def set_conv_pool_fusion(on):

@@ -18,7 +18,8 @@ library chose, its duration, TFLOP/s, the fraction of the bf16 MFMA peak, and
 ``load --shape N,C,H,W,K,R,stride,pad --data normal|relu|zeros --seconds S`` keeps one layer
 running so that clocks and power can be read meanwhile; ``mfma --data both|dense|zeros --waves 4|8 --seconds S``
 does the same with a probe that issues matrix instructions on register operands and nothing else (the ceiling of
-the matrix pipelines for an operand pattern).  ``run`` takes ``--models name:batch,...`` (default: the four ImageNet-size
+the matrix pipelines for an operand pattern).  ``timeline --shape ... [--tile 7|11]`` prints the wall-clock stamps that the
+first workgroups of a launch record about themselves (argument fetch, first data, main loop, epilogue).  ``run`` takes ``--models name:batch,...`` (default: the four ImageNet-size
 models at their configurations' batch sizes plus the benchmark layer) and
 ``--shapes "N,C,H,W,K,R,stride,pad;..."`` for extra layers.  Inputs are dense
 N(0,1) values (no zeros), the most power-hungry case for the matrix pipelines;
@@ -145,6 +146,44 @@ def load(args):
             iters = max(50, int(1000.0 / ms))
 
 
+STAMP_POINTS = ["first instruction", "argument block fetched", "position table complete", "first patch and weights in LDS",
+                "end of the main loop", "tile staged", "output stores issued"]
+
+
+def timeline(args):
+    """Prints where the first workgroups of a launch spend their time (``gpulet_conv2d_timeline``):
+    microseconds from the earliest workgroup's first instruction to each point, next to the
+    launch-to-launch time of the same layer measured right before."""
+    import torch
+    from paper_2109_01611_amd import gpulet
+    dev = torch.device("cuda:0")
+    N, C, H, W, K, R, stride, pad = (int(v) for v in args.shape.split(","))
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    gen = torch.Generator(device=dev).manual_seed(0)
+    x = torch.relu(torch.randn((N, H, W, C), device=dev, generator=gen)).to(torch.bfloat16)
+    w = (torch.randn((K, R, R, C), device=dev, generator=gen) * (2.0 / (C * R * R)) ** 0.5).to(torch.bfloat16)
+    b = torch.zeros(K, device=dev)
+    y = torch.empty((N, P, Q, K), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    with gpulet.Partition(0, 100, 0) as part:
+        if args.tile >= 0:
+            gpulet.set_conv_tile(args.tile)
+        try:
+            ms = gpulet.time_conv2d(x, w, b, y, N, C, H, W, K, R, R, stride, pad, True, stream=part.stream, warmup=3000, iters=3000)
+            print("shape %s: %.2f us per launch, launch to launch (3000 launches between one event pair)" % (args.shape, ms * 1e3))
+            for rep in range(args.reps):
+                rows = gpulet.conv2d_timeline(x, w, b, y, N, C, H, W, K, R, R, stride, pad, True, stream=part.stream, warmup=500)
+                if not rows:
+                    print("the kernel that runs this layer records no stamps")
+                    return
+                t0 = min(r[0] for r in rows)
+                print("launch %d: microseconds since the earliest first instruction of workgroups 0..%d" % (rep, len(rows) - 1))
+                for i, name in enumerate(STAMP_POINTS):
+                    print("  %-34s %s" % (name, " ".join("%6.2f" % ((r[i] - t0) / 100.0) for r in rows)))
+        finally:
+            gpulet.set_conv_tile(-1)
+
+
 def mfma(args):
     """Runs the matrix-instruction-only probe (no memory traffic at all) for ``--seconds`` per operand
     pattern and prints its rate once a second: the ceiling of any kernel's matrix throughput at the
@@ -224,6 +263,10 @@ def main():
     r.add_argument("--models", default=DEFAULT_MODELS)
     r.add_argument("--shapes", default="")
     r.add_argument("--reps", type=int, default=20)
+    t = sub.add_parser("timeline")
+    t.add_argument("--shape", default=",".join(str(v) for v in BENCH_SHAPE), help="N,C,H,W,K,R,stride,pad")
+    t.add_argument("--tile", type=int, default=-1, help="force a tile id (7 and 11 record stamps)")
+    t.add_argument("--reps", type=int, default=3)
     m = sub.add_parser("mfma")
     m.add_argument("--data", default="both", choices=["both", "dense", "zeros"])
     m.add_argument("--waves", type=int, default=8, choices=[4, 8])
@@ -242,6 +285,8 @@ def main():
         load(args)
     elif args.cmd == "mfma":
         mfma(args)
+    elif args.cmd == "timeline":
+        timeline(args)
     else:
         parse(args.trace_dir, args.pmc_dir)
 

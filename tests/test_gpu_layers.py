@@ -756,6 +756,31 @@ def test_conv3x3_maxpool2_argument_errors(part):
     part.sync()
 
 
+def test_conv_timeline_records_ordered_stamps_for_the_patch_and_tall_kernels(part):
+    def run(N, C, H, W, K, R, pad, tile):
+        x = torch.zeros((N, H, W, C), dtype=torch.bfloat16, device=DEV)
+        w = torch.zeros((K, R, R, C), dtype=torch.bfloat16, device=DEV)
+        b = torch.zeros(K, device=DEV)
+        y = torch.full((N, H, W, K), 3.0, dtype=torch.bfloat16, device=DEV)
+        torch.cuda.synchronize()
+        gpulet.set_conv_tile(tile)
+        try:
+            rows = gpulet.conv2d_timeline(x, w, b, y, N, C, H, W, K, R, R, 1, pad, True, stream=part.stream, warmup=3)
+        finally:
+            gpulet.set_conv_tile(-1)
+        assert bool((y == 0).all())                 # the stamped launch is a full launch of the layer
+        return rows
+    for tile, shape in ((7, (32, 256, 14, 14, 256, 3, 1)), (11, (4, 128, 56, 56, 128, 3, 1))):
+        rows = run(*shape, tile)
+        assert len(rows) == 8, tile
+        for r in rows:
+            assert r[7] == 0 and all(0 < a <= b for a, b in zip(r[:6], r[1:7])), (tile, r)   # points in program order
+            assert r[6] - r[0] < 20000, (tile, r)                                        # within 200 us (10 ns units)
+        starts = [r[0] for r in rows]
+        assert max(starts) - min(starts) < 1000          # the first workgroups of a launch start within 10 us of one another
+    assert run(2, 64, 8, 8, 64, 1, 0, -1) == []           # a 1x1 layer runs a kernel that records nothing
+
+
 # N, In, Out
 FC_CASES = [(32, 400, 120), (32, 120, 84), (32, 84, 10), (1, 2048, 1000), (8, 1024, 1000),
             (33, 72, 17), (5, 8, 3), (40, 4096, 1000), (16, 25088, 64), (2, 100, 7),
