@@ -327,10 +327,15 @@ gpulet_status gpulet_maxpool3_conv1x1_fwd(const void *x, const void *w, const fl
  *   2 position table complete      3 first input patch and weights in LDS
  *   4 end of the main loop         5 fp32 tile staged in LDS
  *   6 output stores issued         7 unused (0)
+ * (tiles 7 and 11 of gpulet_set_conv_tile).  The kernel that keeps the weights
+ * of 64 input channels in registers (tile 10) walks over many pixel tiles and
+ * records instead: 0 first instruction, 1 weights requested, and around its
+ * fourth pixel tile 2 arrival at the "patch landed" barrier, 3 patch there,
+ * 4 matrix instructions issued, 5 patch released, 6 output stores issued,
+ * 7 arrival at the next tile's barrier (7 - 2 = one tile period).
  * stamps: HOST array of 8 x 8 int64, row = workgroup; *workgroups = how many
  * rows were filled: 0 when the kernel that runs this layer records no stamps
- * (only the kernels that keep the input patch in LDS, tiles 7 and 11 of
- * gpulet_set_conv_tile, do).  Allocates and frees a 512-byte device buffer;
+ * (the gathering, streaming, stem and depthwise kernels).  Allocates and frees a 512-byte device buffer;
  * synchronises.  Errors as gpulet_conv2d_fwd; GPULET_EINVAL for NULL stamps or
  * workgroups or a negative warmup.
  */

@@ -299,8 +299,15 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
 // is added last, so results are bit-identical to the other tiles.  No residual
 // operand; K % 8 == 0 and a destination that allows aligned 16-byte stores.
 // ---------------------------------------------------------------------------
+// STAMP: the instance that records wall-clock stamps of its first workgroups (gpulet_conv2d_timeline):
+// 0 first instruction, 1 weights requested, and for the workgroup's fourth pixel tile 2 before B1,
+// 3 patch there (after B1), 4 matrix instructions issued, 5 patch released (after B2), 6 output
+// stores issued, 7 the fifth tile before B1 (tile period = 7 - 2).
+template <bool STAMP>
 __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, const int wgs_per_col, const int tiles_m,
                                                           const int die_aware) {
+    long long t_start = 0;
+    if constexpr (STAMP) t_start = wall_clock64();
     fetch_params(p);
     asm volatile("" ::"s"(p.pool2));   // requested with the rest of the argument block
     constexpr int BM = PATCH_BM, BN = 64, NPROD = 4, PMAX = PATCH_PMAX, NB = 2;  // NB patch buffers
@@ -340,6 +347,8 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    Stamps<STAMP> st(p, wave);
+    st.put(0, t_start);
     const int NP = p.N * p.P;
     const int Hp = p.H + 2 * p.pad;       // virtual rows per image
     const int pwt = p.tw + 2;             // patch width: block columns plus the two halo columns
@@ -422,6 +431,7 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
                 wf[i] = __builtin_bit_cast(bf16x8, raw);
             }
         }
+        st.at(1);
         unsigned char *tr = trs + wave * (64 * TROW);
         const unsigned limit = relu_limit(p.relu);
         const int kst = n0 + wx * 32 + (lane & 3) * 8;   // first of the 8 filters this lane stores
@@ -442,7 +452,10 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+            if (t == 3) st.at(2);
+            if (t == 4) st.at(7);
             __syncthreads();  // B1
+            if (t == 3) st.at(3);
             const __bf16 *pa = patch + (t % NB) * PATCH;
             // The fragments of depth step i+AHEAD are requested before the matrix instructions of
             // step i are issued, so LDS reads and matrix instructions overlap inside the wavefront.
@@ -471,7 +484,9 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
                     acc[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], f[i].a[h], acc[h], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (t == 3) st.at(4);
             __syncthreads();  // B2
+            if (t == 3) st.at(5);
 
             // Register v of a lane: filter 8*(v/4) + 4*(lane/32) + v%4 of the 32, pixel lane%32 (+32 h).
 #pragma unroll
@@ -524,6 +539,7 @@ __global__ __launch_bounds__(512) void conv3x3_c64_kernel(const ConvParams p, co
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
+            if (t == 3) st.at(6);
         }
     }
 }
@@ -611,8 +627,12 @@ hipError_t launch_c64(ConvParams p, int tw, int n_cu, bool pool2, hipStream_t st
     int wgs_per_col = std::max(1, std::min(tiles_m, n_cu / p.tiles_n));
     const int die_aware = wgs_per_col >= 8 ? 1 : 0;
     if (die_aware) wgs_per_col &= ~7;
-    hipLaunchKernelGGL(conv3x3_c64_kernel, dim3(static_cast<unsigned>(wgs_per_col * p.tiles_n)), dim3(512), 0, stream, p,
-                       wgs_per_col, tiles_m, die_aware);
+    if (p.stamps)
+        hipLaunchKernelGGL(conv3x3_c64_kernel<true>, dim3(static_cast<unsigned>(wgs_per_col * p.tiles_n)), dim3(512), 0, stream, p,
+                           wgs_per_col, tiles_m, die_aware);
+    else
+        hipLaunchKernelGGL(conv3x3_c64_kernel<false>, dim3(static_cast<unsigned>(wgs_per_col * p.tiles_n)), dim3(512), 0, stream, p,
+                           wgs_per_col, tiles_m, die_aware);
     return hipGetLastError();
 }
 

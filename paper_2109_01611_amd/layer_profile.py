@@ -150,6 +150,11 @@ STAMP_POINTS = ["first instruction", "argument block fetched", "position table c
                 "end of the main loop", "tile staged", "output stores issued"]
 
 
+STAMP_POINTS_C64 = ["first instruction", "weights requested", "tile 4: at the patch barrier", "tile 4: patch there",
+                    "tile 4: matrix instructions issued", "tile 4: patch released", "tile 4: output stores issued",
+                    "tile 5: at the patch barrier"]
+
+
 def timeline(args):
     """Prints where the first workgroups of a launch spend their time (``gpulet_conv2d_timeline``):
     microseconds from the earliest workgroup's first instruction to each point, next to the
@@ -178,7 +183,8 @@ def timeline(args):
                     return
                 t0 = min(r[0] for r in rows)
                 print("launch %d: microseconds since the earliest first instruction of workgroups 0..%d" % (rep, len(rows) - 1))
-                for i, name in enumerate(STAMP_POINTS):
+                names = STAMP_POINTS_C64 if rows[0][7] else STAMP_POINTS   # only the resident-weight kernel uses point 7
+                for i, name in enumerate(names):
                     print("  %-34s %s" % (name, " ".join("%6.2f" % ((r[i] - t0) / 100.0) for r in rows)))
         finally:
             gpulet.set_conv_tile(-1)
@@ -265,7 +271,7 @@ def main():
     r.add_argument("--reps", type=int, default=20)
     t = sub.add_parser("timeline")
     t.add_argument("--shape", default=",".join(str(v) for v in BENCH_SHAPE), help="N,C,H,W,K,R,stride,pad")
-    t.add_argument("--tile", type=int, default=-1, help="force a tile id (7 and 11 record stamps)")
+    t.add_argument("--tile", type=int, default=-1, help="force a tile id (7, 10 and 11 record stamps)")
     t.add_argument("--reps", type=int, default=3)
     m = sub.add_parser("mfma")
     m.add_argument("--data", default="both", choices=["both", "dense", "zeros"])

@@ -778,6 +778,10 @@ def test_conv_timeline_records_ordered_stamps_for_the_patch_and_tall_kernels(par
             assert r[6] - r[0] < 20000, (tile, r)                                        # within 200 us (10 ns units)
         starts = [r[0] for r in rows]
         assert max(starts) - min(starts) < 1000          # the first workgroups of a launch start within 10 us of one another
+    rows = run(16, 64, 112, 112, 64, 3, 1, 10)            # weights in registers: six pixel tiles per workgroup at least
+    assert len(rows) == 8
+    for r in rows:
+        assert all(0 < a <= b for a, b in zip(r[:6], r[1:7])) and r[2] < r[7] < r[2] + 2000, r
     assert run(2, 64, 8, 8, 64, 1, 0, -1) == []           # a 1x1 layer runs a kernel that records nothing
 
 
