@@ -67,3 +67,37 @@ def test_graph_matches_eager_on_every_replay(model, batch):
     want = oracle.run_model(model, params, x).reshape(batch, -1)
     whole, per_img = oracle.rel_err(got, want)
     assert max(whole, per_img) <= MODEL_TOL
+
+
+def test_graph_with_pools_in_the_convolutions_epilogue_matches_the_two_kernel_path():
+    # A captured forward pass whose convolution + max pool pairs run as one launch gives, on every
+    # replay, the bits of the eager pass that runs them as two kernels.
+    model = workloads.vgg16(width_div=2, in_hw=224, n_class=20)
+    batch = 32
+    params = workloads.parameters(model, 3)
+    dm = lowering.DeviceModel(model, params, DEV)
+    with gpulet.Partition(0, 100, 0) as p:
+        xd = dm.input_to_device(workloads.batch_input(model, batch, 3))
+        try:
+            gpulet.set_conv_pool_fusion(False)
+            ref, _ = dm.run(p, xd)
+            ref = ref.clone()
+            n_plain = p.kernel_launches()
+        finally:
+            gpulet.set_conv_pool_fusion(True)
+        y_eager, _ = dm.run(p, xd)
+        n_fused = p.kernel_launches() - n_plain
+        assert n_plain == dm.desc.n_layers and n_fused < n_plain      # some pairs do share a launch at this size
+        assert torch.equal(y_eager, ref)
+        ws, n = dm.workspace(batch)
+        y = dm.alloc_output(batch)
+        torch.cuda.synchronize()
+        with gpulet.ModelGraph(dm.desc, batch, p, xd, y, ws, n) as g:
+            for i in range(3):
+                y.fill_(-1.0)
+                torch.cuda.synchronize()
+                g.launch()
+                p.sync()
+                assert torch.equal(y, ref), i
+                dm.run(p, xd)                    # eager work between the replays
+                torch.cuda.synchronize()
