@@ -275,8 +275,10 @@ gpulet_status gpulet_conv1x1_maxpool3_fwd(const void *x, const void *w, const fl
  *   y = maxpool2x2(relu(b + conv3x3(x, w)))
  * The layer's own output is never written: the kernel's epilogue takes the
  * maximum of each 2x2 window of a tile's fp32 sums, then adds the bias, applies
- * the ReLU and rounds once (rounding and ReLU do not decrease, so the result
- * has the bits of gpulet_conv2d_fwd_ex followed by gpulet_pool).  x: N*H*W*C
+ * the ReLU and rounds once (rounding and ReLU do not decrease, so for finite
+ * sums the result has the bits of gpulet_conv2d_fwd_ex followed by gpulet_pool;
+ * a NaN sum loses against any number here, while the pool kernel orders NaN
+ * bit patterns like numbers).  x: N*H*W*C
  * bf16, w: K*3*3*C bf16, b: K fp32 or NULL, y: N*(H/2)*(W/2) pixels of
  * y_ch_stride channels (0 = K), filter k stored at channel y_ch_offset + k.
  * Device pointers owned by the caller; asynchronous on `stream`.
