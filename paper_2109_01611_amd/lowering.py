@@ -92,6 +92,40 @@ class DeviceModel:
                     alias[s] = (nd.dst, off, total)
                     off += chans[s]
                 chans[nd.dst] = total
+        # A convolution whose K is not a multiple of 8 makes its reader gather 2-byte elements one by one
+        # (the scalar-gather kernel: LeNet's 6 -> 16 layer took 13 us of the model's 41).  Where the
+        # tensor goes nowhere but through at most one max pool into one plain convolution, the
+        # producer gets zero filters up to the next multiple of 8 and the reader zero weights for
+        # them: the extra channels are relu(0) = 0 and add exact zeros, every sum keeps its bits.
+        self.k_pad = {}      # convolution name -> zero filters appended
+        c_extra = {}         # tensor -> zero channels it carries
+        all_readers = {}
+        for nd in nodes:
+            reads = list(nd.src) if nd.op == "concat" else [nd.src]
+            if nd.op == "conv" and nd.attr["residual"]:
+                reads.append(nd.attr["residual"])
+            for t in reads:
+                all_readers.setdefault(t, []).append(nd)
+        for nd in nodes:
+            if (nd.op != "conv" or nd.attr["K"] % 8 == 0 or nd.dst in alias or nd.dst == model.out or nd.attr["residual"]
+                    or len(all_readers.get(nd.src, [])) != 1):
+                continue
+            chain, t = [], nd.dst
+            rs = all_readers.get(t, [])
+            if len(rs) == 1 and rs[0].op == "maxpool" and rs[0].dst != model.out:
+                chain.append(rs[0])
+                t = rs[0].dst
+                rs = all_readers.get(t, [])
+            if not (len(rs) == 1 and rs[0].op == "conv" and rs[0].src == t and not rs[0].attr["residual"]
+                    and "in_slice" not in rs[0].attr):
+                continue
+            pad = (-nd.attr["K"]) % 8
+            self.k_pad[nd.name] = pad
+            c_extra[nd.dst] = pad
+            chans[nd.dst] += pad
+            for pool in chain:
+                c_extra[pool.dst] = pad
+                chans[pool.dst] += pad
         # With ``fuse_pools`` a 3x3 / stride 1 / pad 1 max pool whose only reader is a plain 1x1
         # convolution (the pooling branch of an inception block) runs inside that convolution's
         # kernel and the pooled tensor is never stored; ``fused_pools`` names the pool nodes that
@@ -195,14 +229,21 @@ class DeviceModel:
                     b = np.concatenate([np.asarray(params[n][1]) for n in a["parts"]], axis=0)
                 else:
                     w, b = params[nd.name]
-                C = a["C"]
+                C, K = a["C"], a["K"]
                 if nd.src == "x" and self.in_pad:
                     w = np.pad(np.asarray(w), ((0, 0), (0, self.in_pad), (0, 0), (0, 0)))
                     C += self.in_pad
+                if c_extra.get(nd.src):          # the input carries zero channels: zero weights for them
+                    w = np.pad(np.asarray(w), ((0, 0), (0, c_extra[nd.src]), (0, 0), (0, 0)))
+                    C += c_extra[nd.src]
+                if self.k_pad.get(nd.name):      # zero filters (and zero bias) up to a multiple of 8
+                    w = np.pad(np.asarray(w), ((0, self.k_pad[nd.name]), (0, 0), (0, 0), (0, 0)))
+                    b = np.pad(np.asarray(b), (0, self.k_pad[nd.name]))
+                    K += self.k_pad[nd.name]
                 wd = kcrs_to_krsc(w, self.device)
                 bd = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).to(self.device)
                 self._keep += [wd, bd]
-                L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, C, a["K"], a["k"], a["k"]
+                L.op, L.C, L.K, L.R, L.S = gpulet.OP_CONV, C, K, a["k"], a["k"]
                 L.stride, L.pad, L.relu = a["stride"], a["pad"], int(a["relu"])
                 L.pre_pool = a.get("pre_pool", 0)
                 L.group_next = a.get("group_next", 0)
