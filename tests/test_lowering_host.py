@@ -94,3 +94,35 @@ def test_buffers_released_inside_a_group_are_not_reused_by_its_members():
     with pytest.raises(gpulet.GpuletError) as e:
         gpulet.model_workspace_bytes(d, 2)
     assert e.value.status == gpulet.EINVAL
+
+
+def test_odd_filter_counts_are_padded_with_zero_filters_only_where_one_plain_convolution_reads_them():
+    ln = _lower(workloads.lenet5())
+    assert ln.k_pad == {"conv1": 2}
+    conv1, pool1, conv2 = ln.layers[0], ln.layers[1], ln.layers[2]
+    assert (conv1.C, conv1.K) == (8, 8) and pool1.C == 8 and (conv2.C, conv2.K) == (8, 16)
+    w1 = ln._keep[0].to(float).numpy()             # conv1: K R S C
+    assert w1.shape == (8, 5, 5, 8) and not w1[6:].any() and not w1[..., 1:].any() and w1[:6, ..., 0].any()
+    b1 = ln._keep[1].numpy()
+    assert b1.shape == (8,) and not b1[6:].any()
+    w2 = ln._keep[2].to(float).numpy()             # conv2: zero weights for the two zero channels
+    assert w2.shape == (16, 5, 5, 8) and not w2[..., 6:].any() and w2[..., :6].any()
+    assert gpulet.model_workspace_bytes(ln.desc, 4) > 0          # the planner accepts the widened table
+    # a filter count that is odd but feeds a concatenation, a residual sum, an FC layer or the output stays as it is
+    for m in (workloads.googlenet(width_div=4, in_hw=64, n_class=20, n_blocks=2), workloads.ssd_mobilenet(width_div=4, in_hw=96, n_class=5),
+              workloads.resnet50(width_div=4, in_hw=64, n_class=20, blocks=(1, 1, 1, 1))):
+        assert _lower(m).k_pad == {}
+
+
+def test_a_convolutions_input_outlives_the_max_pool_behind_it():
+    # The library may run a convolution and the 2x2 / stride 2 max pool behind it as one launch that
+    # reads the convolution's input while it writes the pool's buffer: the two must never share a buffer.
+    for model in (workloads.vgg16(width_div=8, in_hw=64, n_class=10), workloads.lenet5()):
+        dm = _lower(model)
+        layers = list(dm.layers)
+        pairs = 0
+        for a, b in zip(layers, layers[1:]):
+            if a.op == gpulet.OP_CONV and b.op == gpulet.OP_POOL and b.in_buf == a.out_buf and (b.R, b.stride, b.pad) == (2, 2, 0):
+                pairs += 1
+                assert b.out_buf != a.in_buf, (a.in_buf, a.out_buf, b.out_buf)
+        assert pairs == (5 if model.name.startswith("vgg") else 2)
