@@ -200,6 +200,18 @@ Choice choose_kernel(const ConvParams &p, bool vec, const LaunchCtx &ctx) {
             }
         }
     }
+    // Filters larger than 1x1 on very few tiles: the two producers of the 64x64 tile, which locate every
+    // tap of their pixels themselves, are what such a launch waits for; 64x128 has four and half as
+    // many rows per producer.  Measured on MI355X with at most an eighth as many 64x64 tiles as CUs
+    // (3x3 stride 2 at batch 1, SSD's last feature maps): 64x128 is 7-10 % faster; from 56 tiles on
+    // 256 CUs on it is the other way round or even.
+    if (forced < 0 && best == 3 && best_split == 1 && p.R * p.S > 1) {
+        const long long tiles3 = 1LL * ((p.M + 63) / 64) * ((p.K + 63) / 64);
+        if (8 * tiles3 <= n_cu) {
+            best = 2;
+            best_cost = static_cast<double>(64 * 128) / 0.72;   // one round of 64x128 at its table efficiency
+        }
+    }
     if (forced >= 0 && forced < GPULET_CONV_TILES) {
         best = forced;
         best_split = 1;
