@@ -63,7 +63,10 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     constexpr int LDS_ELEMS = MAIN > BM * LDT * 2 ? MAIN : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 lds[LDS_ELEMS];
     // Per patch position: byte offset in x of its first channel (block 0), or OOB, with the
-    // position's swizzle key in the three low bits.  Locating a position costs two divisions;
+    // position's swizzle key in bits 4-6 (a pixel's channels start on a multiple of 128 bytes, so
+    // the lane that fills physical chunk q gets its offset with one XOR by q << 4; an entry
+    // with the OOB bit keeps it whatever is XORed or added below 2^31, and the hardware
+    // answers such an offset with zeros).  Locating a position costs two divisions;
     // the 256 consumer threads compute one position each while the producers already fetch
     // weights, instead of every producer lane locating eight (which kept the first patch
     // transfer waiting for 0.9 us on a 10 us kernel).
@@ -83,7 +86,10 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
     const int tm = fdiv(tile, p.d_tiles_n), tn = tile - tm * p.tiles_n;
     const int tl = fdiv(tm, p.d_ncb), cb = tm - tl * p.n_cb;
     const int l0 = tl * BM, n0 = tn * BN, q0 = cb * p.tw;
-    const BiasRegs bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);
+    // The bias is requested only once a wavefront's first transfers (or its table entry) are on
+    // their way: a launch starts with cold instruction caches, and every instruction in front
+    // of the first transfer delays it by its share of the fetch misses.
+    BiasRegs bias_regs;
     const int NP = p.N * p.P;
     const int Hp = p.H + 2 * p.pad;       // virtual rows per image
     const int pwt = p.tw + 2;             // patch width: block columns plus the two halo columns
@@ -111,14 +117,23 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
         const i32x4 rw = make_rsrc(p.w, p.w_bytes);
 
         // Weight transfer i fills rows rg*8 .. +8 of tap s of the stage, q = i*NPROD + pw = s*RG + rg.
+        // NPROD divides RG, so s = (i*NPROD) / RG and rg = (i*NPROD) % RG + pw: the tap and the
+        // row group's first part are known at compile time, and with NPROD even the chunk a lane
+        // fills, (lane & 7) ^ ((row >> 1) & 7), is the same for every i.  One offset is computed
+        // and the others follow by adding a constant times C (a few instructions in front of
+        // the first transfer instead of a dozen per transfer).
+        static_assert(RG % NPROD == 0 && NPROD % 2 == 0, "weight transfers: one chunk per lane");
         unsigned b_off[BOPS];
+        {
+            const int row0 = pw * 8 + (lane >> 3);
+            const int cc = (lane & 7) ^ ((row0 >> 1) & 7);
+            const unsigned first = static_cast<unsigned>((((n0 + row0) * 9) * p.C + cc * CHUNK) * 2);
+            const int left = p.K - n0 - row0;   // rows from this lane's first one to the end of the filters
 #pragma unroll
-        for (int i = 0; i < BOPS; ++i) {
-            const int q = i * NPROD + pw;
-            const int s = q / RG, row = (q - s * RG) * 8 + (lane >> 3);
-            const int cc = (lane & 7) ^ ((row >> 1) & 7);
-            const int k = n0 + row;
-            b_off[i] = k < p.K ? static_cast<unsigned>(((k * 9 + s) * p.C + cc * CHUNK) * 2) : OOB;
+            for (int i = 0; i < BOPS; ++i) {
+                const int s = (i * NPROD) / RG, rg = (i * NPROD) % RG;
+                b_off[i] = rg * 8 < left ? first + static_cast<unsigned>((rg * 8 * 9 + s) * 2) * p.C : OOB;
+            }
         }
 
         unsigned a_off[POPS];
@@ -126,10 +141,8 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             const unsigned base = lds_addr(patch + (blk & 1) * PATCH) + pw * 1024;
             const unsigned add = static_cast<unsigned>(blk * BK * 2);
 #pragma unroll
-            for (int j = half * (POPS / 2); j < (half + 1) * (POPS / 2); ++j) {
-                const unsigned off = (blk < nblk && a_off[j] != OOB) ? a_off[j] + add : OOB;
-                dma16(rx, base + j * NPROD * 1024, off);
-            }
+            for (int j = half * (POPS / 2); j < (half + 1) * (POPS / 2); ++j)
+                dma16(rx, base + j * NPROD * 1024, blk < nblk ? a_off[j] + add : OOB);
         };
         // Weights of step t = 3*blk + r into ring stage `stage`.
         auto issue_weights = [&](int blk, int r, int stage) {
@@ -137,8 +150,7 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
             const unsigned add = static_cast<unsigned>((r * 3 * p.C + blk * BK) * 2);
 #pragma unroll
             for (int i = 0; i < BOPS; ++i) {
-                const unsigned off = (blk < nblk && b_off[i] != OOB) ? b_off[i] + add : OOB;
-                dma16(rw, base + i * NPROD * 1024, off);
+                dma16(rw, base + i * NPROD * 1024, blk < nblk ? b_off[i] + add : OOB);   // OOB + add stays out of bounds
             }
         };
 
@@ -147,13 +159,10 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
         // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8;
         // this lane fills physical chunk lane&7 of one of them.
 #pragma unroll
-        for (int j = 0; j < POPS; ++j) {
-            const unsigned e = ptab[(j * NPROD + pw) * 8 + (lane >> 3)];
-            const unsigned cc = (lane & 7u) ^ (e & 7u);
-            a_off[j] = (e & OOB) ? OOB : (e & ~7u) + cc * (CHUNK * 2);
-        }
+        for (int j = 0; j < POPS; ++j) a_off[j] = ptab[(j * NPROD + pw) * 8 + (lane >> 3)] ^ ((lane & 7u) << 4);
         issue_patch(0, 0);
         issue_patch(0, 1);
+        bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);   // two plain loads: complete in order with the transfers
         issue_weights(0, 1, 1);   // not needed by the first step: behind the patch
         for (int blk = 0; blk < nblk; ++blk) {
             // step 3*blk: its weights were followed by those of step 3*blk+1 only
@@ -187,9 +196,10 @@ __global__ __launch_bounds__((4 + NPROD) * 64) void conv3x3_patch_kernel(const C
                 if (n < p.N && (unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
                     e = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C) * 2);
             }
-            ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr));
+            ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr) << 4);
         }
         __syncthreads();   // the table is complete (the producers wait here too)
+        bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);
         st.at(2);
 #pragma unroll
         for (int j = 0; j < NT; ++j)

@@ -190,8 +190,9 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     constexpr int LDS_ELEMS = MAIN > BM * LDT * 2 ? MAIN : BM * LDT * 2;
     __shared__ __attribute__((aligned(1024))) __bf16 lds[LDS_ELEMS];
     // Per patch position: byte offset in x of its first channel (block 0), or OOB, with the
-    // position's swizzle key in the three low bits; filled by the consumer threads (one position
-    // each) while the producers already fetch weights.
+    // position's swizzle key in bits 4-6 (as in the patch kernel: one XOR by the lane's chunk
+    // gives its offset, and the OOB bit survives it); filled by the consumer threads (one
+    // position each) while the producers already fetch weights.
     __shared__ unsigned ptab[PMAX];
     static_assert(PMAX <= NCONS * 64, "one table entry per consumer thread");
     __bf16 *const wring = lds;
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
     const int n = fdiv(tm, p.d_hp), ti = tm - n * p.tiles_img;
     const int tyi = fdiv(ti, p.d_ncb), txi = ti - tyi * p.n_cb;
     const int ty0 = tyi * p.th, tx0 = txi * p.tw, n0 = tn * BN;
-    const BiasRegs bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);
+    BiasRegs bias_regs;   // requested once a wavefront's first transfers (or its table entry) are on their way
     const int pwt = p.tw + 2;                      // patch width: tile columns plus the two halo columns
     const int npix = p.th * p.tw;                  // tile rows that are pixels
     const int npos = (p.th + 2) * pwt;             // patch positions in use (<= PMAX)
@@ -230,13 +231,18 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
 
         unsigned a_off[POPS];
         // Weight transfer i fills rows (i*NPROD + pw)*8 .. +8 of the stage.
+        // Rows i*NPROD*8 further down change nothing in the chunk a lane fills (NPROD * 4 is a
+        // multiple of 8): one offset is computed, the others add a constant times C.
+        static_assert((NPROD * 4) % 8 == 0, "weight transfers: one chunk per lane");
         unsigned b_off[WOPS];
+        {
+            const int row0 = pw * 8 + (lane >> 3);
+            const int cc = (lane & 7) ^ ((row0 >> 1) & 7);
+            const unsigned first = static_cast<unsigned>((((n0 + row0) * 9) * p.C + cc * CHUNK) * 2);
+            const int left = p.K - n0 - row0;   // rows from this lane's first one to the end of the filters
 #pragma unroll
-        for (int i = 0; i < WOPS; ++i) {
-            const int row = (i * NPROD + pw) * 8 + (lane >> 3);
-            const int cc = (lane & 7) ^ ((row >> 1) & 7);
-            const int k = n0 + row;
-            b_off[i] = k < p.K ? static_cast<unsigned>(((k * 9) * p.C + cc * CHUNK) * 2) : OOB;
+            for (int i = 0; i < WOPS; ++i)
+                b_off[i] = i * NPROD * 8 < left ? first + static_cast<unsigned>(i * NPROD * 8 * 9 * 2) * p.C : OOB;
         }
 
         // Pieces first .. first+count-1 of the patch of channel block blk.
@@ -245,8 +251,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
             const unsigned add = static_cast<unsigned>(blk * BK * 2);
 #pragma unroll
             for (int j = first; j < first + count; ++j) {
-                const unsigned off = (blk < nblk && a_off[j] != OOB) ? a_off[j] + add : OOB;
-                dma16(rx, base + j * NPROD * 1024, off);
+                dma16(rx, base + j * NPROD * 1024, blk < nblk ? a_off[j] + add : OOB);   // OOB + add stays out of bounds
             }
         };
         // Weights of tap `tap` of block blk, tap counter g, into stage g % NS.
@@ -255,8 +260,7 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
             const unsigned add = static_cast<unsigned>((tap * p.C + blk * BK) * 2);
 #pragma unroll
             for (int i = 0; i < WOPS; ++i) {
-                const unsigned off = (blk < nblk && b_off[i] != OOB) ? b_off[i] + add : OOB;
-                dma16(rw, base + i * NPROD * 1024, off);
+                dma16(rw, base + i * NPROD * 1024, blk < nblk ? b_off[i] + add : OOB);
             }
         };
 
@@ -266,12 +270,9 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
         // Patch transfer j of this wavefront fills positions (j*NPROD + pw)*8 .. +8; this lane
         // fills physical chunk lane&7 of one of them.
 #pragma unroll
-        for (int j = 0; j < POPS; ++j) {
-            const unsigned e = ptab[(j * NPROD + pw) * 8 + (lane >> 3)];
-            const unsigned cc = (lane & 7u) ^ (e & 7u);
-            a_off[j] = (e & OOB) ? OOB : (e & ~7u) + cc * (CHUNK * 2);
-        }
+        for (int j = 0; j < POPS; ++j) a_off[j] = ptab[(j * NPROD + pw) * 8 + (lane >> 3)] ^ ((lane & 7u) << 4);
         issue_patch(0, 0, POPS);
+        bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);   // plain loads complete in order with the transfers
         issue_weights(0, 2, 2);
         int g = 0;
         for (int blk = 0; blk < nblk; ++blk) {
@@ -309,11 +310,12 @@ __global__ __launch_bounds__(768) void conv3x3_tall_kernel(const ConvParams p) {
                     if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W)
                         e = static_cast<unsigned>((((n * p.H + h) * p.W + w) * p.C) * 2);
                 }
-                ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr));
+                ptab[pos] = e | static_cast<unsigned>(patch_key(pos, vr) << 4);
             }
         }
         __syncthreads();   // the table is complete (the producers wait here too)
         st.at(2);
+        bias_regs = load_bias<BN, (NCONS + NPROD) * 64>(p, n0);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
